@@ -1,0 +1,150 @@
+/*
+ * zipccl.h -- C ABI of libzipccl.so: lossless exponent coding of bf16 / fp32 communication
+ * tensors on one MI355X (gfx950), after "ZipCCL" section 4.
+ *
+ * Conventions (all entry points):
+ *   - `d_` pointers are DEVICE pointers, everything else is a HOST pointer.
+ *   - The caller owns every buffer.  The library allocates nothing, frees nothing and keeps
+ *     no pointer past the call.  Host arrays are read before the call returns.
+ *   - compress / decompress are asynchronous on `stream` (a hipStream_t passed as void*,
+ *     NULL = the default stream); they never synchronise with the host.
+ *   - The return value covers argument and launch errors only.  Data-dependent problems
+ *     (a corrupt stream) are reported through a device status word.
+ *   - The device of the calling thread's current HIP context is used.
+ *
+ * Compressed layout, little-endian.  The output holds one SLOT per chunk; slot c starts at
+ * slot_off[c] (a multiple of 128, known before compression from the element counts alone:
+ * section 4.2.1's 128-byte peer padding), so a collective can send and decode every peer
+ * slice on its own.  With pad(x) = x rounded up to 128 and a chunk of n elements:
+ *
+ *   HDR  128 B          "ZPCL", version u32 = 1, dtype u32, G u32, n u64, n_esc u64,
+ *                       chunk_bytes u64, dec[8], zero fill
+ *   SM   pad(n)         byte i = sign << 7 | 7 mantissa bits of the high 16-bit word
+ *                       (section 4: sign and mantissa kept verbatim at a fixed stride)
+ *   LO   pad(2n)        fp32 only: u16 i = low 16 bits of the word
+ *   P0,P1,P2  pad(ceil(n/8)) each
+ *                       plane k, byte i >> 3, bit i & 7 = bit k of code_i (section 4.2.1:
+ *                       the 3-bit code stored as three 1-bit arrays)
+ *   IDX  pad(4 ceil(n/G))  u32 g = zero-points among elements [0, g G) of this chunk
+ *                       (section 4.2.3's stored prefix count; G = ZIPCCL_GROUP = 512)
+ *   ESC  pad(n_esc) used, pad(n) reserved
+ *                       byte j = raw exponent of the j-th zero-point, in element order
+ *
+ *   code_i = E - dec[1] + 1 when dec[1] <= E <= dec[7], else 0 (a "zero-point", section 4).
+ *   Padding, and plane bits / IDX entries past n, are zero.
+ *   chunk_bytes = HDR..IDX (the "static part", size independent of the data) + pad(n_esc)
+ *   (the "dynamic part") = what a collective transmits for the chunk.
+ */
+#ifndef ZIPCCL_H
+#define ZIPCCL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ZIPCCL_GROUP 512u        /* elements per IDX entry: one wave64 x 8 values per lane */
+#define ZIPCCL_ALIGN 128u        /* alignment of every slot and section */
+#define ZIPCCL_MAX_CHUNK_ELEMS 0xFFFFFFFFull /* IDX entries are u32 */
+
+typedef enum { ZIPCCL_BF16 = 0, ZIPCCL_FP32 = 1 } zipccl_dtype_t;
+
+typedef enum {
+    ZIPCCL_OK = 0,
+    ZIPCCL_ERR_INVALID_ARG = 1,       /* null pointer, misaligned buffer, bad chunk split, bad table */
+    ZIPCCL_ERR_UNSUPPORTED_DTYPE = 2,
+    ZIPCCL_ERR_BUFFER_TOO_SMALL = 3,  /* out_capacity / workspace_bytes / comp_capacity too small */
+    ZIPCCL_ERR_CORRUPT = 4,           /* device status word only: header or index inconsistent */
+    ZIPCCL_ERR_DEVICE = 5             /* a HIP call failed (launch error) */
+} zipccl_status_t;
+
+/* dec[0] is unused (code 0 flags a zero-point); dec[1..7] are the biased exponents of codes
+ * 1..7 and must be consecutive ascending values (the Gaussian model always yields a window). */
+typedef struct { uint8_t dec[8]; } zipccl_table_t;
+
+/*
+ * Code-table builder (section 4.1).  Host only, pure.  For a zero-mean Gaussian of standard
+ * deviation sigma, Eq.5 gives the continuous optimum of the window base
+ * x_opt = log2(sigma) + 0.5 log2(14 ln2 / 16383); the better of floor/ceil(x_opt) under the
+ * coverage of Eq.2 is taken (lower on a tie) and clamped so that dec[1] = x + 127 lies in
+ * [1, 248].  The same table serves bf16 and fp32 (same exponent field).
+ * Errors: sigma <= 0, NaN or Inf, or out == NULL -> ZIPCCL_ERR_INVALID_ARG.
+ */
+zipccl_status_t zipccl_build_table(double sigma, zipccl_dtype_t dt, zipccl_table_t* out);
+
+/*
+ * Chunk split used by every call below: chunk_elems (host, n_chunks entries) gives the
+ * element count of each peer chunk, in order, and must sum to n_elems; NULL means an equal
+ * split and requires n_elems % n_chunks == 0.  A chunk may be empty (header-only slot).
+ * Each chunk holds at most ZIPCCL_MAX_CHUNK_ELEMS elements.
+ */
+
+/* Bytes needed for the compressed buffer in the worst case (every value a zero-point) =
+ * slot_off[n_chunks].  Returns 0 on invalid arguments. */
+size_t zipccl_max_compressed_size(size_t n_elems, zipccl_dtype_t dt, uint32_t n_chunks,
+                                  const uint64_t* chunk_elems);
+
+/* slot_off (host, n_chunks + 1 entries): byte offset of every slot, and the total. */
+zipccl_status_t zipccl_chunk_slot_offsets(size_t n_elems, zipccl_dtype_t dt, uint32_t n_chunks,
+                                          const uint64_t* chunk_elems, uint64_t* slot_off);
+
+/* Bytes of device scratch zipccl_compress needs for this split (tile scan state of the
+ * chunk-wide zero-point prefix, section 4.2.3).  Returns 0 on invalid arguments. */
+size_t zipccl_compress_workspace_size(size_t n_elems, zipccl_dtype_t dt, uint32_t n_chunks,
+                                      const uint64_t* chunk_elems);
+
+/*
+ * Compress (section 4, second paragraph; kernel steps of section 4.2).
+ *   d_in            device, n_elems values of dtype dt, aligned to the element size
+ *                   (16-byte aligned chunk starts take the vector-load path)
+ *   table           host, from zipccl_build_table
+ *   d_out           device, 128-byte aligned, out_capacity >= zipccl_max_compressed_size(...)
+ *   d_chunk_bytes   device, n_chunks u64, may be NULL: bytes to transmit for each chunk
+ *   d_workspace     device, 8-byte aligned, workspace_bytes >= zipccl_compress_workspace_size(...);
+ *                   contents are overwritten; after the call has completed on the stream its
+ *                   first u32 is 0 on success (nonzero: the scan's bounded wait gave up)
+ * Every byte of [slot_off[c], slot_off[c] + chunk_bytes[c]) is written; the rest of a slot is
+ * left untouched.  Calls on different streams need different workspaces.
+ */
+zipccl_status_t zipccl_compress(const void* d_in, size_t n_elems, zipccl_dtype_t dt,
+                                uint32_t n_chunks, const uint64_t* chunk_elems,
+                                const zipccl_table_t* table,
+                                void* d_out, size_t out_capacity, uint64_t* d_chunk_bytes,
+                                void* d_workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Decompress (section 4, third paragraph): code != 0 -> exponent from the table in the chunk
+ * header, code == 0 -> next exponent of the zero-point list, found through IDX; recombined
+ * with the stored sign and mantissa bits.
+ *   d_comp          device, 128-byte aligned; slots at the a-priori offsets for this split
+ *                   (a peer decodes one received slice with n_chunks = 1); comp_capacity is
+ *                   the number of readable bytes and must cover the static part of every slot;
+ *                   the kernel checks that each slot's zero-point list also fits
+ *   d_out           device, n_elems values of dtype dt, aligned to the element size
+ *   d_status        device u32, may be NULL: OR-ed with ZIPCCL_ERR_CORRUPT if a header does not
+ *                   match (magic, version, dtype, G, n, table) or an index leaves the list;
+ *                   the caller zeroes it.  Values of a corrupt chunk are unspecified, but no
+ *                   read or write leaves the caller's buffers.
+ */
+zipccl_status_t zipccl_decompress(const void* d_comp, size_t comp_capacity,
+                                  void* d_out, size_t n_elems, zipccl_dtype_t dt,
+                                  uint32_t n_chunks, const uint64_t* chunk_elems,
+                                  uint32_t* d_status, void* stream);
+
+const char* zipccl_status_string(zipccl_status_t s);
+
+/*
+ * Diagnostic switch, process-wide: path = 0 selects the single fused compress kernel (the
+ * default; chunk-wide zero-point prefix by look-back across tiles), path = 1 the three-kernel
+ * form (count, scan, emit) that reads the input twice and never waits on another workgroup.
+ * Both produce identical bytes.  The environment variable ZIPCCL_COMPRESS_PATH=3pass sets the
+ * initial value to 1.  Returns the previous value; any other argument only queries.
+ */
+int zipccl_debug_compress_path(int path);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ZIPCCL_H */

@@ -1,0 +1,277 @@
+/*
+ * Host side of libzipccl.so: the code-table builder (paper section 4.1), size / offset
+ * arithmetic for the chunked layout (section 4.2.1) and argument checking + launch logic
+ * of compress / decompress.  No device memory is allocated here.
+ */
+#include <atomic>
+#include <cmath>
+#include <cstdint>
+#include <cstdlib>
+#include <cstring>
+#include <vector>
+
+#include "zipccl_internal.h"
+
+using namespace zipccl;
+
+namespace {
+
+bool dtype_ok(int dt) { return dt == ZIPCCL_BF16 || dt == ZIPCCL_FP32; }
+
+/* Eq.2 of section 4.1: P(|w| in [2^x, 2^(x+7))) for w ~ N(0, sigma^2). */
+double window_coverage(double sigma, int x)
+{
+    const double s = sigma * std::sqrt(2.0);
+    return std::erf(std::ldexp(1.0, x + 7) / s) - std::erf(std::ldexp(1.0, x) / s);
+}
+
+/* Resolve the chunk split into explicit element counts; false if it is not a valid split. */
+bool resolve_split(size_t n_elems, uint32_t n_chunks, const uint64_t* chunk_elems, std::vector<uint64_t>& ce)
+{
+    if (n_chunks == 0) return false;
+    ce.resize(n_chunks);
+    if (!chunk_elems) {
+        if (n_elems % n_chunks) return false;
+        for (uint32_t c = 0; c < n_chunks; ++c) ce[c] = n_elems / n_chunks;
+    } else {
+        uint64_t total = 0;
+        for (uint32_t c = 0; c < n_chunks; ++c) {
+            ce[c] = chunk_elems[c];
+            if (total + ce[c] < total) return false;
+            total += ce[c];
+        }
+        if (total != n_elems) return false;
+    }
+    for (uint32_t c = 0; c < n_chunks; ++c)
+        if (ce[c] > ZIPCCL_MAX_CHUNK_ELEMS) return false;
+    return true;
+}
+
+bool table_ok(const zipccl_table_t* t)
+{
+    if (!t) return false;
+    if (t->dec[1] > 249) return false;
+    for (int k = 2; k <= 7; ++k)
+        if (t->dec[k] != t->dec[1] + k - 1) return false;
+    return true;
+}
+
+/* Fill the by-value chunk table of one launch covering chunks [c0, c0 + nb). */
+uint32_t fill_tab(ChunkTab& tab, const std::vector<uint64_t>& ce, const std::vector<uint64_t>& slot_off,
+                  uint32_t c0, uint32_t nb, int dt)
+{
+    tab.n_chunks = nb;
+    uint64_t eoff = 0;
+    uint32_t tiles = 0;
+    for (uint32_t i = 0; i < nb; ++i) {
+        tab.tile_start[i] = tiles;
+        tab.elem_off[i] = eoff;
+        tab.slot_off[i] = slot_off[c0 + i] - slot_off[c0];
+        tiles += (uint32_t)tiles_of(ce[c0 + i]);
+        eoff += ce[c0 + i];
+    }
+    tab.tile_start[nb] = tiles;
+    tab.elem_off[nb] = eoff;
+    tab.slot_off[nb] = slot_off[c0 + nb] - slot_off[c0];
+    for (uint32_t i = nb + 1; i <= kMaxBatch; ++i) {
+        tab.tile_start[i] = tiles;
+        tab.elem_off[i] = eoff;
+        tab.slot_off[i] = tab.slot_off[nb];
+    }
+    (void)dt;
+    return tiles;
+}
+
+/* Total tiles of the call; 0 if it exceeds what one call supports. */
+uint64_t total_tiles(const std::vector<uint64_t>& ce)
+{
+    uint64_t t = 0;
+    for (uint64_t n : ce) t += tiles_of(n);
+    return t;
+}
+
+/* 0 = fused single kernel, 1 = three kernels (count, scan, emit); see zipccl_debug_compress_path */
+std::atomic<int>& compress_path()
+{
+    static std::atomic<int> path([] {
+        const char* e = std::getenv("ZIPCCL_COMPRESS_PATH");
+        return (e && std::strcmp(e, "3pass") == 0) ? 1 : 0;
+    }());
+    return path;
+}
+
+} // namespace
+
+extern "C" {
+
+zipccl_status_t zipccl_build_table(double sigma, zipccl_dtype_t dt, zipccl_table_t* out)
+{
+    if (!dtype_ok(dt)) return ZIPCCL_ERR_UNSUPPORTED_DTYPE;
+    if (!out || !(sigma > 0.0) || std::isinf(sigma)) return ZIPCCL_ERR_INVALID_ARG;
+    /* Eq.5: continuous optimum of the window base */
+    const double x_opt = std::log2(sigma) + 0.5 * std::log2(14.0 * std::log(2.0) / 16383.0);
+    const int lo = (int)std::floor(x_opt), hi = (int)std::ceil(x_opt);
+    const int x = window_coverage(sigma, hi) > window_coverage(sigma, lo) ? hi : lo;
+    int e0 = x + 127;
+    e0 = e0 < 1 ? 1 : (e0 > 248 ? 248 : e0);
+    out->dec[0] = 0;
+    for (int k = 1; k <= 7; ++k) out->dec[k] = (uint8_t)(e0 + k - 1);
+    return ZIPCCL_OK;
+}
+
+zipccl_status_t zipccl_chunk_slot_offsets(size_t n_elems, zipccl_dtype_t dt, uint32_t n_chunks,
+                                          const uint64_t* chunk_elems, uint64_t* slot_off)
+{
+    if (!dtype_ok(dt)) return ZIPCCL_ERR_UNSUPPORTED_DTYPE;
+    std::vector<uint64_t> ce;
+    if (!slot_off || !resolve_split(n_elems, n_chunks, chunk_elems, ce)) return ZIPCCL_ERR_INVALID_ARG;
+    uint64_t off = 0;
+    for (uint32_t c = 0; c < n_chunks; ++c) {
+        slot_off[c] = off;
+        off += slot_layout(ce[c], dt).cap;
+    }
+    slot_off[n_chunks] = off;
+    return ZIPCCL_OK;
+}
+
+size_t zipccl_max_compressed_size(size_t n_elems, zipccl_dtype_t dt, uint32_t n_chunks,
+                                  const uint64_t* chunk_elems)
+{
+    if (!dtype_ok(dt)) return 0;
+    std::vector<uint64_t> ce;
+    if (!resolve_split(n_elems, n_chunks, chunk_elems, ce)) return 0;
+    uint64_t off = 0;
+    for (uint64_t n : ce) off += slot_layout(n, dt).cap;
+    return (size_t)off;
+}
+
+size_t zipccl_compress_workspace_size(size_t n_elems, zipccl_dtype_t dt, uint32_t n_chunks,
+                                      const uint64_t* chunk_elems)
+{
+    if (!dtype_ok(dt)) return 0;
+    std::vector<uint64_t> ce;
+    if (!resolve_split(n_elems, n_chunks, chunk_elems, ce)) return 0;
+    return (size_t)(kWorkspaceHeader + 8 * total_tiles(ce));
+}
+
+zipccl_status_t zipccl_compress(const void* d_in, size_t n_elems, zipccl_dtype_t dt,
+                                uint32_t n_chunks, const uint64_t* chunk_elems,
+                                const zipccl_table_t* table,
+                                void* d_out, size_t out_capacity, uint64_t* d_chunk_bytes,
+                                void* d_workspace, size_t workspace_bytes, void* stream)
+{
+    if (!dtype_ok(dt)) return ZIPCCL_ERR_UNSUPPORTED_DTYPE;
+    std::vector<uint64_t> ce;
+    if (!resolve_split(n_elems, n_chunks, chunk_elems, ce)) return ZIPCCL_ERR_INVALID_ARG;
+    if (!table_ok(table) || !d_out || !d_workspace || (!d_in && n_elems)) return ZIPCCL_ERR_INVALID_ARG;
+    const uint32_t es = elem_size(dt);
+    if ((reinterpret_cast<uintptr_t>(d_in) % es) || (reinterpret_cast<uintptr_t>(d_out) % ZIPCCL_ALIGN) ||
+        (reinterpret_cast<uintptr_t>(d_workspace) % 8) || (reinterpret_cast<uintptr_t>(d_chunk_bytes) % 8))
+        return ZIPCCL_ERR_INVALID_ARG;
+
+    std::vector<uint64_t> slot_off(n_chunks + 1);
+    uint64_t off = 0;
+    for (uint32_t c = 0; c < n_chunks; ++c) {
+        slot_off[c] = off;
+        off += slot_layout(ce[c], dt).cap;
+    }
+    slot_off[n_chunks] = off;
+    if (off > out_capacity) return ZIPCCL_ERR_BUFFER_TOO_SMALL;
+    const uint64_t tiles = total_tiles(ce);
+    if (tiles > 0x7FFFFFFFull) return ZIPCCL_ERR_INVALID_ARG;
+    const uint64_t ws_need = kWorkspaceHeader + 8 * tiles;
+    if (ws_need > workspace_bytes) return ZIPCCL_ERR_BUFFER_TOO_SMALL;
+
+    /* tile states must start as "not published"; the status word as 0 */
+    if (launch_fill_zero(d_workspace, ws_need, stream) != 0) return ZIPCCL_ERR_DEVICE;
+
+    const int mode = compress_path().load() == 1 ? (int)kModeEmit : (int)kModeFused;
+    CompressArgs a;
+    std::memset(&a, 0, sizeof a);
+    a.err = reinterpret_cast<uint32_t*>(d_workspace);
+    a.e0 = table->dec[1];
+    std::memcpy(&a.dec_lo, table->dec, 4);
+    std::memcpy(&a.dec_hi, table->dec + 4, 4);
+    uint64_t elem_base = 0, tile_base = 0;
+    for (uint32_t c0 = 0; c0 < n_chunks; c0 += kMaxBatch) {
+        const uint32_t nb = (n_chunks - c0) < kMaxBatch ? (n_chunks - c0) : kMaxBatch;
+        const uint32_t nt = fill_tab(a.tab, ce, slot_off, c0, nb, dt);
+        a.in = static_cast<const uint8_t*>(d_in) + elem_base * es;
+        a.out = static_cast<uint8_t*>(d_out) + slot_off[c0];
+        a.chunk_bytes = d_chunk_bytes ? d_chunk_bytes + c0 : nullptr;
+        a.tile_state = reinterpret_cast<uint64_t*>(static_cast<uint8_t*>(d_workspace) + kWorkspaceHeader) + tile_base;
+        if (mode == kModeFused) {
+            if (launch_compress(dt, kModeFused, a, nt, stream) != 0) return ZIPCCL_ERR_DEVICE;
+        } else {
+            if (launch_compress(dt, kModeCount, a, nt, stream) != 0) return ZIPCCL_ERR_DEVICE;
+            if (launch_tile_scan(a, stream) != 0) return ZIPCCL_ERR_DEVICE;
+            if (launch_compress(dt, kModeEmit, a, nt, stream) != 0) return ZIPCCL_ERR_DEVICE;
+        }
+        elem_base += a.tab.elem_off[nb];
+        tile_base += nt;
+    }
+    return ZIPCCL_OK;
+}
+
+zipccl_status_t zipccl_decompress(const void* d_comp, size_t comp_capacity,
+                                  void* d_out, size_t n_elems, zipccl_dtype_t dt,
+                                  uint32_t n_chunks, const uint64_t* chunk_elems,
+                                  uint32_t* d_status, void* stream)
+{
+    if (!dtype_ok(dt)) return ZIPCCL_ERR_UNSUPPORTED_DTYPE;
+    std::vector<uint64_t> ce;
+    if (!resolve_split(n_elems, n_chunks, chunk_elems, ce)) return ZIPCCL_ERR_INVALID_ARG;
+    if (!d_comp || (!d_out && n_elems)) return ZIPCCL_ERR_INVALID_ARG;
+    const uint32_t es = elem_size(dt);
+    if ((reinterpret_cast<uintptr_t>(d_comp) % ZIPCCL_ALIGN) || (reinterpret_cast<uintptr_t>(d_out) % es) ||
+        (reinterpret_cast<uintptr_t>(d_status) % 4))
+        return ZIPCCL_ERR_INVALID_ARG;
+
+    std::vector<uint64_t> slot_off(n_chunks + 1);
+    uint64_t off = 0;
+    for (uint32_t c = 0; c < n_chunks; ++c) {
+        slot_off[c] = off;
+        const SlotLayout L = slot_layout(ce[c], dt);
+        if (off + L.esc > comp_capacity) return ZIPCCL_ERR_BUFFER_TOO_SMALL; /* static part must be readable */
+        off += L.cap;
+    }
+    slot_off[n_chunks] = off;
+    if (total_tiles(ce) > 0x7FFFFFFFull) return ZIPCCL_ERR_INVALID_ARG;
+
+    DecompressArgs a;
+    std::memset(&a, 0, sizeof a);
+    a.status = d_status;
+    uint64_t elem_base = 0;
+    for (uint32_t c0 = 0; c0 < n_chunks; c0 += kMaxBatch) {
+        const uint32_t nb = (n_chunks - c0) < kMaxBatch ? (n_chunks - c0) : kMaxBatch;
+        const uint32_t nt = fill_tab(a.tab, ce, slot_off, c0, nb, dt);
+        a.comp = static_cast<const uint8_t*>(d_comp) + slot_off[c0];
+        a.comp_capacity = comp_capacity - slot_off[c0];
+        a.out = static_cast<uint8_t*>(d_out) + elem_base * es;
+        if (launch_decompress(dt, a, nt, stream) != 0) return ZIPCCL_ERR_DEVICE;
+        elem_base += a.tab.elem_off[nb];
+    }
+    return ZIPCCL_OK;
+}
+
+int zipccl_debug_compress_path(int path)
+{
+    const int prev = compress_path().load();
+    if (path == 0 || path == 1) compress_path().store(path);
+    return prev;
+}
+
+const char* zipccl_status_string(zipccl_status_t s)
+{
+    switch (s) {
+        case ZIPCCL_OK: return "ok";
+        case ZIPCCL_ERR_INVALID_ARG: return "invalid argument";
+        case ZIPCCL_ERR_UNSUPPORTED_DTYPE: return "unsupported dtype";
+        case ZIPCCL_ERR_BUFFER_TOO_SMALL: return "buffer too small";
+        case ZIPCCL_ERR_CORRUPT: return "corrupt compressed data";
+        case ZIPCCL_ERR_DEVICE: return "device error";
+    }
+    return "unknown status";
+}
+
+} // extern "C"

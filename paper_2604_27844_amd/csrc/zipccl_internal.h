@@ -1,0 +1,93 @@
+/* Internal declarations shared by the host logic and the HIP kernels of libzipccl.so. */
+#ifndef ZIPCCL_INTERNAL_H
+#define ZIPCCL_INTERNAL_H
+
+#include <stdint.h>
+#include "zipccl.h"
+
+#if defined(__HIPCC__)
+#define ZIPCCL_HD __host__ __device__ inline
+#else
+#define ZIPCCL_HD inline
+#endif
+
+namespace zipccl {
+
+/* Work decomposition: a workgroup of 4 wave64 handles one TILE of 16 groups; a wave handles
+ * a group of 512 elements at a time, 8 consecutive elements per lane (one 16-byte bf16 load). */
+constexpr uint32_t kLaneElems = 8;
+constexpr uint32_t kGroup = ZIPCCL_GROUP;
+constexpr uint32_t kWavesPerBlock = 4;
+constexpr uint32_t kThreads = 64 * kWavesPerBlock;
+constexpr uint32_t kGroupsPerWave = 4;
+constexpr uint32_t kGroupsPerTile = kWavesPerBlock * kGroupsPerWave;
+constexpr uint32_t kTile = kGroup * kGroupsPerTile; /* 8192 elements */
+constexpr uint32_t kMaxBatch = 128;                 /* chunks per kernel launch */
+constexpr uint32_t kVersion = 1;
+constexpr uint32_t kMagic = 0x4C43505Au;            /* "ZPCL" little-endian */
+constexpr uint32_t kWorkspaceHeader = 256;          /* bytes before the tile status array */
+
+/* header field offsets */
+constexpr uint32_t kHdrMagic = 0, kHdrVersion = 4, kHdrDtype = 8, kHdrGroup = 12, kHdrN = 16,
+                   kHdrNEsc = 24, kHdrChunkBytes = 32, kHdrDec = 40;
+
+ZIPCCL_HD uint64_t pad128(uint64_t x) { return (x + 127u) & ~(uint64_t)127u; }
+ZIPCCL_HD uint32_t elem_size(int dt) { return dt == ZIPCCL_BF16 ? 2u : 4u; }
+
+/* Byte offsets of the sections inside a slot of n elements (all multiples of 128). */
+struct SlotLayout {
+    uint64_t sm, lo, p0, plane_bytes, idx, esc, cap;
+};
+
+ZIPCCL_HD SlotLayout slot_layout(uint64_t n, int dt)
+{
+    SlotLayout L;
+    L.sm = 128;
+    L.lo = L.sm + pad128(n);
+    L.p0 = L.lo + (dt == ZIPCCL_FP32 ? pad128(2 * n) : 0);
+    L.plane_bytes = pad128((n + 7) / 8);
+    L.idx = L.p0 + 3 * L.plane_bytes;
+    L.esc = L.idx + pad128(4 * ((n + kGroup - 1) / kGroup));
+    L.cap = L.esc + pad128(n);
+    return L;
+}
+
+ZIPCCL_HD uint64_t tiles_of(uint64_t n) { return n == 0 ? 1 : (n + kTile - 1) / kTile; }
+
+/* Per-launch chunk table, passed by value in the kernel argument segment. */
+struct ChunkTab {
+    uint32_t n_chunks;
+    uint32_t tile_start[kMaxBatch + 1]; /* first tile of chunk c in this launch */
+    uint64_t elem_off[kMaxBatch + 1];   /* first element of chunk c, relative to the launch's input */
+    uint64_t slot_off[kMaxBatch + 1];   /* byte offset of slot c, relative to the launch's output */
+};
+
+struct CompressArgs {
+    const uint8_t* in;       /* first element of the launch's first chunk */
+    uint8_t* out;            /* compressed buffer base for this launch */
+    uint64_t* chunk_bytes;   /* entry of the launch's first chunk, or null */
+    uint64_t* tile_state;    /* one u64 per tile of this launch */
+    uint32_t* err;           /* workspace status word */
+    uint32_t e0;             /* dec[1] */
+    uint32_t dec_lo, dec_hi; /* dec[0..3], dec[4..7] packed little-endian */
+    ChunkTab tab;
+};
+
+struct DecompressArgs {
+    const uint8_t* comp;
+    uint64_t comp_capacity;  /* readable bytes from comp */
+    uint8_t* out;
+    uint32_t* status;        /* may be null */
+    ChunkTab tab;
+};
+
+enum CompressMode { kModeCount = 0, kModeEmit = 1, kModeFused = 2 };
+
+/* launchers implemented in zipccl_kernels.hip; return a hipError_t as int */
+int launch_fill_zero(void* d_ptr, uint64_t bytes, void* stream);
+int launch_compress(int dt, int mode, const CompressArgs& a, uint32_t n_tiles, void* stream);
+int launch_tile_scan(const CompressArgs& a, void* stream);
+int launch_decompress(int dt, const DecompressArgs& a, uint32_t n_tiles, void* stream);
+
+} // namespace zipccl
+#endif

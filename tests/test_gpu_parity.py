@@ -1,0 +1,188 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, bit for bit.
+
+Integer / byte work throughout, so the bar is exact equality of the compressed bytes over
+the transmitted range of every slot, of chunk_bytes, and of the decoded words.
+"""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2604_27844_amd.binding as z
+from paper_2604_27844_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    from gpu_util import DEV, check_parity, gpu_compress, gpu_decompress, to_device_words
+
+
+def _say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(params=[0, 1], ids=["fused", "3pass"])
+def compress_path(request):
+    prev = z.zipccl_debug_compress_path(request.param)
+    yield request.param
+    z.zipccl_debug_compress_path(prev)
+
+
+SMALL = [("c1", 1.0), ("c2", 1 / 8), ("c3", 1 / 32), ("c4", 1 / 64), ("c5", 1 / 64), ("c5_fp32", 1 / 32)]
+
+
+@pytest.mark.parametrize("name,scale", SMALL)
+def test_workload_parity_small(name, scale, compress_path):
+    w = W.make(name, scale)
+    _say(f"[parity] {w.name} n={w.n_elems} chunks={w.n_chunks} path={compress_path}")
+    check_parity(w.data, w.dtype, w.sigma, w.n_chunks, w.chunk_elems, label=w.name)
+
+
+EDGE_N = [0, 1, 7, 8, 9, 63, 64, 127, 128, 129, 511, 512, 513, 1023, 4095, 4096, 4097, 8191, 8192, 8193,
+          16384, 16389, 40000]
+
+
+@pytest.mark.parametrize("dtype", [z.BF16, z.FP32], ids=["bf16", "fp32"])
+def test_edge_sizes_single_chunk(dtype, compress_path):
+    rng = np.random.default_rng(100 + dtype)
+    for n in EDGE_N:
+        _say(f"[edge] dtype={dtype} n={n} path={compress_path}")
+        f = rng.standard_normal(n, dtype=np.float32)
+        data = W.f32_to_bf16_words(f) if dtype == z.BF16 else f.view(np.uint32).copy()
+        check_parity(data, dtype, 1.0, 1, None, label=f"n={n}")
+
+
+@pytest.mark.parametrize("dtype", [z.BF16, z.FP32], ids=["bf16", "fp32"])
+def test_ragged_chunks_with_empty_and_unaligned_starts(dtype, compress_path):
+    # odd chunk sizes make chunk starts 2/4-byte aligned only -> the element-wise path
+    ce = np.array([0, 1, 8191, 8192, 3, 0, 20001, 513, 16384, 7, 0], dtype=np.uint64)
+    n = int(ce.sum())
+    rng = np.random.default_rng(7)
+    f = rng.standard_normal(n, dtype=np.float32) * np.float32(0.5)
+    data = W.f32_to_bf16_words(f) if dtype == z.BF16 else f.view(np.uint32).copy()
+    _say(f"[ragged] dtype={dtype} n={n} chunks={len(ce)} path={compress_path}")
+    check_parity(data, dtype, 0.5, len(ce), ce, label="ragged")
+
+
+def test_more_chunks_than_one_launch_holds(compress_path):
+    rng = np.random.default_rng(8)
+    ce = rng.integers(0, 3000, 300).astype(np.uint64)
+    ce[::17] = 0
+    ce[5] = 30000
+    n = int(ce.sum())
+    data = W.f32_to_bf16_words(rng.standard_normal(n, dtype=np.float32))
+    _say(f"[batches] n={n} chunks=300 path={compress_path}")
+    check_parity(data, z.BF16, 1.0, 300, ce, label="300 chunks")
+
+
+def test_all_bf16_patterns_and_extreme_tables(compress_path):
+    data = np.tile(np.arange(65536, dtype=np.uint16), 2)[:-5]
+    for sigma in (1.0, 1e-45, 1e300, 0.02):
+        _say(f"[patterns] sigma={sigma} path={compress_path}")
+        check_parity(data, z.BF16, sigma, 1, None, label=f"patterns sigma={sigma}")
+
+
+def test_fp32_random_bit_patterns(compress_path):
+    rng = np.random.default_rng(9)
+    data = rng.integers(0, 2 ** 32, 100_003, dtype=np.uint64).astype(np.uint32)
+    data[:6] = [0, 0x80000000, 0x7F800000, 0xFF800000, 0x7FC00001, 0xFFFFFFFF]
+    _say(f"[fp32 bits] path={compress_path}")
+    check_parity(data, z.FP32, 1.0, 1, None, label="fp32 bits")
+
+
+def test_all_zero_points_and_none(compress_path):
+    n = 3 * 8192 + 77
+    zeros = np.zeros(n, dtype=np.uint16)                     # every value a zero-point: ESC = n bytes
+    ones = np.full(n, 0x3F80, dtype=np.uint16)               # no zero-point at all
+    half = ones.copy()
+    half[::2] = 0x7F80                                       # alternating +Inf
+    for name, d in (("all-escape", zeros), ("no-escape", ones), ("alternating", half)):
+        _say(f"[{name}] path={compress_path}")
+        got, cb, off = check_parity(d, z.BF16, 1.0, 1, None, label=name)
+    # worst case fills the slot exactly: chunk_bytes == capacity
+    d_out, d_cb, _ = gpu_compress(np.zeros(8192, dtype=np.uint16), z.BF16, 1.0)
+    assert int(d_cb.item()) == z.zipccl_max_compressed_size(8192, z.BF16, 1)
+
+
+def test_peer_decodes_its_slice_alone_from_transmitted_bytes():
+    w = W.make("c3", 1 / 64)
+    d_out, d_cb, table = gpu_compress(w.data, w.dtype, w.sigma, w.n_chunks, w.chunk_elems)
+    off = z.zipccl_chunk_slot_offsets(w.n_elems, w.dtype, w.n_chunks, w.chunk_elems)
+    cb = d_cb.cpu().numpy()
+    start = 0
+    for c in range(w.n_chunks):
+        nc = int(w.chunk_elems[c])
+        if c % 9 == 0:
+            slice_ = d_out[int(off[c]):int(off[c]) + int(cb[c])].clone()     # exactly what would be sent
+            back, st = gpu_decompress(slice_, nc, w.dtype, 1, None)
+            assert st == 0 and np.array_equal(back, w.data[start:start + nc]), c
+        start += nc
+
+
+def test_compress_is_deterministic_and_reuses_workspace():
+    w = W.make("c4", 1 / 64)
+    table = z.zipccl_build_table(w.sigma, w.dtype)
+    cap = z.zipccl_max_compressed_size(w.n_elems, w.dtype, w.n_chunks)
+    d_in = to_device_words(w.data)
+    d_ws = torch.empty(z.zipccl_compress_workspace_size(w.n_elems, w.dtype, w.n_chunks), dtype=torch.uint8, device=DEV)
+    outs = []
+    for it in range(4):
+        d_out = torch.full((cap,), 0x11 * (it + 1), dtype=torch.uint8, device=DEV)
+        d_cb = torch.zeros(w.n_chunks, dtype=torch.int64, device=DEV)
+        z.zipccl_compress(d_in, w.n_elems, w.dtype, w.n_chunks, None, table, d_out, d_cb, d_ws)
+        torch.cuda.synchronize()
+        assert int(d_ws[:4].view(torch.int32).item()) == 0
+        outs.append((d_out.cpu().numpy(), d_cb.cpu().numpy()))
+    off = z.zipccl_chunk_slot_offsets(w.n_elems, w.dtype, w.n_chunks)
+    for o, cb in outs[1:]:
+        assert np.array_equal(cb, outs[0][1])
+        for c in range(w.n_chunks):
+            s, e = int(off[c]), int(off[c]) + int(cb[c])
+            assert np.array_equal(o[s:e], outs[0][0][s:e])
+
+
+def test_decoder_flags_corrupt_streams_without_leaving_buffers():
+    w = W.make("c1", 1 / 16)
+    d_out, d_cb, _ = gpu_compress(w.data, w.dtype, w.sigma)
+    n = w.n_elems
+    cb = int(d_cb.item())
+    good = d_out[:cb].clone()
+    back, st = gpu_decompress(good, n, w.dtype)
+    assert st == 0 and np.array_equal(back, w.data)
+    lay_idx = 128 + n + 3 * (n // 8)                       # n is a multiple of 1024 here
+    for pos, val in ((0, 0x00), (4, 2), (8, 1), (13, 1), (16, 1), (24, 0xFF), (41, 3)):
+        bad = good.clone()
+        bad[pos] = val
+        _, st = gpu_decompress(bad, n, w.dtype)
+        assert st == 4, pos
+    bad = good.clone()                                       # an index far outside the zero-point list
+    bad[lay_idx + 4:lay_idx + 8] = torch.tensor([0xFF, 0xFF, 0xFF, 0x7F], dtype=torch.uint8, device=DEV)
+    _, st = gpu_decompress(bad, n, w.dtype)
+    assert st == 4
+    # zero-point list cut off: the header promises more bytes than the buffer holds
+    _, st = gpu_decompress(good, n, w.dtype, comp_capacity=cb - 128)
+    assert st == 4
+    with pytest.raises(z.ZipcclError) as ei:                 # static part not readable: host error
+        gpu_decompress(good, n, w.dtype, comp_capacity=lay_idx)
+    assert ei.value.code == 3
+
+
+def test_runs_on_a_side_stream():
+    w = W.make("c2", 1 / 16)
+    s = torch.cuda.Stream()
+    table = z.zipccl_build_table(w.sigma, w.dtype)
+    cap = z.zipccl_max_compressed_size(w.n_elems, w.dtype, w.n_chunks)
+    d_in = to_device_words(w.data)
+    d_out = torch.empty(cap, dtype=torch.uint8, device=DEV)
+    d_cb = torch.zeros(w.n_chunks, dtype=torch.int64, device=DEV)
+    d_ws = torch.empty(z.zipccl_compress_workspace_size(w.n_elems, w.dtype, w.n_chunks), dtype=torch.uint8, device=DEV)
+    d_back = torch.zeros_like(d_in)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        z.zipccl_compress(d_in, w.n_elems, w.dtype, w.n_chunks, None, table, d_out, d_cb, d_ws, stream=s)
+        z.zipccl_decompress(d_out, d_back, w.n_elems, w.dtype, w.n_chunks, None, None, stream=s)
+    s.synchronize()
+    assert np.array_equal(d_back.cpu().numpy().view(np.uint16), w.data)
