@@ -1,0 +1,214 @@
+#!/usr/bin/env python3
+"""Benchmark of the ZipCCL codec hot path on one MI355X.
+
+A step = one compress + one decompress of the whole workload (all peer chunks), inputs
+resident in HBM.  Prints ONE JSON line: round-trip throughput in uncompressed GB/s, the
+per-direction rates and compression ratio, the HBM roofline of the dominant kernel measured
+live with events on the launch stream, and the CPU oracle timed on the host cores.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c5] [--all]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0            # MI355X HBM3E, published peak
+PAPER_CONTEXT = ("paper (64x RTX A6000, 200 Gb/s): communication time -1.35x, end-to-end training 1.18x; "
+                 "it prints no codec GB/s, so vs_baseline is null")
+
+
+def log(msg):
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+def run_gpu(w, steps, warmup):
+    import torch
+    import paper_2604_27844_amd.binding as z
+
+    dev = torch.device("cuda:0")
+    signed = np.int16 if w.dtype == z.BF16 else np.int32
+    d_in = torch.from_numpy(w.data.view(signed)).to(dev)
+    table = z.zipccl_build_table(w.sigma, w.dtype)
+    cap = z.zipccl_max_compressed_size(w.n_elems, w.dtype, w.n_chunks, w.chunk_elems)
+    d_out = torch.empty(cap, dtype=torch.uint8, device=dev)
+    d_cb = torch.zeros(w.n_chunks, dtype=torch.int64, device=dev)
+    d_ws = torch.empty(z.zipccl_compress_workspace_size(w.n_elems, w.dtype, w.n_chunks, w.chunk_elems),
+                       dtype=torch.uint8, device=dev)
+    d_back = torch.empty_like(d_in)
+    d_st = torch.zeros(1, dtype=torch.int32, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def compress():
+        z.zipccl_compress(d_in, w.n_elems, w.dtype, w.n_chunks, w.chunk_elems, table, d_out, d_cb, d_ws, stream=stream)
+
+    def decompress():
+        z.zipccl_decompress(d_out, d_back, w.n_elems, w.dtype, w.n_chunks, w.chunk_elems, d_st, stream=stream)
+
+    for _ in range(max(1, warmup)):
+        compress()
+        decompress()
+    torch.cuda.synchronize()
+    assert int(d_st.item()) == 0 and int(d_ws[:4].view(torch.int32).item()) == 0
+    assert torch.equal(d_back, d_in), "round trip is not the identity"
+    comp_bytes = int(d_cb.sum().item())
+
+    # K timed steps, bracketed by synchronize; events (on the launch stream) split the directions
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(steps):
+        evs[k][0].record(stream)
+        compress()
+        evs[k][1].record(stream)
+        decompress()
+        evs[k][2].record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    tc = np.array([e[0].elapsed_time(e[1]) for e in evs])      # ms
+    td = np.array([e[1].elapsed_time(e[2]) for e in evs])
+    return dict(wall_s=wall, tc_ms=tc, td_ms=td, comp_bytes=comp_bytes,
+                d_out=d_out, d_cb=d_cb, table=table)
+
+
+def run_oracle(w, gpu_out=None, gpu_cb=None):
+    """The oracle as it stands: single thread over the whole workload, then one chunk per host thread."""
+    import oracle
+    dec = oracle.build_table(w.sigma)
+    t0 = time.perf_counter()
+    ref, ref_cb, off = oracle.compress(w.data, w.dtype, dec, w.n_chunks, w.chunk_elems)
+    t1 = time.perf_counter()
+    back = oracle.decompress(ref, w.n_elems, w.dtype, w.n_chunks, w.chunk_elems)
+    t2 = time.perf_counter()
+    assert np.array_equal(back, w.data)
+    same = None
+    if gpu_out is not None:
+        same = bool(np.array_equal(gpu_cb, ref_cb))
+        for c in range(0, w.n_chunks, max(1, w.n_chunks // 8)):    # sampled slots, byte for byte
+            s, e = int(off[c]), int(off[c]) + int(ref_cb[c])
+            same = same and bool(np.array_equal(gpu_out[s:e], ref[s:e]))
+    # chunk-parallel: every peer slice is independent
+    cores = len(os.sched_getaffinity(0))
+    ce = w.chunk_elems if w.chunk_elems is not None else np.full(w.n_chunks, w.n_elems // w.n_chunks, dtype=np.uint64)
+    starts = np.concatenate([[0], np.cumsum(ce)]).astype(np.int64)
+
+    def one(c):
+        x = w.data[starts[c]:starts[c + 1]]
+        o, cb, _ = oracle.compress(x, w.dtype, dec)
+        oracle.decompress(o, x.size, w.dtype)
+
+    threads = min(cores, w.n_chunks)
+    t3 = time.perf_counter()
+    with ThreadPoolExecutor(threads) as ex:
+        list(ex.map(one, range(w.n_chunks)))
+    t4 = time.perf_counter()
+    gb = w.nbytes / 1e9
+    return dict(single=dict(compress_GBps=gb / (t1 - t0), decompress_GBps=gb / (t2 - t1),
+                            roundtrip_GBps=gb / (t2 - t0)),
+                parallel=dict(roundtrip_GBps=gb / (t4 - t3), threads=threads),
+                ratio=w.nbytes / float(ref_cb.sum()), matches_gpu=same, host_cores=cores)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c5", help="c1|c2|c3|c4|c5|c5_fp32 (default: c5, the largest)")
+    ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (parity/debug only)")
+    ap.add_argument("--all", action="store_true", help="also time the other >=256 MB workloads (extra object)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build is a single-GPU codec path; run with --gpus 1 "
+                 "(no collective or second GPU is used anywhere)")
+
+    import torch
+    from paper_2604_27844_amd import workloads
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU (the product path has no CPU fallback)")
+
+    log(f"generating workload {args.workload} (scale {args.scale})")
+    w = workloads.make(args.workload, args.scale)
+    log(f"{w.name}: n={w.n_elems} ({w.nbytes / 2**20:.0f} MiB), {w.n_chunks} chunks, sigma={w.sigma}")
+    r = run_gpu(w, args.steps, args.warmup)
+    gb = w.nbytes / 1e9
+    tc, td = float(r["tc_ms"].mean()), float(r["td_ms"].mean())
+    ms_per_step = r["wall_s"] * 1e3 / args.steps
+    algo_bytes = w.nbytes + r["comp_bytes"]       # each direction reads one side and writes the other
+    dominant = "compress" if tc >= td else "decompress"
+    t_dom = max(tc, td)
+    achieved = algo_bytes / (t_dom * 1e-3) / 1e9
+    es = 2 if w.dtype == 0 else 4
+    traffic = None
+    tfile = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tfile):
+        traffic = json.load(open(tfile)).get(f"{args.workload}:{dominant}")
+
+    out = {
+        "metric": "codec_roundtrip_uncompressed_GBps", "value": round(gb / (ms_per_step * 1e-3), 2), "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u16" if w.dtype == 0 else "u32", "data": "synthetic",
+        "config": {"workload": w.name, "n_elems": w.n_elems, "elem_bytes": es, "n_chunks": w.n_chunks,
+                   "ragged": w.chunk_elems is not None, "table_sigma": w.sigma, "group": 512, "scale": args.scale},
+        "compress_GBps": round(gb / (tc * 1e-3), 2), "decompress_GBps": round(gb / (td * 1e-3), 2),
+        "compress_ms": round(tc, 4), "decompress_ms": round(td, 4),
+        "compress_ms_min": round(float(r["tc_ms"].min()), 4), "decompress_ms_min": round(float(r["td_ms"].min()), 4),
+        "compression_ratio": round(w.nbytes / r["comp_bytes"], 5),
+        "roofline": {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                     "algorithmic_bytes_per_launch": algo_bytes,
+                     "compress_frac": round(algo_bytes / (tc * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                     "decompress_frac": round(algo_bytes / (td * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)},
+        "paper_context": PAPER_CONTEXT,
+    }
+
+    if not args.no_cpu:
+        log("timing the CPU oracle on the same workload")
+        o = run_oracle(w, r["d_out"].cpu().numpy(), r["d_cb"].cpu().numpy().astype(np.uint64))
+        out["cpu_baseline"] = {"value": round(o["single"]["roundtrip_GBps"], 4), "unit": "GB/s", "cores": 1,
+                               "kind": "oracle",
+                               "sample": f"the whole workload ({w.nbytes / 2**20:.0f} MiB), compress + decompress, "
+                                         "scalar C oracle on one host thread",
+                               "compress_GBps": round(o["single"]["compress_GBps"], 4),
+                               "decompress_GBps": round(o["single"]["decompress_GBps"], 4),
+                               "all_cores": {"value": round(o["parallel"]["roundtrip_GBps"], 4),
+                                             "cores": o["parallel"]["threads"],
+                                             "how": "one peer chunk per host thread"},
+                               "host_cores": o["host_cores"], "ratio": round(o["ratio"], 5),
+                               "gpu_bytes_match_oracle": o["matches_gpu"]}
+    del r
+
+    if args.all:
+        extra = {}
+        for name in ("c3", "c4", "c5", "c5_fp32", "c2", "c1"):
+            if name == args.workload:
+                continue
+            log(f"extra workload {name}")
+            w2 = workloads.make(name, args.scale)
+            r2 = run_gpu(w2, args.steps, args.warmup)
+            tc2, td2 = float(r2["tc_ms"].mean()), float(r2["td_ms"].mean())
+            ab = w2.nbytes + r2["comp_bytes"]
+            extra[w2.name] = {"MiB": round(w2.nbytes / 2**20, 1),
+                              "compress_GBps": round(w2.nbytes / 1e9 / (tc2 * 1e-3), 2),
+                              "decompress_GBps": round(w2.nbytes / 1e9 / (td2 * 1e-3), 2),
+                              "compress_hbm_frac": round(ab / (tc2 * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                              "decompress_hbm_frac": round(ab / (td2 * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                              "compression_ratio": round(w2.nbytes / r2["comp_bytes"], 5)}
+            del r2, w2
+            torch.cuda.empty_cache()
+        out["other_workloads"] = extra
+
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()
