@@ -61,7 +61,8 @@ typedef enum {
 } zipccl_status_t;
 
 /* dec[0] is unused (code 0 flags a zero-point); dec[1..7] are the biased exponents of codes
- * 1..7 and must be consecutive ascending values (the Gaussian model always yields a window). */
+ * 1..7 and must be consecutive ascending values with 1 <= dec[1] <= 249 (the Gaussian model
+ * always yields such a window). */
 typedef struct { uint8_t dec[8]; } zipccl_table_t;
 
 /*

@@ -50,7 +50,7 @@ bool resolve_split(size_t n_elems, uint32_t n_chunks, const uint64_t* chunk_elem
 bool table_ok(const zipccl_table_t* t)
 {
     if (!t) return false;
-    if (t->dec[1] > 249) return false;
+    if (t->dec[1] < 1 || t->dec[1] > 249) return false;
     for (int k = 2; k <= 7; ++k)
         if (t->dec[k] != t->dec[1] + k - 1) return false;
     return true;

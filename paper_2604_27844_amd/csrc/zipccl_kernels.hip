@@ -4,10 +4,14 @@
  * compress   : paper section 4 (split, 3-bit code, zero-points) with the kernel steps of
  *              section 4.2 re-designed for wave64: one wave handles a group of 512 values,
  *              8 consecutive values per lane (one 16-byte load for bf16), a workgroup of
- *              4 waves handles a tile of 16 groups.  The zero-point offsets of section 4.2.3
- *              are an exclusive prefix in element order (lane -> wave -> tile -> chunk), so the
- *              output is deterministic; the chunk-wide part is a decoupled look-back over
- *              per-tile state words instead of the paper's block-level atomic add.
+ *              4 waves handles a tile of 16 groups.  Per lane the work is SWAR on packed
+ *              words: v_perm_b32 gathers the sign/mantissa and exponent bytes, packed 16-bit
+ *              sub/min produce the codes, v_dot4_u32_u8 transposes code bits into plane bytes.
+ *              Plane bytes and zero-point exponents are staged in LDS and leave as wide
+ *              stores.  The zero-point offsets of section 4.2.3 are an exclusive prefix in
+ *              element order (lane -> wave -> tile -> chunk), so the output is deterministic;
+ *              the chunk-wide part is a decoupled look-back over per-tile state words instead
+ *              of the paper's block-level atomic add.
  * decompress : section 4, third paragraph.  No dependency between workgroups.
  *
  * Everything is integer work; sigma / erf live on the host.
@@ -23,27 +27,53 @@ constexpr uint64_t kFlagAgg = 1ull << 32;  /* tile state: low 32 bits = this til
 constexpr uint64_t kFlagInc = 2ull << 32;  /* tile state: low 32 bits = count of this and all earlier tiles of the chunk */
 constexpr uint32_t kSpinLimit = 1u << 22;  /* polls before the look-back gives up and flags an error */
 
+typedef unsigned short us2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ uint32_t pk_sub_u16(uint32_t a, uint32_t b)
+{
+    return __builtin_bit_cast(uint32_t, (us2)(__builtin_bit_cast(us2, a) - __builtin_bit_cast(us2, b)));
+}
+__device__ __forceinline__ uint32_t pk_min_u16(uint32_t a, uint32_t b)
+{
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_min(__builtin_bit_cast(us2, a), __builtin_bit_cast(us2, b)));
+}
+/* byte k of the result = byte sel.k of the 8-byte pool {hi:lo} (indices 0-3 = lo, 4-7 = hi, 0x0c = 0) */
+__device__ __forceinline__ uint32_t perm(uint32_t hi, uint32_t lo, uint32_t sel)
+{
+    return __builtin_amdgcn_perm(hi, lo, sel);
+}
+__device__ __forceinline__ uint32_t bfi(uint32_t mask, uint32_t a, uint32_t b) { return (a & mask) | (b & ~mask); }
+
 __device__ __forceinline__ uint32_t lane_id()
 {
     return __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
 }
 
-/* inclusive prefix sum over the 64 lanes of a wave */
-__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t x, uint32_t lane)
+/* inclusive prefix sum over the 64 lanes of a wave (DPP row shifts, then row broadcasts) */
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t x)
 {
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const uint32_t y = __shfl_up(x, d, 64);
-        if (lane >= (uint32_t)d) x += y;
-    }
+    x += __builtin_amdgcn_update_dpp(0u, x, 0x111, 0xF, 0xF, true);  /* row_shr:1 */
+    x += __builtin_amdgcn_update_dpp(0u, x, 0x112, 0xF, 0xF, true);  /* row_shr:2 */
+    x += __builtin_amdgcn_update_dpp(0u, x, 0x114, 0xF, 0xF, true);  /* row_shr:4 */
+    x += __builtin_amdgcn_update_dpp(0u, x, 0x118, 0xF, 0xF, true);  /* row_shr:8 */
+    x += __builtin_amdgcn_update_dpp(0u, x, 0x142, 0xA, 0xF, false); /* row_bcast:15 into rows 1,3 */
+    x += __builtin_amdgcn_update_dpp(0u, x, 0x143, 0xC, 0xF, false); /* row_bcast:31 into rows 2,3 */
+    return x;
+}
+
+/* inclusive prefix sum inside each row of 16 lanes */
+__device__ __forceinline__ uint32_t row_incl_scan(uint32_t x)
+{
+    x += __builtin_amdgcn_update_dpp(0u, x, 0x111, 0xF, 0xF, true);
+    x += __builtin_amdgcn_update_dpp(0u, x, 0x112, 0xF, 0xF, true);
+    x += __builtin_amdgcn_update_dpp(0u, x, 0x114, 0xF, 0xF, true);
+    x += __builtin_amdgcn_update_dpp(0u, x, 0x118, 0xF, 0xF, true);
     return x;
 }
 
 __device__ __forceinline__ uint32_t wave_sum(uint32_t x)
 {
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) x += __shfl_xor(x, d, 64);
-    return x;
+    return __builtin_amdgcn_readlane(wave_incl_scan(x), 63);
 }
 
 /* largest c with tile_start[c] <= t (every chunk owns at least one tile) */
@@ -70,6 +100,7 @@ __device__ __forceinline__ uint64_t load_state(const uint64_t* p)
  * Load the lane's 8 consecutive values starting at chunk-relative element e.
  * hp[k] packs the high 16-bit words of values 2k (low half) and 2k+1 (high half);
  * lp[k] the low words (fp32 only).  vmask bit j = value j exists (e + j < n).
+ * Values that do not exist read as 0.
  */
 template <int DT, bool FAST>
 __device__ __forceinline__ void load_lane(const uint8_t* __restrict__ cin, uint64_t e, uint64_t n,
@@ -87,8 +118,8 @@ __device__ __forceinline__ void load_lane(const uint8_t* __restrict__ cin, uint6
             const uint32_t x[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                hp[k] = (x[2 * k] >> 16) | (x[2 * k + 1] & 0xFFFF0000u);
-                lp[k] = (x[2 * k] & 0xFFFFu) | (x[2 * k + 1] << 16);
+                hp[k] = perm(x[2 * k + 1], x[2 * k], 0x07060302u);
+                lp[k] = perm(x[2 * k + 1], x[2 * k], 0x05040100u);
             }
         }
     } else {
@@ -115,57 +146,48 @@ __device__ __forceinline__ void load_lane(const uint8_t* __restrict__ cin, uint6
     }
 }
 
+/* What a lane derives from its 8 values (section 4: split, code, zero-point detection). */
+struct LaneEnc {
+    uint32_t sm0, sm1;      /* 8 sign+mantissa bytes */
+    uint32_t ex0, ex1;      /* 8 raw exponent bytes */
+    uint32_t b0, b1, b2;    /* plane bytes: bit j = bit k of the code of value j */
+    uint32_t m;             /* bit j = value j is a zero-point (before masking non-existent values) */
+};
+
 /*
- * Encode one group (section 4: split / code / zero-point detection).  Writes the SM, LO and
- * plane bytes of the lane when STORE; returns the lane's 8 raw exponents (ex_lo, ex_hi), its
- * zero-point mask m, its exclusive offset inside the group and the group's zero-point count.
+ * SWAR encode of 8 values held as four packed pairs of 16-bit words.
+ * k7 = (dec[1] - 1) << 7 in both halves; a value of exponent E has
+ * t = E - (dec[1] - 1): code = t for t in 1..7, zero-point otherwise.
  */
-template <int DT, bool FAST, bool STORE>
-__device__ __forceinline__ void encode_group(const uint8_t* __restrict__ cin, uint8_t* __restrict__ slot,
-                                             const SlotLayout& L, uint64_t n, uint64_t e, uint32_t e0m1,
-                                             uint32_t lane, uint32_t& ex_lo, uint32_t& ex_hi, uint32_t& m,
-                                             uint32_t& loff, uint32_t& gtot)
+__device__ __forceinline__ LaneEnc encode8(const uint32_t w[4], uint32_t k7)
 {
-    uint32_t hp[4], lp[4], vmask;
-    load_lane<DT, FAST>(cin, e, n, hp, lp, vmask);
-    uint32_t sm[2] = {0, 0}, ex[2] = {0, 0}, b0 = 0, b1 = 0, b2 = 0;
-    m = 0;
+    LaneEnc r;
+    uint32_t c4[2];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const uint32_t h = (j & 1) ? (hp[j >> 1] >> 16) : (hp[j >> 1] & 0xFFFFu);
-        const uint32_t E = (h >> 7) & 0xFFu;
-        const uint32_t t = E - e0m1;               /* 1..7 inside the window (mod 2^32) */
-        uint32_t code = t < 8u ? t : 0u;
-        if (!FAST) code = ((vmask >> j) & 1u) ? code : 0u;
-        const uint32_t smb = ((h >> 8) & 0x80u) | (h & 0x7Fu);
-        sm[j >> 2] |= smb << (8 * (j & 3));
-        ex[j >> 2] |= E << (8 * (j & 3));
-        b0 |= (code & 1u) << j;
-        b1 |= ((code >> 1) & 1u) << j;
-        b2 |= (code >> 2) << j;
-        m |= (code == 0u ? 1u : 0u) << j;
+    for (int h = 0; h < 2; ++h) {
+        const uint32_t wa = w[2 * h], wb = w[2 * h + 1];
+        const uint32_t lo = perm(wb, wa, 0x06040200u);   /* low bytes: mantissa | E bit 0 << 7 */
+        const uint32_t hi = perm(wb, wa, 0x07050301u);   /* high bytes: sign << 7 | E >> 1 */
+        const uint32_t sm = bfi(0x7F7F7F7Fu, lo, hi);
+        const uint32_t ex = bfi(0xFEFEFEFEu, hi << 1, lo >> 7);
+        /* (E << 7) - k7 per half, clamped to 8 << 7: 1..7 << 7 inside the window */
+        const uint32_t qa = pk_min_u16(pk_sub_u16(wa & 0x7F807F80u, k7), 0x04000400u) >> 7;
+        const uint32_t qb = pk_min_u16(pk_sub_u16(wb & 0x7F807F80u, k7), 0x04000400u) >> 7;
+        c4[h] = perm(qb, qa, 0x06040200u);               /* 4 code bytes, 8 = outside the window */
+        if (h == 0) { r.sm0 = sm; r.ex0 = ex; } else { r.sm1 = sm; r.ex1 = ex; }
     }
-    m &= vmask;
-    if (STORE) {
-        if (FAST || e < pad128(n))
-            *reinterpret_cast<uint2*>(slot + L.sm + e) = make_uint2(sm[0], sm[1]);
-        if (DT == ZIPCCL_FP32) {
-            if (FAST || 2 * e < pad128(2 * n))
-                *reinterpret_cast<uint4*>(slot + L.lo + 2 * e) = make_uint4(lp[0], lp[1], lp[2], lp[3]);
-        }
-        const uint64_t pb = e >> 3;
-        if (FAST || pb < L.plane_bytes) {
-            slot[L.p0 + pb] = (uint8_t)b0;
-            slot[L.p0 + L.plane_bytes + pb] = (uint8_t)b1;
-            slot[L.p0 + 2 * L.plane_bytes + pb] = (uint8_t)b2;
-        }
-    }
-    const uint32_t cnt = __popc(m);
-    const uint32_t inc = wave_incl_scan(cnt, lane);
-    loff = inc - cnt;
-    gtot = __shfl(inc, 63, 64);
-    ex_lo = ex[0];
-    ex_hi = ex[1];
+    /* bit-matrix transpose with dot products: sum of bit * 2^j over the 8 code bytes */
+    const uint32_t p0 = __builtin_amdgcn_udot4(c4[1] & 0x01010101u, 0x80402010u,
+                        __builtin_amdgcn_udot4(c4[0] & 0x01010101u, 0x08040201u, 0u, false), false);
+    const uint32_t p1 = __builtin_amdgcn_udot4(c4[1] & 0x02020202u, 0x80402010u,
+                        __builtin_amdgcn_udot4(c4[0] & 0x02020202u, 0x08040201u, 0u, false), false);
+    const uint32_t p2 = __builtin_amdgcn_udot4(c4[1] & 0x04040404u, 0x80402010u,
+                        __builtin_amdgcn_udot4(c4[0] & 0x04040404u, 0x08040201u, 0u, false), false);
+    r.b0 = p0;
+    r.b1 = p1 >> 1;
+    r.b2 = p2 >> 2;
+    r.m = ~(r.b0 | r.b1 | r.b2) & 0xFFu;
+    return r;
 }
 
 /*
@@ -202,13 +224,59 @@ __device__ __forceinline__ uint32_t look_back(const uint64_t* state, uint32_t t,
     }
 }
 
+struct CompressShared {
+    uint8_t planes[3][kTile / 8];          /* plane bytes of the tile, natural order */
+    uint8_t esc[kGroupsPerTile][kGroup];   /* zero-point exponents, one region per group */
+    uint32_t gcnt[kGroupsPerTile];         /* zero-points per group */
+    uint32_t goff[kGroupsPerTile];         /* exclusive prefix of gcnt */
+    uint32_t prefix;                       /* zero-points of the chunk before this tile */
+    uint32_t total;                        /* zero-points of this tile */
+};
+
+/* One group of one wave: load, encode, store SM/LO, stage planes and zero-points in LDS. */
+template <int DT, bool FAST, bool STORE>
+__device__ __forceinline__ void compress_group(const uint8_t* __restrict__ cin, uint8_t* __restrict__ slot,
+                                               const SlotLayout& L, uint64_t n, uint64_t ts, uint32_t gi,
+                                               uint32_t k7, uint32_t lane, CompressShared& sh)
+{
+    const uint64_t e = ts + (uint64_t)gi * kGroup + lane * kLaneElems;
+    uint32_t hp[4], lp[4], vmask;
+    load_lane<DT, FAST>(cin, e, n, hp, lp, vmask);
+    const LaneEnc r = encode8(hp, k7);
+    const uint32_t m = r.m & vmask;
+    if (STORE) {
+        if (FAST || e < pad128(n))
+            *reinterpret_cast<uint2*>(slot + L.sm + e) = make_uint2(r.sm0, r.sm1);
+        if (DT == ZIPCCL_FP32) {
+            if (FAST || 2 * e < pad128(2 * n))
+                *reinterpret_cast<uint4*>(slot + L.lo + 2 * e) = make_uint4(lp[0], lp[1], lp[2], lp[3]);
+        }
+        const uint32_t pi = gi * 64u + lane;
+        sh.planes[0][pi] = (uint8_t)r.b0;
+        sh.planes[1][pi] = (uint8_t)r.b1;
+        sh.planes[2][pi] = (uint8_t)r.b2;
+    }
+    const uint32_t cnt = __popc(m);
+    const uint32_t inc = wave_incl_scan(cnt);
+    if (lane == 63) sh.gcnt[gi] = inc;
+    if (STORE) {
+        /* the lane's zero-point exponents, in element order, at its offset inside the group */
+        uint8_t* dst = &sh.esc[gi][inc - cnt];
+        uint32_t mm = m;
+        while (mm) {
+            const uint32_t j = __builtin_ctz(mm);
+            mm &= mm - 1u;
+            *dst++ = (uint8_t)perm(r.ex1, r.ex0, j | 0x0C0C0C00u);
+        }
+    }
+}
+
 template <int DT, int MODE>
 __global__ __launch_bounds__(kThreads) void k_compress(const CompressArgs a)
 {
     constexpr uint32_t ES = DT == ZIPCCL_BF16 ? 2u : 4u;
     constexpr bool STORE = MODE != kModeCount;
-    __shared__ uint32_t s_gcnt[kGroupsPerTile];
-    __shared__ uint32_t s_prefix;
+    __shared__ CompressShared sh;
 
     const uint32_t t = blockIdx.x;
     const uint32_t c = find_chunk(a.tab, t);
@@ -222,82 +290,73 @@ __global__ __launch_bounds__(kThreads) void k_compress(const CompressArgs a)
     const bool fast = (ts + kTile <= n) && ((reinterpret_cast<uintptr_t>(cin) & 15u) == 0);
     const uint32_t lane = lane_id();
     const uint32_t wave = threadIdx.x >> 6;
-    const uint32_t e0m1 = a.e0 - 1u;
+    const uint32_t k7 = ((a.e0 - 1u) << 7) * 0x00010001u;
 
-    uint32_t ex_lo[kGroupsPerWave], ex_hi[kGroupsPerWave], em[kGroupsPerWave], loff[kGroupsPerWave],
-        gtot[kGroupsPerWave];
     if (fast) {
 #pragma unroll
-        for (uint32_t u = 0; u < kGroupsPerWave; ++u) {
-            const uint64_t e = ts + (uint64_t)(u * kWavesPerBlock + wave) * kGroup + lane * kLaneElems;
-            encode_group<DT, true, STORE>(cin, slot, L, n, e, e0m1, lane, ex_lo[u], ex_hi[u], em[u], loff[u], gtot[u]);
-        }
+        for (uint32_t u = 0; u < kGroupsPerWave; ++u)
+            compress_group<DT, true, STORE>(cin, slot, L, n, ts, u * kWavesPerBlock + wave, k7, lane, sh);
     } else {
 #pragma unroll
-        for (uint32_t u = 0; u < kGroupsPerWave; ++u) {
-            const uint64_t e = ts + (uint64_t)(u * kWavesPerBlock + wave) * kGroup + lane * kLaneElems;
-            encode_group<DT, false, STORE>(cin, slot, L, n, e, e0m1, lane, ex_lo[u], ex_hi[u], em[u], loff[u], gtot[u]);
-        }
-    }
-
-    /* tile-level exclusive prefix of the 16 group counts, in element order */
-    if (lane == 0) {
-#pragma unroll
-        for (uint32_t u = 0; u < kGroupsPerWave; ++u) s_gcnt[u * kWavesPerBlock + wave] = gtot[u];
+        for (uint32_t u = 0; u < kGroupsPerWave; ++u)
+            compress_group<DT, false, STORE>(cin, slot, L, n, ts, u * kWavesPerBlock + wave, k7, lane, sh);
     }
     __syncthreads();
-    uint32_t goff[kGroupsPerWave], tile_total = 0;
-#pragma unroll
-    for (uint32_t g = 0; g < kGroupsPerTile; ++g) {
-        if ((g % kWavesPerBlock) == wave) goff[g / kWavesPerBlock] = tile_total;
-        tile_total += s_gcnt[g];
-    }
 
-    if (MODE == kModeCount) {
-        if (threadIdx.x == 0) a.tile_state[t] = tile_total;
-        return;
-    }
-
-    /* chunk-level exclusive prefix P = zero-points of this chunk before this tile */
-    uint32_t P;
-    if (MODE == kModeEmit) {
-        P = (uint32_t)a.tile_state[t];
-    } else {
-        if (wave == 0) {
+    /* wave 0: tile-level prefix of the 16 group counts, then the chunk-level prefix */
+    if (wave == 0) {
+        const uint32_t cnt = lane < kGroupsPerTile ? sh.gcnt[lane] : 0u;
+        const uint32_t inc = row_incl_scan(cnt);
+        const uint32_t tile_total = __builtin_amdgcn_readlane(inc, kGroupsPerTile - 1);
+        if (lane < kGroupsPerTile) sh.goff[lane] = inc - cnt;
+        if (MODE == kModeCount) {
+            if (lane == 0) a.tile_state[t] = tile_total;
+        } else {
             uint32_t p = 0;
-            if (t != first) {
+            if (MODE == kModeEmit) {
+                p = (uint32_t)a.tile_state[t];
+            } else if (t != first) {
                 if (lane == 0) store_state(a.tile_state + t, kFlagAgg | tile_total);
                 p = look_back(a.tile_state, t, first, lane, a.err);
             }
             if (lane == 0) {
-                store_state(a.tile_state + t, kFlagInc | (uint64_t)(p + tile_total));
-                s_prefix = p;
+                if (MODE == kModeFused) store_state(a.tile_state + t, kFlagInc | (uint64_t)(p + tile_total));
+                sh.prefix = p;
+                sh.total = tile_total;
             }
         }
-        __syncthreads();
-        P = s_prefix;
+    } else if (STORE) {
+        /* waves 1..3: one plane each, 16 bytes per lane, while wave 0 resolves the prefix */
+        const uint32_t k = wave - 1u;
+        const uint64_t pb = ts / 8 + lane * 16u;
+        if (fast || pb < L.plane_bytes)
+            *reinterpret_cast<uint4*>(slot + L.p0 + k * L.plane_bytes + pb) =
+                *reinterpret_cast<const uint4*>(&sh.planes[k][lane * 16u]);
     }
+    if (MODE == kModeCount) return;
+    __syncthreads();
 
-    /* group index (section 4.2.3) and zero-point exponents in element order */
+    const uint32_t P = sh.prefix;
     const uint64_t ng = (n + kGroup - 1) / kGroup;
     uint32_t* __restrict__ idx = reinterpret_cast<uint32_t*>(slot + L.idx);
     uint8_t* __restrict__ esc = slot + L.esc;
+
+    /* group index (section 4.2.3) */
+    if (wave == 0 && lane < kGroupsPerTile) {
+        const uint64_t g = ts / kGroup + lane;
+        if (g < ng) idx[g] = P + sh.goff[lane];
+    }
+    /* zero-point exponents: every wave copies the segments of its own groups */
 #pragma unroll
     for (uint32_t u = 0; u < kGroupsPerWave; ++u) {
-        const uint64_t g = ts / kGroup + (u * kWavesPerBlock + wave);
-        if (lane == 0 && g < ng) idx[g] = P + goff[u];
-        uint8_t* dst = esc + (uint64_t)P + goff[u] + loff[u];
-        uint32_t mm = em[u];
-        const uint64_t ex = (uint64_t)ex_lo[u] | ((uint64_t)ex_hi[u] << 32);
-        while (mm) {
-            const uint32_t j = __builtin_ctz(mm);
-            mm &= mm - 1u;
-            *dst++ = (uint8_t)(ex >> (8 * j));
-        }
+        const uint32_t gi = u * kWavesPerBlock + wave;
+        const uint32_t cnt = sh.gcnt[gi];
+        uint8_t* dst = esc + (uint64_t)P + sh.goff[gi];
+        for (uint32_t i = lane; i < cnt; i += 64u) dst[i] = sh.esc[gi][i];
     }
 
     if (last_tile) {
-        const uint64_t n_esc = (uint64_t)P + tile_total;
+        const uint64_t n_esc = (uint64_t)P + sh.total;
         const uint64_t cbytes = L.esc + pad128(n_esc);
         if (threadIdx.x < 32) {
             uint32_t w = 0;
@@ -352,10 +411,32 @@ __global__ __launch_bounds__(kThreads) void k_tile_scan(const CompressArgs a)
         }
 }
 
+/*
+ * Decoder tables in LDS, indexed by a 4-bit zero-point mask q of four values:
+ * .x = v_perm selector putting the r-th byte of a compacted list at the position of the r-th
+ * set bit of q (0x0c = constant 0 elsewhere), .y = 0xff in the bytes of set bits.
+ */
+__device__ __forceinline__ uint2 expand_entry(uint32_t q)
+{
+    uint32_t sel = 0, msk = 0, r = 0;
+#pragma unroll
+    for (uint32_t i = 0; i < 4; ++i) {
+        if ((q >> i) & 1u) { sel |= r << (8 * i); msk |= 0xFFu << (8 * i); ++r; }
+        else sel |= 0x0Cu << (8 * i);
+    }
+    return make_uint2(sel, msk);
+}
+
+/* bits 0..3 of x -> bit 0 of bytes 0..3 */
+__device__ __forceinline__ uint32_t spread4(uint32_t x)
+{
+    return __umul24(x, 0x204081u) & 0x01010101u;
+}
+
 template <int DT, bool FAST>
 __device__ __forceinline__ bool decode_group(const uint8_t* __restrict__ slot, uint8_t* __restrict__ cout,
-                                             const SlotLayout& L, uint64_t n, uint64_t n_esc, uint64_t gstart,
-                                             uint32_t e0, uint32_t lane)
+                                             const SlotLayout& L, uint64_t n, uint32_t n_esc, uint64_t gstart,
+                                             uint32_t e0, uint32_t lane, const uint2* __restrict__ lut)
 {
     const uint64_t e = gstart + lane * kLaneElems;
     uint2 sm = make_uint2(0, 0);
@@ -376,24 +457,46 @@ __device__ __forceinline__ bool decode_group(const uint8_t* __restrict__ slot, u
     if (!FAST) vmask = e >= n ? 0u : (n - e >= 8 ? 0xFFu : ((1u << (uint32_t)(n - e)) - 1u));
     const uint32_t m = ~(b0 | b1 | b2) & vmask;    /* code 0 = zero-point; tail bits are not */
     const uint32_t cnt = __popc(m);
-    const uint32_t inc = wave_incl_scan(cnt, lane);
-    uint64_t pos = (uint64_t)base + (inc - cnt);
-    const uint8_t* __restrict__ esc = slot + L.esc;
+    const uint32_t inc = wave_incl_scan(cnt);
+    const uint32_t gtot = __builtin_amdgcn_readlane(inc, 63);
+
+    /* code bytes of values 0..3 and 4..7, then exponent = dec[1] - 1 + code */
+    const uint32_t k4 = (e0 - 1u) * 0x01010101u;
+    uint32_t eA = (spread4(b0 & 15u) | (spread4(b1 & 15u) << 1) | (spread4(b2 & 15u) << 2)) + k4;
+    uint32_t eB = (spread4(b0 >> 4) | (spread4(b1 >> 4) << 1) | (spread4(b2 >> 4) << 2)) + k4;
+
     bool bad = false;
-    uint32_t hp[4] = {0, 0, 0, 0};
-    const uint32_t smw[2] = {sm.x, sm.y};
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const uint32_t code = ((b0 >> j) & 1u) | (((b1 >> j) & 1u) << 1) | (((b2 >> j) & 1u) << 2);
-        uint32_t E = e0 + code - 1u;
-        if ((m >> j) & 1u) {
-            if (pos < n_esc) E = esc[pos]; else { bad = true; E = 0; }
-            ++pos;
+    if (gtot != 0u) {
+        /* the lane's zero-point exponents are the bytes [pos, pos + cnt) of the list */
+        const uint32_t loff = inc - cnt;
+        const bool base_ok = base <= n_esc;
+        const uint32_t room = base_ok ? n_esc - base : 0u;
+        const bool lane_ok = loff + cnt <= room;
+        bad = !lane_ok && cnt != 0u;
+        if (n_esc != 0u) {
+            const uint32_t pos = lane_ok ? base + loff : 0u;
+            const uint32_t last = (n_esc - 1u) & ~3u;        /* last aligned word holding a list byte */
+            const uint32_t a0 = pos & ~3u;
+            const uint32_t* __restrict__ esc32 = reinterpret_cast<const uint32_t*>(slot + L.esc);
+            const uint32_t d0 = esc32[min(a0, last) >> 2];
+            const uint32_t d1 = esc32[min(a0 + 4u, last) >> 2];
+            const uint32_t d2 = esc32[min(a0 + 8u, last) >> 2];
+            const uint32_t l8 = __builtin_amdgcn_alignbyte(d1, d0, pos & 3u);
+            const uint32_t h8 = __builtin_amdgcn_alignbyte(d2, d1, pos & 3u);
+            const uint32_t mA = m & 15u, mB = m >> 4;
+            const uint32_t nA = __popc(mA);
+            const uint2 tA = lut[mA], tB = lut[mB];
+            const uint32_t xB = nA == 4u ? h8 : __builtin_amdgcn_alignbyte(h8, l8, nA);
+            eA = bfi(tA.y, perm(0u, l8, tA.x), eA);
+            eB = bfi(tB.y, perm(0u, xB, tB.x), eB);
         }
-        const uint32_t s = (smw[j >> 2] >> (8 * (j & 3))) & 0xFFu;
-        const uint32_t h = ((s & 0x80u) << 8) | ((E & 0xFFu) << 7) | (s & 0x7Fu);
-        hp[j >> 1] |= h << (16 * (j & 1));
     }
+
+    /* recombine with sign and mantissa: low byte = mantissa | E bit 0 << 7, high = sign | E >> 1 */
+    const uint32_t lA = bfi(0x7F7F7F7Fu, sm.x, eA << 7), hA = bfi(0x80808080u, sm.x, eA >> 1);
+    const uint32_t lB = bfi(0x7F7F7F7Fu, sm.y, eB << 7), hB = bfi(0x80808080u, sm.y, eB >> 1);
+    const uint32_t hp[4] = {perm(hA, lA, 0x05010400u), perm(hA, lA, 0x07030602u),
+                            perm(hB, lB, 0x05010400u), perm(hB, lB, 0x07030602u)};
     const uint32_t low[4] = {lo.x, lo.y, lo.z, lo.w};
     if (FAST) {
         if (DT == ZIPCCL_BF16) {
@@ -402,8 +505,8 @@ __device__ __forceinline__ bool decode_group(const uint8_t* __restrict__ slot, u
             uint32_t x[8];
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                x[2 * k] = (hp[k] << 16) | (low[k] & 0xFFFFu);
-                x[2 * k + 1] = (hp[k] & 0xFFFF0000u) | (low[k] >> 16);
+                x[2 * k] = perm(hp[k], low[k], 0x05040100u);
+                x[2 * k + 1] = perm(hp[k], low[k], 0x07060302u);
             }
             *reinterpret_cast<uint4*>(cout + e * 4) = make_uint4(x[0], x[1], x[2], x[3]);
             *reinterpret_cast<uint4*>(cout + e * 4 + 16) = make_uint4(x[4], x[5], x[6], x[7]);
@@ -429,6 +532,9 @@ template <int DT>
 __global__ __launch_bounds__(kThreads) void k_decompress(const DecompressArgs a)
 {
     constexpr uint32_t ES = DT == ZIPCCL_BF16 ? 2u : 4u;
+    __shared__ uint2 s_lut[16];
+    if (threadIdx.x < 16) s_lut[threadIdx.x] = expand_entry(threadIdx.x);
+
     const uint32_t t = blockIdx.x;
     const uint32_t c = find_chunk(a.tab, t);
     const uint64_t n = a.tab.elem_off[c + 1] - a.tab.elem_off[c];
@@ -447,8 +553,9 @@ __global__ __launch_bounds__(kThreads) void k_decompress(const DecompressArgs a)
     bool ok = hw[0] == kMagic && hw[1] == kVersion && hw[2] == (uint32_t)DT && hw[3] == kGroup;
     ok = ok && n_hdr == n && n_esc <= n && cbytes == L.esc + pad128(n_esc);
     ok = ok && a.tab.slot_off[c] + cbytes <= a.comp_capacity;
-    ok = ok && e0 <= 249u && (dec_lo >> 8) == (e0 | ((e0 + 1u) << 8) | ((e0 + 2u) << 16)) &&
+    ok = ok && e0 >= 1u && e0 <= 249u && (dec_lo >> 8) == (e0 | ((e0 + 1u) << 8) | ((e0 + 2u) << 16)) &&
          dec_hi == ((e0 + 3u) | ((e0 + 4u) << 8) | ((e0 + 5u) << 16) | ((e0 + 6u) << 24));
+    __syncthreads();
     if (!ok) {
         if (threadIdx.x == 0 && a.status) atomicOr(a.status, (uint32_t)ZIPCCL_ERR_CORRUPT);
         return;
@@ -462,12 +569,12 @@ __global__ __launch_bounds__(kThreads) void k_decompress(const DecompressArgs a)
 #pragma unroll
         for (uint32_t u = 0; u < kGroupsPerWave; ++u) {
             const uint64_t gstart = ts + (uint64_t)(u * kWavesPerBlock + wave) * kGroup;
-            bad |= decode_group<DT, true>(slot, cout, L, n, n_esc, gstart, e0, lane);
+            bad |= decode_group<DT, true>(slot, cout, L, n, (uint32_t)n_esc, gstart, e0, lane, s_lut);
         }
     } else {
         for (uint32_t u = 0; u < kGroupsPerWave; ++u) {
             const uint64_t gstart = ts + (uint64_t)(u * kWavesPerBlock + wave) * kGroup;
-            if (gstart < n) bad |= decode_group<DT, false>(slot, cout, L, n, n_esc, gstart, e0, lane);
+            if (gstart < n) bad |= decode_group<DT, false>(slot, cout, L, n, (uint32_t)n_esc, gstart, e0, lane, s_lut);
         }
     }
     if (bad && a.status) atomicOr(a.status, (uint32_t)ZIPCCL_ERR_CORRUPT);
