@@ -62,32 +62,54 @@ uint32_t fill_tab(ChunkTab& tab, const std::vector<uint64_t>& ce, const std::vec
 {
     tab.n_chunks = nb;
     uint64_t eoff = 0;
-    uint32_t tiles = 0;
+    uint32_t tiles = 0, blks = 0, sups = 0;
     for (uint32_t i = 0; i < nb; ++i) {
         tab.tile_start[i] = tiles;
+        tab.blk_start[i] = blks;
+        tab.sup_start[i] = sups;
         tab.elem_off[i] = eoff;
         tab.slot_off[i] = slot_off[c0 + i] - slot_off[c0];
         tiles += (uint32_t)tiles_of(ce[c0 + i]);
+        blks += (uint32_t)blocks_of(ce[c0 + i]);
+        sups += (uint32_t)supers_of(ce[c0 + i]);
         eoff += ce[c0 + i];
     }
-    tab.tile_start[nb] = tiles;
-    tab.elem_off[nb] = eoff;
-    tab.slot_off[nb] = slot_off[c0 + nb] - slot_off[c0];
-    for (uint32_t i = nb + 1; i <= kMaxBatch; ++i) {
+    for (uint32_t i = nb; i <= kMaxBatch; ++i) {
         tab.tile_start[i] = tiles;
+        tab.blk_start[i] = blks;
+        tab.sup_start[i] = sups;
         tab.elem_off[i] = eoff;
-        tab.slot_off[i] = tab.slot_off[nb];
+        tab.slot_off[i] = slot_off[c0 + nb] - slot_off[c0];
     }
     (void)dt;
     return tiles;
 }
 
-/* Total tiles of the call; 0 if it exceeds what one call supports. */
 uint64_t total_tiles(const std::vector<uint64_t>& ce)
 {
     uint64_t t = 0;
     for (uint64_t n : ce) t += tiles_of(n);
     return t;
+}
+
+/* Workspace layout: header | u32 per super-block | u32 per tile | u32 per block (8-byte aligned parts). */
+struct WorkspacePlan {
+    uint64_t tiles, blocks, supers, sup_off, tile_off, blk_off, bytes;
+};
+
+WorkspacePlan plan_workspace(const std::vector<uint64_t>& ce)
+{
+    WorkspacePlan w{};
+    for (uint64_t n : ce) {
+        w.tiles += tiles_of(n);
+        w.blocks += blocks_of(n);
+        w.supers += supers_of(n);
+    }
+    w.sup_off = kWorkspaceHeader;
+    w.tile_off = w.sup_off + ((4 * w.supers + 7) & ~7ull);
+    w.blk_off = w.tile_off + ((4 * w.tiles + 7) & ~7ull);
+    w.bytes = w.blk_off + ((4 * w.blocks + 7) & ~7ull);
+    return w;
 }
 
 /* 0 = fused single kernel, 1 = three kernels (count, scan, emit); see zipccl_debug_compress_path */
@@ -151,7 +173,7 @@ size_t zipccl_compress_workspace_size(size_t n_elems, zipccl_dtype_t dt, uint32_
     if (!dtype_ok(dt)) return 0;
     std::vector<uint64_t> ce;
     if (!resolve_split(n_elems, n_chunks, chunk_elems, ce)) return 0;
-    return (size_t)(kWorkspaceHeader + 8 * total_tiles(ce));
+    return (size_t)plan_workspace(ce).bytes;
 }
 
 zipccl_status_t zipccl_compress(const void* d_in, size_t n_elems, zipccl_dtype_t dt,
@@ -177,9 +199,9 @@ zipccl_status_t zipccl_compress(const void* d_in, size_t n_elems, zipccl_dtype_t
     }
     slot_off[n_chunks] = off;
     if (off > out_capacity) return ZIPCCL_ERR_BUFFER_TOO_SMALL;
-    const uint64_t tiles = total_tiles(ce);
-    if (tiles > 0x7FFFFFFFull) return ZIPCCL_ERR_INVALID_ARG;
-    const uint64_t ws_need = kWorkspaceHeader + 8 * tiles;
+    const WorkspacePlan wp = plan_workspace(ce);
+    if (wp.tiles > 0x7FFFFFFFull) return ZIPCCL_ERR_INVALID_ARG;
+    const uint64_t ws_need = wp.bytes;
     if (ws_need > workspace_bytes) return ZIPCCL_ERR_BUFFER_TOO_SMALL;
 
     /* tile states must start as "not published"; the status word as 0 */
@@ -192,14 +214,17 @@ zipccl_status_t zipccl_compress(const void* d_in, size_t n_elems, zipccl_dtype_t
     a.e0 = table->dec[1];
     std::memcpy(&a.dec_lo, table->dec, 4);
     std::memcpy(&a.dec_hi, table->dec + 4, 4);
-    uint64_t elem_base = 0, tile_base = 0;
+    uint64_t elem_base = 0, tile_base = 0, blk_base = 0, sup_base = 0;
+    uint8_t* const ws = static_cast<uint8_t*>(d_workspace);
     for (uint32_t c0 = 0; c0 < n_chunks; c0 += kMaxBatch) {
         const uint32_t nb = (n_chunks - c0) < kMaxBatch ? (n_chunks - c0) : kMaxBatch;
         const uint32_t nt = fill_tab(a.tab, ce, slot_off, c0, nb, dt);
         a.in = static_cast<const uint8_t*>(d_in) + elem_base * es;
         a.out = static_cast<uint8_t*>(d_out) + slot_off[c0];
         a.chunk_bytes = d_chunk_bytes ? d_chunk_bytes + c0 : nullptr;
-        a.tile_state = reinterpret_cast<uint64_t*>(static_cast<uint8_t*>(d_workspace) + kWorkspaceHeader) + tile_base;
+        a.sup_state = reinterpret_cast<uint32_t*>(ws + wp.sup_off) + sup_base;
+        a.tile_state = reinterpret_cast<uint32_t*>(ws + wp.tile_off) + tile_base;
+        a.blk_state = reinterpret_cast<uint32_t*>(ws + wp.blk_off) + blk_base;
         if (mode == kModeFused) {
             if (launch_compress(dt, kModeFused, a, nt, stream) != 0) return ZIPCCL_ERR_DEVICE;
         } else {
@@ -209,6 +234,8 @@ zipccl_status_t zipccl_compress(const void* d_in, size_t n_elems, zipccl_dtype_t
         }
         elem_base += a.tab.elem_off[nb];
         tile_base += nt;
+        blk_base += a.tab.blk_start[nb];
+        sup_base += a.tab.sup_start[nb];
     }
     return ZIPCCL_OK;
 }

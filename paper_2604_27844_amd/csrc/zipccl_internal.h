@@ -25,7 +25,9 @@ constexpr uint32_t kTile = kGroup * kGroupsPerTile; /* 8192 elements */
 constexpr uint32_t kMaxBatch = 128;                 /* chunks per kernel launch */
 constexpr uint32_t kVersion = 1;
 constexpr uint32_t kMagic = 0x4C43505Au;            /* "ZPCL" little-endian */
-constexpr uint32_t kWorkspaceHeader = 256;          /* bytes before the tile status array */
+constexpr uint32_t kWorkspaceHeader = 256;          /* bytes before the scan state arrays */
+constexpr uint32_t kTilesPerBlock = 64;             /* scan hierarchy: 64 tiles = 1 block, 64 blocks = 1 super-block */
+constexpr uint32_t kTilesPerSuper = 64 * 64;
 
 /* header field offsets */
 constexpr uint32_t kHdrMagic = 0, kHdrVersion = 4, kHdrDtype = 8, kHdrGroup = 12, kHdrN = 16,
@@ -53,11 +55,15 @@ ZIPCCL_HD SlotLayout slot_layout(uint64_t n, int dt)
 }
 
 ZIPCCL_HD uint64_t tiles_of(uint64_t n) { return n == 0 ? 1 : (n + kTile - 1) / kTile; }
+ZIPCCL_HD uint64_t blocks_of(uint64_t n) { return (tiles_of(n) + kTilesPerBlock - 1) / kTilesPerBlock; }
+ZIPCCL_HD uint64_t supers_of(uint64_t n) { return (tiles_of(n) + kTilesPerSuper - 1) / kTilesPerSuper; }
 
 /* Per-launch chunk table, passed by value in the kernel argument segment. */
 struct ChunkTab {
     uint32_t n_chunks;
     uint32_t tile_start[kMaxBatch + 1]; /* first tile of chunk c in this launch */
+    uint32_t blk_start[kMaxBatch + 1];  /* first scan block (64 tiles, never spanning chunks) of chunk c */
+    uint32_t sup_start[kMaxBatch + 1];  /* first scan super-block (64 blocks) of chunk c */
     uint64_t elem_off[kMaxBatch + 1];   /* first element of chunk c, relative to the launch's input */
     uint64_t slot_off[kMaxBatch + 1];   /* byte offset of slot c, relative to the launch's output */
 };
@@ -66,7 +72,9 @@ struct CompressArgs {
     const uint8_t* in;       /* first element of the launch's first chunk */
     uint8_t* out;            /* compressed buffer base for this launch */
     uint64_t* chunk_bytes;   /* entry of the launch's first chunk, or null */
-    uint64_t* tile_state;    /* one u64 per tile of this launch */
+    uint32_t* tile_state;    /* one u32 per tile of this launch */
+    uint32_t* blk_state;     /* one u32 per scan block of this launch */
+    uint32_t* sup_state;     /* one u32 per scan super-block of this launch */
     uint32_t* err;           /* workspace status word */
     uint32_t e0;             /* dec[1] */
     uint32_t dec_lo, dec_hi; /* dec[0..3], dec[4..7] packed little-endian */

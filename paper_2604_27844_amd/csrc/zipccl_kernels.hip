@@ -10,8 +10,8 @@
  *              Plane bytes and zero-point exponents are staged in LDS and leave as wide
  *              stores.  The zero-point offsets of section 4.2.3 are an exclusive prefix in
  *              element order (lane -> wave -> tile -> chunk), so the output is deterministic;
- *              the chunk-wide part is a decoupled look-back over per-tile state words instead
- *              of the paper's block-level atomic add.
+ *              the chunk-wide part reads published per-tile / per-block count words instead of
+ *              the paper's block-level atomic add.
  * decompress : section 4, third paragraph.  No dependency between workgroups.
  *
  * Everything is integer work; sigma / erf live on the host.
@@ -23,9 +23,8 @@
 namespace zipccl {
 namespace {
 
-constexpr uint64_t kFlagAgg = 1ull << 32;  /* tile state: low 32 bits = this tile's zero-point count */
-constexpr uint64_t kFlagInc = 2ull << 32;  /* tile state: low 32 bits = count of this and all earlier tiles of the chunk */
-constexpr uint32_t kSpinLimit = 1u << 22;  /* polls before the look-back gives up and flags an error */
+constexpr uint32_t kValid = 1u << 31;      /* scan state word: bit 31 = published, low bits = a zero-point count */
+constexpr uint32_t kSpinLimit = 1u << 22;  /* polls before the scan wait gives up and flags an error */
 
 typedef unsigned short us2 __attribute__((ext_vector_type(2)));
 
@@ -87,11 +86,8 @@ __device__ __forceinline__ uint32_t find_chunk(const ChunkTab& tab, uint32_t t)
     return lo;
 }
 
-__device__ __forceinline__ void store_state(uint64_t* p, uint64_t v)
-{
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ uint64_t load_state(const uint64_t* p)
+template <typename T>
+__device__ __forceinline__ T load_agent(const T* p)
 {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
@@ -190,38 +186,66 @@ __device__ __forceinline__ LaneEnc encode8(const uint32_t w[4], uint32_t k7)
     return r;
 }
 
-/*
- * Decoupled look-back (run by one wave): sum of the zero-point counts of tiles [first, t).
- * Lane i inspects tile t-1-i; a tile state is 0 (not yet published), an aggregate, or an
- * inclusive prefix.  Tiles before `first` count as an inclusive prefix of 0.  The wait is
- * bounded: past kSpinLimit polls the error word is set and the result is unspecified.
- */
-__device__ __forceinline__ uint32_t look_back(const uint64_t* state, uint32_t t, uint32_t first,
-                                              uint32_t lane, uint32_t* err)
+/* Sum of `count` published state words state[0..count) (count <= 64), or false if one is missing. */
+__device__ __forceinline__ bool window_sum(const uint32_t* state, uint32_t count, uint32_t lane, uint32_t& sum)
 {
-    uint32_t prefix = 0, spins = 0;
-    int64_t look = (int64_t)t - 1;
+    uint32_t v = kValid;
+    if (lane < count) v = load_agent(state + lane);
+    if (__ballot((v & kValid) == 0u) != 0ull) return false;
+    sum = wave_sum(v & ~kValid);
+    return true;
+}
+
+/*
+ * Chunk-wide exclusive prefix of the per-tile zero-point counts (section 4.2.3's "global"
+ * level), run by one wave of tile `ti` (index inside its chunk, workgroup id t) after it has
+ * published its own count `own`.  Tiles form blocks of 64 and super-blocks of 64 blocks, never
+ * spanning chunks.  The prefix is
+ *   (tiles before ti in its block) + (blocks before it in its super-block) + (super-blocks before),
+ * three independent reads of at most 64 state words each.  The last tile of a block publishes
+ * the block's sum (its own first term + its count), the last tile of a super-block the
+ * super-block's sum, so no state word depends on a chain of earlier waits and a tile needs at
+ * most three memory round trips after its predecessors have counted, whatever the chunk size.
+ * Only plain stores and loads at device scope are used (read-modify-write atomics on shared
+ * counters serialise badly across the chip).  Predecessors have lower workgroup ids, so they
+ * are already running.  The wait is bounded: past kSpinLimit polls the error word is set and
+ * the result is unspecified.
+ */
+__device__ __forceinline__ uint32_t chunk_prefix(uint32_t* tile_state, uint32_t* blk_state, uint32_t* sup_state,
+                                                 uint32_t t, uint32_t ti, uint32_t own, uint32_t lane, uint32_t* err)
+{
+    const uint32_t j = ti % kTilesPerBlock;            /* tiles before this one in its block */
+    const uint32_t bi = ti / kTilesPerBlock;           /* its block, counted inside the chunk */
+    const uint32_t b = bi % 64u;                       /* blocks before its block in its super-block */
+    const uint32_t s = ti / kTilesPerSuper;            /* super-blocks before its super-block */
+    uint32_t s0 = 0, s1 = 0, s2 = 0, spins = 0;
+    bool ok0 = false, ok1 = false, ok2 = false;
     for (;;) {
-        const int64_t i = look - (int64_t)lane;
-        uint64_t s = kFlagInc; /* before the chunk's first tile: nothing */
-        if (i >= (int64_t)first) s = load_state(state + i);
-        const uint32_t flag = (uint32_t)(s >> 32);
-        const uint64_t invalid = __ballot(flag == 0u);
-        const uint64_t incl = __ballot(flag == 2u);
-        const uint32_t j = incl ? (uint32_t)__builtin_ctzll(incl) : 64u; /* nearest inclusive */
-        const uint64_t need = j >= 63u ? ~0ull : ((2ull << j) - 1ull);   /* lanes 0..j */
-        if (invalid & need) {
-            if (++spins > kSpinLimit) {
-                if (lane == 0) atomicOr(err, (uint32_t)ZIPCCL_ERR_DEVICE);
-                return prefix;
-            }
-            __builtin_amdgcn_s_sleep(1);
-            continue;
+        if (!ok0 && window_sum(tile_state + (t - j), j, lane, s0)) {
+            ok0 = true;
+            if (j == kTilesPerBlock - 1u && lane == 0)
+                __hip_atomic_store(blk_state + bi, kValid | (s0 + own), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
-        prefix += wave_sum(lane <= j ? (uint32_t)s : 0u);
-        if (j < 64u) return prefix;
-        look -= 64;
+        if (!ok1 && window_sum(blk_state + (bi - b), b, lane, s1)) ok1 = true;
+        if (!ok2) {
+            uint32_t acc = 0, part = 0;
+            bool all = true;
+            for (uint32_t w = 0; w < s && all; w += 64u) {   /* more than 64 only for chunks past 2^31 values */
+                all = window_sum(sup_state + w, s - w < 64u ? s - w : 64u, lane, part);
+                acc += part;
+            }
+            if (all) { ok2 = true; s2 = acc; }
+        }
+        if (ok0 && ok1 && ok2) break;
+        if (++spins > kSpinLimit) {
+            if (lane == 0) atomicOr(err, (uint32_t)ZIPCCL_ERR_DEVICE);
+            return 0;
+        }
+        __builtin_amdgcn_s_sleep(1);
     }
+    if (ti % kTilesPerSuper == kTilesPerSuper - 1u && lane == 0)
+        __hip_atomic_store(sup_state + s, kValid | (s0 + s1 + own), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return s0 + s1 + s2;
 }
 
 struct CompressShared {
@@ -314,13 +338,16 @@ __global__ __launch_bounds__(kThreads) void k_compress(const CompressArgs a)
         } else {
             uint32_t p = 0;
             if (MODE == kModeEmit) {
-                p = (uint32_t)a.tile_state[t];
-            } else if (t != first) {
-                if (lane == 0) store_state(a.tile_state + t, kFlagAgg | tile_total);
-                p = look_back(a.tile_state, t, first, lane, a.err);
+                p = a.tile_state[t];
+            } else {
+                const uint32_t ti = t - first;
+                if (lane == 0)
+                    __hip_atomic_store(a.tile_state + t, kValid | tile_total, __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+                p = chunk_prefix(a.tile_state, a.blk_state + a.tab.blk_start[c], a.sup_state + a.tab.sup_start[c],
+                                 t, ti, tile_total, lane, a.err);
             }
             if (lane == 0) {
-                if (MODE == kModeFused) store_state(a.tile_state + t, kFlagInc | (uint64_t)(p + tile_total));
                 sh.prefix = p;
                 sh.total = tile_total;
             }
@@ -398,14 +425,14 @@ __global__ __launch_bounds__(kThreads) void k_tile_scan(const CompressArgs a)
     const uint32_t b = first + threadIdx.x * per;
     uint32_t sum = 0;
     for (uint32_t i = 0; i < per; ++i)
-        if (b + i < end) sum += (uint32_t)a.tile_state[b + i];
+        if (b + i < end) sum += a.tile_state[b + i];
     s_part[threadIdx.x] = sum;
     __syncthreads();
     uint32_t run = 0;
     for (uint32_t i = 0; i < threadIdx.x; ++i) run += s_part[i];
     for (uint32_t i = 0; i < per; ++i)
         if (b + i < end) {
-            const uint32_t v = (uint32_t)a.tile_state[b + i];
+            const uint32_t v = a.tile_state[b + i];
             a.tile_state[b + i] = run;
             run += v;
         }

@@ -61,8 +61,10 @@ def test_sizes_and_offsets_match_oracle():
     assert z.zipccl_max_compressed_size(10, z.BF16, 0) == 0
     assert z.zipccl_max_compressed_size(10, z.BF16, 2, [4, 5]) == 0       # must sum to n
     assert z.zipccl_max_compressed_size(10, 5, 1) == 0
-    assert z.zipccl_compress_workspace_size(8192 * 3 + 1, z.BF16, 1) == 256 + 8 * 4
-    assert z.zipccl_compress_workspace_size(0, z.BF16, 2, [0, 0]) == 256 + 8 * 2
+    # header + u32 per super-block + u32 per tile + u32 per block (each part padded to 8 bytes)
+    assert z.zipccl_compress_workspace_size(8192 * 3 + 1, z.BF16, 1) == 256 + 8 + 4 * 4 + 8
+    assert z.zipccl_compress_workspace_size(0, z.BF16, 2, [0, 0]) == 256 + 8 + 8 + 8
+    assert z.zipccl_compress_workspace_size(8192 * 4096 * 2, z.BF16, 2) == 256 + 8 + 4 * 8192 + 4 * 128
 
 
 def test_argument_errors_return_before_any_launch():
