@@ -91,10 +91,15 @@ size_t zipccl_max_compressed_size(size_t n_elems, zipccl_dtype_t dt, uint32_t n_
 zipccl_status_t zipccl_chunk_slot_offsets(size_t n_elems, zipccl_dtype_t dt, uint32_t n_chunks,
                                           const uint64_t* chunk_elems, uint64_t* slot_off);
 
-/* Bytes of device scratch zipccl_compress needs for this split (tile scan state of the
- * chunk-wide zero-point prefix, section 4.2.3).  Returns 0 on invalid arguments. */
+/* Bytes of device scratch for zipccl_compress.  With zipccl_compress_workspace_size bytes
+ * (about one byte per element) compress reads the input once: zero-point exponents are parked
+ * in the scratch until the per-chunk prefix of section 4.2.3 is known.  With less, but at least
+ * zipccl_compress_min_workspace_size bytes (8 bytes per 8192 elements), it reads the input twice.
+ * Both return 0 on invalid arguments. */
 size_t zipccl_compress_workspace_size(size_t n_elems, zipccl_dtype_t dt, uint32_t n_chunks,
                                       const uint64_t* chunk_elems);
+size_t zipccl_compress_min_workspace_size(size_t n_elems, zipccl_dtype_t dt, uint32_t n_chunks,
+                                          const uint64_t* chunk_elems);
 
 /*
  * Compress (section 4, second paragraph; kernel steps of section 4.2).
@@ -103,11 +108,11 @@ size_t zipccl_compress_workspace_size(size_t n_elems, zipccl_dtype_t dt, uint32_
  *   table           host, from zipccl_build_table
  *   d_out           device, 128-byte aligned, out_capacity >= zipccl_max_compressed_size(...)
  *   d_chunk_bytes   device, n_chunks u64, may be NULL: bytes to transmit for each chunk
- *   d_workspace     device, 8-byte aligned, workspace_bytes >= zipccl_compress_workspace_size(...);
- *                   contents are overwritten; after the call has completed on the stream its
- *                   first u32 is 0 on success (nonzero: the scan's bounded wait gave up)
+ *   d_workspace     device, 16-byte aligned, workspace_bytes >= zipccl_compress_min_workspace_size(...)
+ *                   (see above for what more buys); contents are overwritten
  * Every byte of [slot_off[c], slot_off[c] + chunk_bytes[c]) is written; the rest of a slot is
- * left untouched.  Calls on different streams need different workspaces.
+ * left untouched.  No kernel waits on another workgroup.  Calls that may overlap in time need
+ * different workspaces.
  */
 zipccl_status_t zipccl_compress(const void* d_in, size_t n_elems, zipccl_dtype_t dt,
                                 uint32_t n_chunks, const uint64_t* chunk_elems,
@@ -137,9 +142,8 @@ zipccl_status_t zipccl_decompress(const void* d_comp, size_t comp_capacity,
 const char* zipccl_status_string(zipccl_status_t s);
 
 /*
- * Diagnostic switch, process-wide: path = 0 selects the single fused compress kernel (the
- * default; chunk-wide zero-point prefix by look-back across tiles), path = 1 the three-kernel
- * form (count, scan, emit) that reads the input twice and never waits on another workgroup.
+ * Diagnostic switch, process-wide: path = 0 (default) lets zipccl_compress use the single-pass
+ * form when the workspace allows it, path = 1 forces the form that reads the input twice.
  * Both produce identical bytes.  The environment variable ZIPCCL_COMPRESS_PATH=3pass sets the
  * initial value to 1.  Returns the previous value; any other argument only queries.
  */

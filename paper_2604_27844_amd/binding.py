@@ -48,6 +48,8 @@ def _load():
     lib.zipccl_chunk_slot_offsets.argtypes = [sz, i32, u32, vp, vp]
     lib.zipccl_compress_workspace_size.restype = sz
     lib.zipccl_compress_workspace_size.argtypes = [sz, i32, u32, vp]
+    lib.zipccl_compress_min_workspace_size.restype = sz
+    lib.zipccl_compress_min_workspace_size.argtypes = [sz, i32, u32, vp]
     lib.zipccl_compress.restype = i32
     lib.zipccl_compress.argtypes = [vp, sz, i32, u32, vp, tp, vp, sz, vp, vp, sz, vp]
     lib.zipccl_decompress.restype = i32
@@ -61,7 +63,7 @@ def _load():
 
 _lib = _load()
 EXPORTS = ("zipccl_build_table", "zipccl_max_compressed_size", "zipccl_chunk_slot_offsets",
-           "zipccl_compress_workspace_size", "zipccl_compress", "zipccl_decompress", "zipccl_status_string",
+           "zipccl_compress_workspace_size", "zipccl_compress_min_workspace_size", "zipccl_compress", "zipccl_decompress", "zipccl_status_string",
            "zipccl_debug_compress_path")
 
 
@@ -121,6 +123,11 @@ def zipccl_chunk_slot_offsets(n_elems, dt, n_chunks=1, chunk_elems=None):
 def zipccl_compress_workspace_size(n_elems, dt, n_chunks=1, chunk_elems=None):
     _keep, p = _host_u64(chunk_elems)
     return int(_lib.zipccl_compress_workspace_size(int(n_elems), dt, int(n_chunks), p))
+
+
+def zipccl_compress_min_workspace_size(n_elems, dt, n_chunks=1, chunk_elems=None):
+    _keep, p = _host_u64(chunk_elems)
+    return int(_lib.zipccl_compress_min_workspace_size(int(n_elems), dt, int(n_chunks), p))
 
 
 def zipccl_compress(d_in, n_elems, dt, n_chunks, chunk_elems, table, d_out, d_chunk_bytes, d_workspace,

@@ -62,22 +62,16 @@ uint32_t fill_tab(ChunkTab& tab, const std::vector<uint64_t>& ce, const std::vec
 {
     tab.n_chunks = nb;
     uint64_t eoff = 0;
-    uint32_t tiles = 0, blks = 0, sups = 0;
+    uint32_t tiles = 0;
     for (uint32_t i = 0; i < nb; ++i) {
         tab.tile_start[i] = tiles;
-        tab.blk_start[i] = blks;
-        tab.sup_start[i] = sups;
         tab.elem_off[i] = eoff;
         tab.slot_off[i] = slot_off[c0 + i] - slot_off[c0];
         tiles += (uint32_t)tiles_of(ce[c0 + i]);
-        blks += (uint32_t)blocks_of(ce[c0 + i]);
-        sups += (uint32_t)supers_of(ce[c0 + i]);
         eoff += ce[c0 + i];
     }
     for (uint32_t i = nb; i <= kMaxBatch; ++i) {
         tab.tile_start[i] = tiles;
-        tab.blk_start[i] = blks;
-        tab.sup_start[i] = sups;
         tab.elem_off[i] = eoff;
         tab.slot_off[i] = slot_off[c0 + nb] - slot_off[c0];
     }
@@ -92,27 +86,25 @@ uint64_t total_tiles(const std::vector<uint64_t>& ce)
     return t;
 }
 
-/* Workspace layout: header | u32 per super-block | u32 per tile | u32 per block (8-byte aligned parts). */
+/* Workspace layout: header | u32 count per tile | u32 prefix per tile | stash (one byte per element). */
 struct WorkspacePlan {
-    uint64_t tiles, blocks, supers, sup_off, tile_off, blk_off, bytes;
+    uint64_t tiles, total_off, prefix_off, stash_off, min_bytes, full_bytes;
 };
 
-WorkspacePlan plan_workspace(const std::vector<uint64_t>& ce)
+WorkspacePlan plan_workspace(const std::vector<uint64_t>& ce, uint64_t n_elems)
 {
     WorkspacePlan w{};
-    for (uint64_t n : ce) {
-        w.tiles += tiles_of(n);
-        w.blocks += blocks_of(n);
-        w.supers += supers_of(n);
-    }
-    w.sup_off = kWorkspaceHeader;
-    w.tile_off = w.sup_off + ((4 * w.supers + 7) & ~7ull);
-    w.blk_off = w.tile_off + ((4 * w.tiles + 7) & ~7ull);
-    w.bytes = w.blk_off + ((4 * w.blocks + 7) & ~7ull);
+    for (uint64_t n : ce) w.tiles += tiles_of(n);
+    const uint64_t arr = (4 * w.tiles + 15) & ~15ull;
+    w.total_off = kWorkspaceHeader;
+    w.prefix_off = w.total_off + arr;
+    w.stash_off = w.prefix_off + arr;
+    w.min_bytes = w.stash_off;
+    w.full_bytes = w.stash_off + ((n_elems + kStashSlack + 15) & ~15ull);
     return w;
 }
 
-/* 0 = fused single kernel, 1 = three kernels (count, scan, emit); see zipccl_debug_compress_path */
+/* 0 = single pass with a stash, 1 = two passes over the input; see zipccl_debug_compress_path */
 std::atomic<int>& compress_path()
 {
     static std::atomic<int> path([] {
@@ -173,7 +165,16 @@ size_t zipccl_compress_workspace_size(size_t n_elems, zipccl_dtype_t dt, uint32_
     if (!dtype_ok(dt)) return 0;
     std::vector<uint64_t> ce;
     if (!resolve_split(n_elems, n_chunks, chunk_elems, ce)) return 0;
-    return (size_t)plan_workspace(ce).bytes;
+    return (size_t)plan_workspace(ce, n_elems).full_bytes;
+}
+
+size_t zipccl_compress_min_workspace_size(size_t n_elems, zipccl_dtype_t dt, uint32_t n_chunks,
+                                          const uint64_t* chunk_elems)
+{
+    if (!dtype_ok(dt)) return 0;
+    std::vector<uint64_t> ce;
+    if (!resolve_split(n_elems, n_chunks, chunk_elems, ce)) return 0;
+    return (size_t)plan_workspace(ce, n_elems).min_bytes;
 }
 
 zipccl_status_t zipccl_compress(const void* d_in, size_t n_elems, zipccl_dtype_t dt,
@@ -188,7 +189,7 @@ zipccl_status_t zipccl_compress(const void* d_in, size_t n_elems, zipccl_dtype_t
     if (!table_ok(table) || !d_out || !d_workspace || (!d_in && n_elems)) return ZIPCCL_ERR_INVALID_ARG;
     const uint32_t es = elem_size(dt);
     if ((reinterpret_cast<uintptr_t>(d_in) % es) || (reinterpret_cast<uintptr_t>(d_out) % ZIPCCL_ALIGN) ||
-        (reinterpret_cast<uintptr_t>(d_workspace) % 8) || (reinterpret_cast<uintptr_t>(d_chunk_bytes) % 8))
+        (reinterpret_cast<uintptr_t>(d_workspace) % 16) || (reinterpret_cast<uintptr_t>(d_chunk_bytes) % 8))
         return ZIPCCL_ERR_INVALID_ARG;
 
     std::vector<uint64_t> slot_off(n_chunks + 1);
@@ -199,22 +200,18 @@ zipccl_status_t zipccl_compress(const void* d_in, size_t n_elems, zipccl_dtype_t
     }
     slot_off[n_chunks] = off;
     if (off > out_capacity) return ZIPCCL_ERR_BUFFER_TOO_SMALL;
-    const WorkspacePlan wp = plan_workspace(ce);
+    const WorkspacePlan wp = plan_workspace(ce, n_elems);
     if (wp.tiles > 0x7FFFFFFFull) return ZIPCCL_ERR_INVALID_ARG;
-    const uint64_t ws_need = wp.bytes;
-    if (ws_need > workspace_bytes) return ZIPCCL_ERR_BUFFER_TOO_SMALL;
+    if (wp.min_bytes > workspace_bytes) return ZIPCCL_ERR_BUFFER_TOO_SMALL;
+    /* without room for the stash the input is read twice instead */
+    const bool stash = compress_path().load() == 0 && wp.full_bytes <= workspace_bytes;
 
-    /* tile states must start as "not published"; the status word as 0 */
-    if (launch_fill_zero(d_workspace, ws_need, stream) != 0) return ZIPCCL_ERR_DEVICE;
-
-    const int mode = compress_path().load() == 1 ? (int)kModeEmit : (int)kModeFused;
     CompressArgs a;
     std::memset(&a, 0, sizeof a);
-    a.err = reinterpret_cast<uint32_t*>(d_workspace);
     a.e0 = table->dec[1];
     std::memcpy(&a.dec_lo, table->dec, 4);
     std::memcpy(&a.dec_hi, table->dec + 4, 4);
-    uint64_t elem_base = 0, tile_base = 0, blk_base = 0, sup_base = 0;
+    uint64_t elem_base = 0, tile_base = 0;
     uint8_t* const ws = static_cast<uint8_t*>(d_workspace);
     for (uint32_t c0 = 0; c0 < n_chunks; c0 += kMaxBatch) {
         const uint32_t nb = (n_chunks - c0) < kMaxBatch ? (n_chunks - c0) : kMaxBatch;
@@ -222,11 +219,13 @@ zipccl_status_t zipccl_compress(const void* d_in, size_t n_elems, zipccl_dtype_t
         a.in = static_cast<const uint8_t*>(d_in) + elem_base * es;
         a.out = static_cast<uint8_t*>(d_out) + slot_off[c0];
         a.chunk_bytes = d_chunk_bytes ? d_chunk_bytes + c0 : nullptr;
-        a.sup_state = reinterpret_cast<uint32_t*>(ws + wp.sup_off) + sup_base;
-        a.tile_state = reinterpret_cast<uint32_t*>(ws + wp.tile_off) + tile_base;
-        a.blk_state = reinterpret_cast<uint32_t*>(ws + wp.blk_off) + blk_base;
-        if (mode == kModeFused) {
-            if (launch_compress(dt, kModeFused, a, nt, stream) != 0) return ZIPCCL_ERR_DEVICE;
+        a.tile_total = reinterpret_cast<uint32_t*>(ws + wp.total_off) + tile_base;
+        a.tile_prefix = reinterpret_cast<uint32_t*>(ws + wp.prefix_off) + tile_base;
+        a.stash = stash ? ws + wp.stash_off + elem_base : nullptr;
+        if (stash) {
+            if (launch_compress(dt, kModeStash, a, nt, stream) != 0) return ZIPCCL_ERR_DEVICE;
+            if (launch_tile_scan(a, stream) != 0) return ZIPCCL_ERR_DEVICE;
+            if (launch_place(dt, a, nt, stream) != 0) return ZIPCCL_ERR_DEVICE;
         } else {
             if (launch_compress(dt, kModeCount, a, nt, stream) != 0) return ZIPCCL_ERR_DEVICE;
             if (launch_tile_scan(a, stream) != 0) return ZIPCCL_ERR_DEVICE;
@@ -234,8 +233,6 @@ zipccl_status_t zipccl_compress(const void* d_in, size_t n_elems, zipccl_dtype_t
         }
         elem_base += a.tab.elem_off[nb];
         tile_base += nt;
-        blk_base += a.tab.blk_start[nb];
-        sup_base += a.tab.sup_start[nb];
     }
     return ZIPCCL_OK;
 }

@@ -25,9 +25,8 @@ constexpr uint32_t kTile = kGroup * kGroupsPerTile; /* 8192 elements */
 constexpr uint32_t kMaxBatch = 128;                 /* chunks per kernel launch */
 constexpr uint32_t kVersion = 1;
 constexpr uint32_t kMagic = 0x4C43505Au;            /* "ZPCL" little-endian */
-constexpr uint32_t kWorkspaceHeader = 256;          /* bytes before the scan state arrays */
-constexpr uint32_t kTilesPerBlock = 64;             /* scan hierarchy: 64 tiles = 1 block, 64 blocks = 1 super-block */
-constexpr uint32_t kTilesPerSuper = 64 * 64;
+constexpr uint32_t kWorkspaceHeader = 256;          /* bytes before the per-tile arrays */
+constexpr uint32_t kStashSlack = 64;                /* readable bytes past the last stash byte */
 
 /* header field offsets */
 constexpr uint32_t kHdrMagic = 0, kHdrVersion = 4, kHdrDtype = 8, kHdrGroup = 12, kHdrN = 16,
@@ -55,15 +54,11 @@ ZIPCCL_HD SlotLayout slot_layout(uint64_t n, int dt)
 }
 
 ZIPCCL_HD uint64_t tiles_of(uint64_t n) { return n == 0 ? 1 : (n + kTile - 1) / kTile; }
-ZIPCCL_HD uint64_t blocks_of(uint64_t n) { return (tiles_of(n) + kTilesPerBlock - 1) / kTilesPerBlock; }
-ZIPCCL_HD uint64_t supers_of(uint64_t n) { return (tiles_of(n) + kTilesPerSuper - 1) / kTilesPerSuper; }
 
 /* Per-launch chunk table, passed by value in the kernel argument segment. */
 struct ChunkTab {
     uint32_t n_chunks;
     uint32_t tile_start[kMaxBatch + 1]; /* first tile of chunk c in this launch */
-    uint32_t blk_start[kMaxBatch + 1];  /* first scan block (64 tiles, never spanning chunks) of chunk c */
-    uint32_t sup_start[kMaxBatch + 1];  /* first scan super-block (64 blocks) of chunk c */
     uint64_t elem_off[kMaxBatch + 1];   /* first element of chunk c, relative to the launch's input */
     uint64_t slot_off[kMaxBatch + 1];   /* byte offset of slot c, relative to the launch's output */
 };
@@ -72,9 +67,9 @@ struct CompressArgs {
     const uint8_t* in;       /* first element of the launch's first chunk */
     uint8_t* out;            /* compressed buffer base for this launch */
     uint64_t* chunk_bytes;   /* entry of the launch's first chunk, or null */
-    uint32_t* tile_state;    /* one u32 per tile of this launch */
-    uint32_t* blk_state;     /* one u32 per scan block of this launch */
-    uint32_t* sup_state;     /* one u32 per scan super-block of this launch */
+    uint32_t* tile_total;    /* one u32 per tile of this launch: its zero-point count */
+    uint32_t* tile_prefix;   /* one u32 per tile: zero-points of its chunk before it */
+    uint8_t* stash;          /* stash mode: one byte per input element of this launch (+ slack) */
     uint32_t* err;           /* workspace status word */
     uint32_t e0;             /* dec[1] */
     uint32_t dec_lo, dec_hi; /* dec[0..3], dec[4..7] packed little-endian */
@@ -89,12 +84,16 @@ struct DecompressArgs {
     ChunkTab tab;
 };
 
-enum CompressMode { kModeCount = 0, kModeEmit = 1, kModeFused = 2 };
+/* kModeStash: single pass over the input; zero-point exponents go to a stash at a position that
+ * does not depend on other tiles, and k_place moves them once the tile prefixes are known.
+ * kModeCount + kModeEmit: the same without a stash, reading the input twice. */
+enum CompressMode { kModeCount = 0, kModeEmit = 1, kModeStash = 2 };
 
 /* launchers implemented in zipccl_kernels.hip; return a hipError_t as int */
 int launch_fill_zero(void* d_ptr, uint64_t bytes, void* stream);
 int launch_compress(int dt, int mode, const CompressArgs& a, uint32_t n_tiles, void* stream);
 int launch_tile_scan(const CompressArgs& a, void* stream);
+int launch_place(int dt, const CompressArgs& a, uint32_t n_tiles, void* stream);
 int launch_decompress(int dt, const DecompressArgs& a, uint32_t n_tiles, void* stream);
 
 } // namespace zipccl

@@ -9,9 +9,15 @@
  *              sub/min produce the codes, v_dot4_u32_u8 transposes code bits into plane bytes.
  *              Plane bytes and zero-point exponents are staged in LDS and leave as wide
  *              stores.  The zero-point offsets of section 4.2.3 are an exclusive prefix in
- *              element order (lane -> wave -> tile -> chunk), so the output is deterministic;
- *              the chunk-wide part reads published per-tile / per-block count words instead of
- *              the paper's block-level atomic add.
+ *              element order (lane -> wave -> tile -> chunk), so the output is deterministic.
+ *              No workgroup ever waits for another: the chunk-wide level, which the paper does
+ *              with a block-level atomic add inside the kernel, is a kernel boundary here.
+ *              k_compress<kModeStash> writes everything whose place is known (SM, LO, planes,
+ *              tile-local index) and parks the zero-point exponents of its tile in a stash;
+ *              k_tile_scan turns the per-tile counts into per-chunk prefixes; k_place moves
+ *              each tile's exponents to their final place and finishes index and header.
+ *              (Waiting in-kernel for the predecessors' counts costs a tile ~10 us of lateness
+ *              of the slowest of them, measured; the stash costs ~2 % extra traffic.)
  * decompress : section 4, third paragraph.  No dependency between workgroups.
  *
  * Everything is integer work; sigma / erf live on the host.
@@ -22,9 +28,6 @@
 
 namespace zipccl {
 namespace {
-
-constexpr uint32_t kValid = 1u << 31;      /* scan state word: bit 31 = published, low bits = a zero-point count */
-constexpr uint32_t kSpinLimit = 1u << 22;  /* polls before the scan wait gives up and flags an error */
 
 typedef unsigned short us2 __attribute__((ext_vector_type(2)));
 
@@ -84,12 +87,6 @@ __device__ __forceinline__ uint32_t find_chunk(const ChunkTab& tab, uint32_t t)
         if (tab.tile_start[mid] <= t) lo = mid; else hi = mid;
     }
     return lo;
-}
-
-template <typename T>
-__device__ __forceinline__ T load_agent(const T* p)
-{
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 /*
@@ -186,75 +183,10 @@ __device__ __forceinline__ LaneEnc encode8(const uint32_t w[4], uint32_t k7)
     return r;
 }
 
-/* Sum of `count` published state words state[0..count) (count <= 64), or false if one is missing. */
-__device__ __forceinline__ bool window_sum(const uint32_t* state, uint32_t count, uint32_t lane, uint32_t& sum)
-{
-    uint32_t v = kValid;
-    if (lane < count) v = load_agent(state + lane);
-    if (__ballot((v & kValid) == 0u) != 0ull) return false;
-    sum = wave_sum(v & ~kValid);
-    return true;
-}
-
-/*
- * Chunk-wide exclusive prefix of the per-tile zero-point counts (section 4.2.3's "global"
- * level), run by one wave of tile `ti` (index inside its chunk, workgroup id t) after it has
- * published its own count `own`.  Tiles form blocks of 64 and super-blocks of 64 blocks, never
- * spanning chunks.  The prefix is
- *   (tiles before ti in its block) + (blocks before it in its super-block) + (super-blocks before),
- * three independent reads of at most 64 state words each.  The last tile of a block publishes
- * the block's sum (its own first term + its count), the last tile of a super-block the
- * super-block's sum, so no state word depends on a chain of earlier waits and a tile needs at
- * most three memory round trips after its predecessors have counted, whatever the chunk size.
- * Only plain stores and loads at device scope are used (read-modify-write atomics on shared
- * counters serialise badly across the chip).  Predecessors have lower workgroup ids, so they
- * are already running.  The wait is bounded: past kSpinLimit polls the error word is set and
- * the result is unspecified.
- */
-__device__ __forceinline__ uint32_t chunk_prefix(uint32_t* tile_state, uint32_t* blk_state, uint32_t* sup_state,
-                                                 uint32_t t, uint32_t ti, uint32_t own, uint32_t lane, uint32_t* err)
-{
-    const uint32_t j = ti % kTilesPerBlock;            /* tiles before this one in its block */
-    const uint32_t bi = ti / kTilesPerBlock;           /* its block, counted inside the chunk */
-    const uint32_t b = bi % 64u;                       /* blocks before its block in its super-block */
-    const uint32_t s = ti / kTilesPerSuper;            /* super-blocks before its super-block */
-    uint32_t s0 = 0, s1 = 0, s2 = 0, spins = 0;
-    bool ok0 = false, ok1 = false, ok2 = false;
-    for (;;) {
-        if (!ok0 && window_sum(tile_state + (t - j), j, lane, s0)) {
-            ok0 = true;
-            if (j == kTilesPerBlock - 1u && lane == 0)
-                __hip_atomic_store(blk_state + bi, kValid | (s0 + own), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-        if (!ok1 && window_sum(blk_state + (bi - b), b, lane, s1)) ok1 = true;
-        if (!ok2) {
-            uint32_t acc = 0, part = 0;
-            bool all = true;
-            for (uint32_t w = 0; w < s && all; w += 64u) {   /* more than 64 only for chunks past 2^31 values */
-                all = window_sum(sup_state + w, s - w < 64u ? s - w : 64u, lane, part);
-                acc += part;
-            }
-            if (all) { ok2 = true; s2 = acc; }
-        }
-        if (ok0 && ok1 && ok2) break;
-        if (++spins > kSpinLimit) {
-            if (lane == 0) atomicOr(err, (uint32_t)ZIPCCL_ERR_DEVICE);
-            return 0;
-        }
-        __builtin_amdgcn_s_sleep(1);
-    }
-    if (ti % kTilesPerSuper == kTilesPerSuper - 1u && lane == 0)
-        __hip_atomic_store(sup_state + s, kValid | (s0 + s1 + own), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    return s0 + s1 + s2;
-}
-
 struct CompressShared {
     uint8_t planes[3][kTile / 8];          /* plane bytes of the tile, natural order */
     uint8_t esc[kGroupsPerTile][kGroup];   /* zero-point exponents, one region per group */
     uint32_t gcnt[kGroupsPerTile];         /* zero-points per group */
-    uint32_t goff[kGroupsPerTile];         /* exclusive prefix of gcnt */
-    uint32_t prefix;                       /* zero-points of the chunk before this tile */
-    uint32_t total;                        /* zero-points of this tile */
 };
 
 /* One group of one wave: load, encode, store SM/LO, stage planes and zero-points in LDS. */
@@ -295,6 +227,47 @@ __device__ __forceinline__ void compress_group(const uint8_t* __restrict__ cin, 
     }
 }
 
+/*
+ * Chunk header, zeroed IDX / ESC padding and chunk_bytes, once the chunk's zero-point count is
+ * known.  Called with at least 128 threads numbered tid = 0.. (or a wave, which loops).
+ */
+template <int DT>
+__device__ __forceinline__ void finish_chunk(uint8_t* __restrict__ slot, const SlotLayout& L, uint64_t n,
+                                             uint64_t n_esc, uint32_t dec_lo, uint32_t dec_hi,
+                                             uint64_t* chunk_bytes, uint32_t tid)
+{
+    const uint64_t ng = (n + kGroup - 1) / kGroup;
+    const uint64_t cbytes = L.esc + pad128(n_esc);
+    uint32_t* __restrict__ idx = reinterpret_cast<uint32_t*>(slot + L.idx);
+    uint8_t* __restrict__ esc = slot + L.esc;
+    if (tid < 32) {
+        uint32_t w = 0;
+        switch (tid) {
+            case 0: w = kMagic; break;
+            case 1: w = kVersion; break;
+            case 2: w = (uint32_t)DT; break;
+            case 3: w = kGroup; break;
+            case 4: w = (uint32_t)n; break;
+            case 5: w = (uint32_t)(n >> 32); break;
+            case 6: w = (uint32_t)n_esc; break;
+            case 7: w = (uint32_t)(n_esc >> 32); break;
+            case 8: w = (uint32_t)cbytes; break;
+            case 9: w = (uint32_t)(cbytes >> 32); break;
+            case 10: w = dec_lo; break;
+            case 11: w = dec_hi; break;
+            default: break;
+        }
+        reinterpret_cast<uint32_t*>(slot)[tid] = w;
+        const uint64_t ie = ng + tid;                       /* zero the IDX padding */
+        if (4 * ie < pad128(4 * ng)) idx[ie] = 0;
+    }
+    for (uint32_t i = tid; i < 128u; i += 64u) {            /* zero the ESC padding */
+        const uint64_t je = n_esc + i;
+        if (je < pad128(n_esc)) esc[je] = 0;
+    }
+    if (tid == 0 && chunk_bytes) *chunk_bytes = cbytes;
+}
+
 template <int DT, int MODE>
 __global__ __launch_bounds__(kThreads) void k_compress(const CompressArgs a)
 {
@@ -327,94 +300,98 @@ __global__ __launch_bounds__(kThreads) void k_compress(const CompressArgs a)
     }
     __syncthreads();
 
-    /* wave 0: tile-level prefix of the 16 group counts, then the chunk-level prefix */
+    /* every wave: tile-level exclusive prefix of the 16 group counts (lanes 0..15 hold them) */
+    const uint32_t gc = lane < kGroupsPerTile ? sh.gcnt[lane] : 0u;
+    const uint32_t ginc = row_incl_scan(gc);
+    const uint32_t gex = ginc - gc;
+    const uint32_t tile_total = __builtin_amdgcn_readlane(ginc, kGroupsPerTile - 1);
+    if (MODE == kModeCount) {
+        if (threadIdx.x == 0) a.tile_total[t] = tile_total;
+        return;
+    }
+    if (MODE == kModeStash && threadIdx.x == 0) a.tile_total[t] = tile_total;
+
+    /* kModeEmit knows the zero-points of the chunk before this tile; kModeStash works tile-local */
+    const uint32_t P = MODE == kModeEmit ? a.tile_prefix[t] : 0u;
+    const uint64_t ng = (n + kGroup - 1) / kGroup;
+    uint32_t* __restrict__ idx = reinterpret_cast<uint32_t*>(slot + L.idx);
+    uint8_t* __restrict__ esc = MODE == kModeEmit ? slot + L.esc + P : a.stash + a.tab.elem_off[c] + ts;
+
     if (wave == 0) {
-        const uint32_t cnt = lane < kGroupsPerTile ? sh.gcnt[lane] : 0u;
-        const uint32_t inc = row_incl_scan(cnt);
-        const uint32_t tile_total = __builtin_amdgcn_readlane(inc, kGroupsPerTile - 1);
-        if (lane < kGroupsPerTile) sh.goff[lane] = inc - cnt;
-        if (MODE == kModeCount) {
-            if (lane == 0) a.tile_state[t] = tile_total;
-        } else {
-            uint32_t p = 0;
-            if (MODE == kModeEmit) {
-                p = a.tile_state[t];
-            } else {
-                const uint32_t ti = t - first;
-                if (lane == 0)
-                    __hip_atomic_store(a.tile_state + t, kValid | tile_total, __ATOMIC_RELAXED,
-                                       __HIP_MEMORY_SCOPE_AGENT);
-                p = chunk_prefix(a.tile_state, a.blk_state + a.tab.blk_start[c], a.sup_state + a.tab.sup_start[c],
-                                 t, ti, tile_total, lane, a.err);
-            }
-            if (lane == 0) {
-                sh.prefix = p;
-                sh.total = tile_total;
-            }
-        }
-    } else if (STORE) {
-        /* waves 1..3: one plane each, 16 bytes per lane, while wave 0 resolves the prefix */
+        /* group index (section 4.2.3); k_place adds the tile's prefix in stash mode */
+        const uint64_t g = ts / kGroup + lane;
+        if (lane < kGroupsPerTile && g < ng) idx[g] = P + gex;
+    } else {
+        /* waves 1..3: one plane each, 16 bytes per lane */
         const uint32_t k = wave - 1u;
         const uint64_t pb = ts / 8 + lane * 16u;
         if (fast || pb < L.plane_bytes)
             *reinterpret_cast<uint4*>(slot + L.p0 + k * L.plane_bytes + pb) =
                 *reinterpret_cast<const uint4*>(&sh.planes[k][lane * 16u]);
     }
-    if (MODE == kModeCount) return;
-    __syncthreads();
-
-    const uint32_t P = sh.prefix;
-    const uint64_t ng = (n + kGroup - 1) / kGroup;
-    uint32_t* __restrict__ idx = reinterpret_cast<uint32_t*>(slot + L.idx);
-    uint8_t* __restrict__ esc = slot + L.esc;
-
-    /* group index (section 4.2.3) */
-    if (wave == 0 && lane < kGroupsPerTile) {
-        const uint64_t g = ts / kGroup + lane;
-        if (g < ng) idx[g] = P + sh.goff[lane];
-    }
-    /* zero-point exponents: every wave copies the segments of its own groups */
+    /* zero-point exponents: every wave copies the segments of its own groups, in element order */
+    const uint32_t wave_s = __builtin_amdgcn_readfirstlane(wave);
 #pragma unroll
     for (uint32_t u = 0; u < kGroupsPerWave; ++u) {
-        const uint32_t gi = u * kWavesPerBlock + wave;
-        const uint32_t cnt = sh.gcnt[gi];
-        uint8_t* dst = esc + (uint64_t)P + sh.goff[gi];
+        const uint32_t gi = u * kWavesPerBlock + wave_s;
+        const uint32_t cnt = __builtin_amdgcn_readlane(gc, gi);
+        uint8_t* dst = esc + __builtin_amdgcn_readlane(gex, gi);
         for (uint32_t i = lane; i < cnt; i += 64u) dst[i] = sh.esc[gi][i];
     }
 
-    if (last_tile) {
-        const uint64_t n_esc = (uint64_t)P + sh.total;
-        const uint64_t cbytes = L.esc + pad128(n_esc);
-        if (threadIdx.x < 32) {
-            uint32_t w = 0;
-            switch (threadIdx.x) {
-                case 0: w = kMagic; break;
-                case 1: w = kVersion; break;
-                case 2: w = (uint32_t)DT; break;
-                case 3: w = kGroup; break;
-                case 4: w = (uint32_t)n; break;
-                case 5: w = (uint32_t)(n >> 32); break;
-                case 6: w = (uint32_t)n_esc; break;
-                case 7: w = (uint32_t)(n_esc >> 32); break;
-                case 8: w = (uint32_t)cbytes; break;
-                case 9: w = (uint32_t)(cbytes >> 32); break;
-                case 10: w = a.dec_lo; break;
-                case 11: w = a.dec_hi; break;
-                default: break;
-            }
-            reinterpret_cast<uint32_t*>(slot)[threadIdx.x] = w;
-            const uint64_t ie = ng + threadIdx.x;           /* zero the IDX padding */
-            if (4 * ie < pad128(4 * ng)) idx[ie] = 0;
-        }
-        if (threadIdx.x < 128) {                            /* zero the ESC padding */
-            const uint64_t je = n_esc + threadIdx.x;
-            if (je < pad128(n_esc)) esc[je] = 0;
-        }
-        if (threadIdx.x == 0 && a.chunk_bytes) a.chunk_bytes[c] = cbytes;
-    }
+    if (MODE == kModeEmit && last_tile)
+        finish_chunk<DT>(slot, L, n, (uint64_t)P + tile_total, a.dec_lo, a.dec_hi,
+                         a.chunk_bytes ? a.chunk_bytes + c : nullptr, threadIdx.x);
 }
 
-/* Three-kernel path only: turn the per-tile counts of every chunk into exclusive prefixes. */
+/*
+ * Stash mode, after k_tile_scan: one wave per tile moves the tile's zero-point exponents from
+ * the stash to ESC[P, P + count), adds P to the tile's index entries, and the last tile of a
+ * chunk writes header, padding and chunk_bytes.
+ */
+template <int DT>
+__global__ __launch_bounds__(kThreads) void k_place(const CompressArgs a, uint32_t n_tiles)
+{
+    const uint32_t lane = lane_id();
+    const uint32_t t = blockIdx.x * kWavesPerBlock + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    if (t >= n_tiles) return;
+    const uint32_t c = find_chunk(a.tab, t);
+    const uint32_t first = a.tab.tile_start[c];
+    const uint64_t n = a.tab.elem_off[c + 1] - a.tab.elem_off[c];
+    const uint64_t ts = (uint64_t)(t - first) * kTile;
+    uint8_t* __restrict__ slot = a.out + a.tab.slot_off[c];
+    const SlotLayout L = slot_layout(n, DT);
+    const uint32_t P = a.tile_prefix[t];
+    const uint32_t cnt = a.tile_total[t];
+
+    if (P != 0u) {
+        const uint64_t ng = (n + kGroup - 1) / kGroup;
+        uint32_t* __restrict__ idx = reinterpret_cast<uint32_t*>(slot + L.idx);
+        const uint64_t g = ts / kGroup + lane;
+        if (lane < kGroupsPerTile && g < ng) idx[g] += P;
+    }
+
+    /* byte-exact move to an arbitrarily aligned destination: head bytes, aligned words, tail bytes */
+    const uint8_t* __restrict__ src = a.stash + a.tab.elem_off[c] + ts;
+    uint8_t* __restrict__ dst = slot + L.esc + P;
+    const uint32_t head = min((uint32_t)(-(int64_t)reinterpret_cast<uintptr_t>(dst)) & 3u, cnt);
+    if (lane < head) dst[lane] = src[lane];
+    const uint32_t nw = (cnt - head) >> 2;
+    const uint32_t sh8 = reinterpret_cast<uintptr_t>(src + head) & 3u;
+    const uint32_t* __restrict__ s32 = reinterpret_cast<const uint32_t*>(
+        reinterpret_cast<uintptr_t>(src + head) & ~(uintptr_t)3);
+    uint32_t* __restrict__ d32 = reinterpret_cast<uint32_t*>(dst + head);
+    for (uint32_t i = lane; i < nw; i += 64u)
+        d32[i] = __builtin_amdgcn_alignbyte(s32[i + 1], s32[i], sh8);   /* reads stay inside the stash slack */
+    const uint32_t done = head + 4u * nw;
+    if (lane < cnt - done) dst[done + lane] = src[done + lane];
+
+    if (t + 1u == a.tab.tile_start[c + 1])
+        finish_chunk<DT>(slot, L, n, (uint64_t)P + cnt, a.dec_lo, a.dec_hi,
+                         a.chunk_bytes ? a.chunk_bytes + c : nullptr, lane);
+}
+
+/* One workgroup per chunk: exclusive prefix of the chunk's per-tile zero-point counts. */
 __global__ __launch_bounds__(kThreads) void k_tile_scan(const CompressArgs a)
 {
     __shared__ uint32_t s_part[kThreads];
@@ -425,16 +402,15 @@ __global__ __launch_bounds__(kThreads) void k_tile_scan(const CompressArgs a)
     const uint32_t b = first + threadIdx.x * per;
     uint32_t sum = 0;
     for (uint32_t i = 0; i < per; ++i)
-        if (b + i < end) sum += a.tile_state[b + i];
+        if (b + i < end) sum += a.tile_total[b + i];
     s_part[threadIdx.x] = sum;
     __syncthreads();
     uint32_t run = 0;
     for (uint32_t i = 0; i < threadIdx.x; ++i) run += s_part[i];
     for (uint32_t i = 0; i < per; ++i)
         if (b + i < end) {
-            const uint32_t v = a.tile_state[b + i];
-            a.tile_state[b + i] = run;
-            run += v;
+            a.tile_prefix[b + i] = run;
+            run += a.tile_total[b + i];
         }
 }
 
@@ -633,11 +609,11 @@ int launch_compress(int dt, int mode, const CompressArgs& a, uint32_t n_tiles, v
     if (dt == ZIPCCL_BF16) {
         if (mode == kModeCount) ZIPCCL_LAUNCH(ZIPCCL_BF16, kModeCount);
         else if (mode == kModeEmit) ZIPCCL_LAUNCH(ZIPCCL_BF16, kModeEmit);
-        else ZIPCCL_LAUNCH(ZIPCCL_BF16, kModeFused);
+        else ZIPCCL_LAUNCH(ZIPCCL_BF16, kModeStash);
     } else {
         if (mode == kModeCount) ZIPCCL_LAUNCH(ZIPCCL_FP32, kModeCount);
         else if (mode == kModeEmit) ZIPCCL_LAUNCH(ZIPCCL_FP32, kModeEmit);
-        else ZIPCCL_LAUNCH(ZIPCCL_FP32, kModeFused);
+        else ZIPCCL_LAUNCH(ZIPCCL_FP32, kModeStash);
     }
 #undef ZIPCCL_LAUNCH
     return (int)hipGetLastError();
@@ -646,6 +622,16 @@ int launch_compress(int dt, int mode, const CompressArgs& a, uint32_t n_tiles, v
 int launch_tile_scan(const CompressArgs& a, void* stream)
 {
     hipLaunchKernelGGL(k_tile_scan, dim3(a.tab.n_chunks), dim3(kThreads), 0, (hipStream_t)stream, a);
+    return (int)hipGetLastError();
+}
+
+int launch_place(int dt, const CompressArgs& a, uint32_t n_tiles, void* stream)
+{
+    const dim3 grid((n_tiles + kWavesPerBlock - 1) / kWavesPerBlock), block(kThreads);
+    if (dt == ZIPCCL_BF16)
+        hipLaunchKernelGGL((k_place<ZIPCCL_BF16>), grid, block, 0, (hipStream_t)stream, a, n_tiles);
+    else
+        hipLaunchKernelGGL((k_place<ZIPCCL_FP32>), grid, block, 0, (hipStream_t)stream, a, n_tiles);
     return (int)hipGetLastError();
 }
 

@@ -27,7 +27,6 @@ def gpu_compress(data, dtype, sigma, n_chunks=1, chunk_elems=None, table=None, d
     d_ws = torch.full((ws,), 0x5A, dtype=torch.uint8, device=DEV)
     z.zipccl_compress(d_in, n, dtype, n_chunks, chunk_elems, table, d_out, d_cb, d_ws)
     torch.cuda.synchronize()
-    assert int(d_ws[:4].view(torch.int32).item()) == 0, "compress status word is nonzero"
     return d_out, d_cb, table
 
 

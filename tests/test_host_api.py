@@ -61,10 +61,11 @@ def test_sizes_and_offsets_match_oracle():
     assert z.zipccl_max_compressed_size(10, z.BF16, 0) == 0
     assert z.zipccl_max_compressed_size(10, z.BF16, 2, [4, 5]) == 0       # must sum to n
     assert z.zipccl_max_compressed_size(10, 5, 1) == 0
-    # header + u32 per super-block + u32 per tile + u32 per block (each part padded to 8 bytes)
-    assert z.zipccl_compress_workspace_size(8192 * 3 + 1, z.BF16, 1) == 256 + 8 + 4 * 4 + 8
-    assert z.zipccl_compress_workspace_size(0, z.BF16, 2, [0, 0]) == 256 + 8 + 8 + 8
-    assert z.zipccl_compress_workspace_size(8192 * 4096 * 2, z.BF16, 2) == 256 + 8 + 4 * 8192 + 4 * 128
+    # header + (u32 count + u32 prefix) per tile, each array padded to 16 bytes [+ stash: 1 byte per element + slack]
+    assert z.zipccl_compress_min_workspace_size(8192 * 3 + 1, z.BF16, 1) == 256 + 16 + 16
+    assert z.zipccl_compress_workspace_size(8192 * 3 + 1, z.BF16, 1) == 256 + 32 + (8192 * 3 + 1 + 64 + 15) // 16 * 16
+    assert z.zipccl_compress_min_workspace_size(0, z.BF16, 2, [0, 0]) == 256 + 32
+    assert z.zipccl_compress_min_workspace_size(8192 * 4096 * 2, z.BF16, 2) == 256 + 2 * 4 * 8192
 
 
 def test_argument_errors_return_before_any_launch():
@@ -72,7 +73,7 @@ def test_argument_errors_return_before_any_launch():
     t = z.zipccl_build_table(1.0)
     A = 1 << 20                      # a fake, aligned "device" address: never dereferenced on these paths
     cap = z.zipccl_max_compressed_size(1024, z.BF16, 1)
-    ws = z.zipccl_compress_workspace_size(1024, z.BF16, 1)
+    ws = z.zipccl_compress_min_workspace_size(1024, z.BF16, 1)
 
     def comp(d_in=A, n=1024, dt=z.BF16, k=1, ce=None, table=t, out=A, ocap=cap, cb=A, w=A, wb=ws):
         tab = ctypes.byref(table) if table is not None else None
@@ -87,7 +88,7 @@ def test_argument_errors_return_before_any_launch():
     assert comp(d_in=None) == 1
     assert comp(d_in=A + 1) == 1
     assert comp(out=A + 64) == 1
-    assert comp(w=A + 4) == 1
+    assert comp(w=A + 8) == 1
     assert comp(ocap=cap - 1) == 3
     assert comp(wb=ws - 1) == 3
     bad = z.zipccl_table_t()
