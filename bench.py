@@ -74,7 +74,18 @@ def run_gpu(w, steps, warmup):
     wall = time.perf_counter() - t0
     tc = np.array([e[0].elapsed_time(e[1]) for e in evs])      # ms
     td = np.array([e[1].elapsed_time(e[2]) for e in evs])
-    return dict(wall_s=wall, tc_ms=tc, td_ms=td, comp_bytes=comp_bytes,
+
+    # yardstick: a plain copy kernel moving the same number of bytes as one codec launch
+    # ((nbytes + comp_bytes) / 2 read and as many written)
+    half = min((w.nbytes + comp_bytes) // 2, w.nbytes) // 16 * 16
+    cevs = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(5)]
+    for k in range(5):
+        cevs[k][0].record(stream)
+        z.zipccl_debug_copy(d_back, d_in, half, stream=stream)
+        cevs[k][1].record(stream)
+    torch.cuda.synchronize()
+    copy_ms = float(np.median([e[0].elapsed_time(e[1]) for e in cevs]))
+    return dict(wall_s=wall, tc_ms=tc, td_ms=td, comp_bytes=comp_bytes, copy_GBps=2 * half / (copy_ms * 1e-3) / 1e9,
                 d_out=d_out, d_cb=d_cb, table=table)
 
 
@@ -167,7 +178,8 @@ def main():
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                      "algorithmic_bytes_per_launch": algo_bytes,
                      "compress_frac": round(algo_bytes / (tc * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
-                     "decompress_frac": round(algo_bytes / (td * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)},
+                     "decompress_frac": round(algo_bytes / (td * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                     "copy_kernel_GBps": round(r["copy_GBps"], 1)},
         "paper_context": PAPER_CONTEXT,
     }
 

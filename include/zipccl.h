@@ -149,6 +149,15 @@ const char* zipccl_status_string(zipccl_status_t s);
  */
 int zipccl_debug_compress_path(int path);
 
+/*
+ * Measurement yardstick: a plain device-to-device copy kernel (16 bytes per lane, one load and
+ * one store per thread, the fastest plain form measured).  d_dst / d_src device, 16-byte
+ * aligned, bytes a multiple of 16; asynchronous on `stream`.  The benchmark reports its rate
+ * as the practical ceiling next to the HBM peak, and counter runs use it to scale
+ * FETCH_SIZE / WRITE_SIZE readings.
+ */
+zipccl_status_t zipccl_debug_copy(void* d_dst, const void* d_src, size_t bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -54,6 +54,8 @@ def _load():
     lib.zipccl_compress.argtypes = [vp, sz, i32, u32, vp, tp, vp, sz, vp, vp, sz, vp]
     lib.zipccl_decompress.restype = i32
     lib.zipccl_decompress.argtypes = [vp, sz, vp, sz, i32, u32, vp, vp, vp]
+    lib.zipccl_debug_copy.restype = i32
+    lib.zipccl_debug_copy.argtypes = [vp, vp, sz, vp]
     lib.zipccl_debug_compress_path.restype = i32
     lib.zipccl_debug_compress_path.argtypes = [i32]
     lib.zipccl_status_string.restype = ctypes.c_char_p
@@ -64,7 +66,7 @@ def _load():
 _lib = _load()
 EXPORTS = ("zipccl_build_table", "zipccl_max_compressed_size", "zipccl_chunk_slot_offsets",
            "zipccl_compress_workspace_size", "zipccl_compress_min_workspace_size", "zipccl_compress", "zipccl_decompress", "zipccl_status_string",
-           "zipccl_debug_compress_path")
+           "zipccl_debug_compress_path", "zipccl_debug_copy")
 
 
 def _host_u64(chunk_elems):
@@ -96,6 +98,12 @@ def zipccl_status_string(code):
 
 def zipccl_debug_compress_path(path=-1):
     return int(_lib.zipccl_debug_compress_path(int(path)))
+
+
+def zipccl_debug_copy(d_dst, d_src, nbytes, stream=None):
+    rc = _lib.zipccl_debug_copy(_dptr(d_dst), _dptr(d_src), int(nbytes), _stream(stream))
+    if rc:
+        raise ZipcclError(rc, "zipccl_debug_copy")
 
 
 def zipccl_build_table(sigma, dt=BF16):

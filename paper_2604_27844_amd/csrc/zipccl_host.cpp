@@ -86,9 +86,9 @@ uint64_t total_tiles(const std::vector<uint64_t>& ce)
     return t;
 }
 
-/* Workspace layout: header | u32 count per tile | u32 prefix per tile | stash (one byte per element). */
+/* Workspace layout: header | u32 count per tile | u32 prefix per tile | [tile descriptors | stash (one byte per element)]. */
 struct WorkspacePlan {
-    uint64_t tiles, total_off, prefix_off, stash_off, min_bytes, full_bytes;
+    uint64_t tiles, total_off, prefix_off, desc_off, stash_off, min_bytes, full_bytes;
 };
 
 WorkspacePlan plan_workspace(const std::vector<uint64_t>& ce, uint64_t n_elems)
@@ -98,8 +98,9 @@ WorkspacePlan plan_workspace(const std::vector<uint64_t>& ce, uint64_t n_elems)
     const uint64_t arr = (4 * w.tiles + 15) & ~15ull;
     w.total_off = kWorkspaceHeader;
     w.prefix_off = w.total_off + arr;
-    w.stash_off = w.prefix_off + arr;
-    w.min_bytes = w.stash_off;
+    w.desc_off = w.prefix_off + arr;
+    w.min_bytes = w.desc_off;
+    w.stash_off = w.desc_off + sizeof(TileDesc) * w.tiles;
     w.full_bytes = w.stash_off + ((n_elems + kStashSlack + 15) & ~15ull);
     return w;
 }
@@ -222,6 +223,7 @@ zipccl_status_t zipccl_compress(const void* d_in, size_t n_elems, zipccl_dtype_t
         a.tile_total = reinterpret_cast<uint32_t*>(ws + wp.total_off) + tile_base;
         a.tile_prefix = reinterpret_cast<uint32_t*>(ws + wp.prefix_off) + tile_base;
         a.stash = stash ? ws + wp.stash_off + elem_base : nullptr;
+        a.desc = stash ? reinterpret_cast<TileDesc*>(ws + wp.desc_off) + tile_base : nullptr;
         if (stash) {
             if (launch_compress(dt, kModeStash, a, nt, stream) != 0) return ZIPCCL_ERR_DEVICE;
             if (launch_tile_scan(a, stream) != 0) return ZIPCCL_ERR_DEVICE;
@@ -276,6 +278,14 @@ zipccl_status_t zipccl_decompress(const void* d_comp, size_t comp_capacity,
         elem_base += a.tab.elem_off[nb];
     }
     return ZIPCCL_OK;
+}
+
+zipccl_status_t zipccl_debug_copy(void* d_dst, const void* d_src, size_t bytes, void* stream)
+{
+    if (!d_dst || !d_src || (reinterpret_cast<uintptr_t>(d_dst) % 16) || (reinterpret_cast<uintptr_t>(d_src) % 16) ||
+        (bytes % 16) || bytes / 16 / 256 > 0x7FFFFFFFull)
+        return ZIPCCL_ERR_INVALID_ARG;
+    return launch_copy(d_dst, d_src, bytes, stream) == 0 ? ZIPCCL_OK : ZIPCCL_ERR_DEVICE;
 }
 
 int zipccl_debug_compress_path(int path)

@@ -30,6 +30,14 @@ namespace zipccl {
 namespace {
 
 typedef unsigned short us2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+/* streaming accesses: every tensor byte is touched once, so keep it out of the way of the caches */
+template <typename T>
+__device__ __forceinline__ T ld_stream(const void* p) { return __builtin_nontemporal_load(static_cast<const T*>(p)); }
+template <typename T>
+__device__ __forceinline__ void st_stream(void* p, T v) { __builtin_nontemporal_store(v, static_cast<T*>(p)); }
 
 __device__ __forceinline__ uint32_t pk_sub_u16(uint32_t a, uint32_t b)
 {
@@ -73,11 +81,6 @@ __device__ __forceinline__ uint32_t row_incl_scan(uint32_t x)
     return x;
 }
 
-__device__ __forceinline__ uint32_t wave_sum(uint32_t x)
-{
-    return __builtin_amdgcn_readlane(wave_incl_scan(x), 63);
-}
-
 /* largest c with tile_start[c] <= t (every chunk owns at least one tile) */
 __device__ __forceinline__ uint32_t find_chunk(const ChunkTab& tab, uint32_t t)
 {
@@ -102,12 +105,12 @@ __device__ __forceinline__ void load_lane(const uint8_t* __restrict__ cin, uint6
     if (FAST) {
         vmask = 0xFFu;
         if (DT == ZIPCCL_BF16) {
-            const uint4 v = *reinterpret_cast<const uint4*>(cin + e * 2);
+            const u32x4 v = ld_stream<u32x4>(cin + e * 2);
             hp[0] = v.x; hp[1] = v.y; hp[2] = v.z; hp[3] = v.w;
             lp[0] = lp[1] = lp[2] = lp[3] = 0;
         } else {
-            const uint4 a = *reinterpret_cast<const uint4*>(cin + e * 4);
-            const uint4 b = *reinterpret_cast<const uint4*>(cin + e * 4 + 16);
+            const u32x4 a = ld_stream<u32x4>(cin + e * 4);
+            const u32x4 b = ld_stream<u32x4>(cin + e * 4 + 16);
             const uint32_t x[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
@@ -201,11 +204,9 @@ __device__ __forceinline__ void compress_group(const uint8_t* __restrict__ cin, 
     const LaneEnc r = encode8(hp, k7);
     const uint32_t m = r.m & vmask;
     if (STORE) {
-        if (FAST || e < pad128(n))
-            *reinterpret_cast<uint2*>(slot + L.sm + e) = make_uint2(r.sm0, r.sm1);
+        if (FAST || e < pad128(n)) st_stream<u32x2>(slot + L.sm + e, u32x2{r.sm0, r.sm1});
         if (DT == ZIPCCL_FP32) {
-            if (FAST || 2 * e < pad128(2 * n))
-                *reinterpret_cast<uint4*>(slot + L.lo + 2 * e) = make_uint4(lp[0], lp[1], lp[2], lp[3]);
+            if (FAST || 2 * e < pad128(2 * n)) st_stream<u32x4>(slot + L.lo + 2 * e, u32x4{lp[0], lp[1], lp[2], lp[3]});
         }
         const uint32_t pi = gi * 64u + lane;
         sh.planes[0][pi] = (uint8_t)r.b0;
@@ -229,9 +230,9 @@ __device__ __forceinline__ void compress_group(const uint8_t* __restrict__ cin, 
 
 /*
  * Chunk header, zeroed IDX / ESC padding and chunk_bytes, once the chunk's zero-point count is
- * known.  Called with at least 128 threads numbered tid = 0.. (or a wave, which loops).
+ * known.  Called by NT cooperating threads numbered tid = 0..NT-1.
  */
-template <int DT>
+template <int DT, uint32_t NT>
 __device__ __forceinline__ void finish_chunk(uint8_t* __restrict__ slot, const SlotLayout& L, uint64_t n,
                                              uint64_t n_esc, uint32_t dec_lo, uint32_t dec_hi,
                                              uint64_t* chunk_bytes, uint32_t tid)
@@ -240,9 +241,9 @@ __device__ __forceinline__ void finish_chunk(uint8_t* __restrict__ slot, const S
     const uint64_t cbytes = L.esc + pad128(n_esc);
     uint32_t* __restrict__ idx = reinterpret_cast<uint32_t*>(slot + L.idx);
     uint8_t* __restrict__ esc = slot + L.esc;
-    if (tid < 32) {
+    for (uint32_t i = tid; i < 32u; i += NT) {
         uint32_t w = 0;
-        switch (tid) {
+        switch (i) {
             case 0: w = kMagic; break;
             case 1: w = kVersion; break;
             case 2: w = (uint32_t)DT; break;
@@ -257,11 +258,11 @@ __device__ __forceinline__ void finish_chunk(uint8_t* __restrict__ slot, const S
             case 11: w = dec_hi; break;
             default: break;
         }
-        reinterpret_cast<uint32_t*>(slot)[tid] = w;
-        const uint64_t ie = ng + tid;                       /* zero the IDX padding */
+        reinterpret_cast<uint32_t*>(slot)[i] = w;
+        const uint64_t ie = ng + i;                         /* zero the IDX padding */
         if (4 * ie < pad128(4 * ng)) idx[ie] = 0;
     }
-    for (uint32_t i = tid; i < 128u; i += 64u) {            /* zero the ESC padding */
+    for (uint32_t i = tid; i < 128u; i += NT) {             /* zero the ESC padding */
         const uint64_t je = n_esc + i;
         if (je < pad128(n_esc)) esc[je] = 0;
     }
@@ -309,7 +310,16 @@ __global__ __launch_bounds__(kThreads) void k_compress(const CompressArgs a)
         if (threadIdx.x == 0) a.tile_total[t] = tile_total;
         return;
     }
-    if (MODE == kModeStash && threadIdx.x == 0) a.tile_total[t] = tile_total;
+    if (MODE == kModeStash && threadIdx.x == 0) {
+        a.tile_total[t] = tile_total;
+        TileDesc d;
+        d.slot = reinterpret_cast<uint64_t>(slot);
+        d.n = n;
+        d.stash = reinterpret_cast<uint64_t>(a.stash + a.tab.elem_off[c] + ts);
+        d.group0 = (uint32_t)(ts / kGroup);
+        d.chunk_last = (c << 8) | (last_tile ? 1u : 0u);
+        a.desc[t] = d;
+    }
 
     /* kModeEmit knows the zero-points of the chunk before this tile; kModeStash works tile-local */
     const uint32_t P = MODE == kModeEmit ? a.tile_prefix[t] : 0u;
@@ -326,8 +336,8 @@ __global__ __launch_bounds__(kThreads) void k_compress(const CompressArgs a)
         const uint32_t k = wave - 1u;
         const uint64_t pb = ts / 8 + lane * 16u;
         if (fast || pb < L.plane_bytes)
-            *reinterpret_cast<uint4*>(slot + L.p0 + k * L.plane_bytes + pb) =
-                *reinterpret_cast<const uint4*>(&sh.planes[k][lane * 16u]);
+            st_stream<u32x4>(slot + L.p0 + k * L.plane_bytes + pb,
+                             *reinterpret_cast<const u32x4*>(&sh.planes[k][lane * 16u]));
     }
     /* zero-point exponents: every wave copies the segments of its own groups, in element order */
     const uint32_t wave_s = __builtin_amdgcn_readfirstlane(wave);
@@ -340,55 +350,107 @@ __global__ __launch_bounds__(kThreads) void k_compress(const CompressArgs a)
     }
 
     if (MODE == kModeEmit && last_tile)
-        finish_chunk<DT>(slot, L, n, (uint64_t)P + tile_total, a.dec_lo, a.dec_hi,
-                         a.chunk_bytes ? a.chunk_bytes + c : nullptr, threadIdx.x);
+        finish_chunk<DT, kThreads>(slot, L, n, (uint64_t)P + tile_total, a.dec_lo, a.dec_hi,
+                                   a.chunk_bytes ? a.chunk_bytes + c : nullptr, threadIdx.x);
+}
+
+/* Move nw aligned words: word i of dst = bytes [4i + sh8, 4i + sh8 + 4) of the aligned word array s32.
+ * `width` lanes (this one is number `lane`) share the job, four words per lane and step, with all
+ * loads of a step issued before its stores.  Reads reach at most 7 bytes past the last source byte. */
+__device__ __forceinline__ void move_words(uint32_t* __restrict__ d32, const uint32_t* __restrict__ s32,
+                                           uint32_t nw, uint32_t sh8, uint32_t lane, uint32_t width)
+{
+    for (uint32_t i0 = 0; i0 < nw; i0 += 4u * width) {
+        uint32_t lo[4], hi[4];
+#pragma unroll
+        for (uint32_t k = 0; k < 4; ++k) {
+            const uint32_t i = i0 + k * width + lane;
+            lo[k] = hi[k] = 0;
+            if (i < nw) { lo[k] = s32[i]; hi[k] = s32[i + 1]; }
+        }
+#pragma unroll
+        for (uint32_t k = 0; k < 4; ++k) {
+            const uint32_t i = i0 + k * width + lane;
+            if (i < nw) d32[i] = __builtin_amdgcn_alignbyte(hi[k], lo[k], sh8);
+        }
+    }
 }
 
 /*
- * Stash mode, after k_tile_scan: one wave per tile moves the tile's zero-point exponents from
- * the stash to ESC[P, P + count), adds P to the tile's index entries, and the last tile of a
- * chunk writes header, padding and chunk_bytes.
+ * Stash mode, after k_tile_scan: 16 lanes per tile (16 tiles per workgroup, so that many tiles'
+ * dependent loads are in flight per wave) move the tile's zero-point exponents from the stash
+ * to ESC[P, P + count), add P to the tile's 16 index entries, and the last tile of a chunk
+ * writes header, padding and chunk_bytes.  Tiles dense in zero-points (more than kPlaceBig
+ * bytes) are moved by the whole workgroup afterwards.
  */
 template <int DT>
 __global__ __launch_bounds__(kThreads) void k_place(const CompressArgs a, uint32_t n_tiles)
 {
-    const uint32_t lane = lane_id();
-    const uint32_t t = blockIdx.x * kWavesPerBlock + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    if (t >= n_tiles) return;
-    const uint32_t c = find_chunk(a.tab, t);
-    const uint32_t first = a.tab.tile_start[c];
-    const uint64_t n = a.tab.elem_off[c + 1] - a.tab.elem_off[c];
-    const uint64_t ts = (uint64_t)(t - first) * kTile;
-    uint8_t* __restrict__ slot = a.out + a.tab.slot_off[c];
-    const SlotLayout L = slot_layout(n, DT);
-    const uint32_t P = a.tile_prefix[t];
-    const uint32_t cnt = a.tile_total[t];
+    constexpr uint32_t kSub = 16;                       /* lanes per tile */
+    constexpr uint32_t kPlaceBig = 1024;                /* bytes a 16-lane group moves on its own */
+    __shared__ uint32_t s_nbig;
+    __shared__ uint32_t s_big[kThreads / kSub];
+    __shared__ uint64_t s_src[kThreads / kSub], s_dst[kThreads / kSub];
+    __shared__ uint32_t s_nw[kThreads / kSub], s_sh[kThreads / kSub];
+    if (threadIdx.x == 0) s_nbig = 0;
+    __syncthreads();
 
-    if (P != 0u) {
+    const uint32_t sub = threadIdx.x % kSub;
+    const uint32_t tw = threadIdx.x / kSub;             /* tile inside the workgroup */
+    const uint32_t t = blockIdx.x * (kThreads / kSub) + tw;
+    if (t < n_tiles) {
+        const TileDesc d = a.desc[t];
+        const uint64_t n = d.n;
+        uint8_t* __restrict__ slot = reinterpret_cast<uint8_t*>(d.slot);
+        const SlotLayout L = slot_layout(n, DT);
+        const uint32_t P = a.tile_prefix[t];
+        const uint32_t cnt = a.tile_total[t];
+
+        /* the tile's 16 index entries */
         const uint64_t ng = (n + kGroup - 1) / kGroup;
         uint32_t* __restrict__ idx = reinterpret_cast<uint32_t*>(slot + L.idx);
-        const uint64_t g = ts / kGroup + lane;
-        if (lane < kGroupsPerTile && g < ng) idx[g] += P;
+        const uint64_t g = (uint64_t)d.group0 + sub;
+        const bool fix_idx = P != 0u && g < ng;
+        uint32_t idx_local = 0;
+        if (fix_idx) idx_local = idx[g];
+
+        /* byte-exact move to an arbitrarily aligned destination: head bytes, aligned words, tail bytes */
+        const uint8_t* __restrict__ src = reinterpret_cast<const uint8_t*>(d.stash);
+        uint8_t* __restrict__ dst = slot + L.esc + P;
+        const uint32_t head = min((uint32_t)(-(int64_t)reinterpret_cast<uintptr_t>(dst)) & 3u, cnt);
+        const uint32_t nw = (cnt - head) >> 2;
+        const uint32_t done = head + 4u * nw;
+        const uint32_t sh8 = reinterpret_cast<uintptr_t>(src + head) & 3u;
+        const uint32_t* __restrict__ s32 = reinterpret_cast<const uint32_t*>(
+            reinterpret_cast<uintptr_t>(src + head) & ~(uintptr_t)3);
+        uint32_t* __restrict__ d32 = reinterpret_cast<uint32_t*>(dst + head);
+        uint8_t hb = 0, tb = 0;
+        if (sub < head) hb = src[sub];
+        if (sub < cnt - done) tb = src[done + sub];
+        if (cnt <= kPlaceBig) {
+            move_words(d32, s32, nw, sh8, sub, kSub);
+        } else if (sub == 0) {
+            const uint32_t k = atomicAdd(&s_nbig, 1u);
+            s_big[k] = tw;
+            s_src[tw] = reinterpret_cast<uint64_t>(s32);
+            s_dst[tw] = reinterpret_cast<uint64_t>(d32);
+            s_nw[tw] = nw;
+            s_sh[tw] = sh8;
+        }
+        if (sub < head) dst[sub] = hb;
+        if (sub < cnt - done) dst[done + sub] = tb;
+        if (fix_idx) idx[g] = idx_local + P;
+        if (d.chunk_last & 1u)
+            finish_chunk<DT, kSub>(slot, L, n, (uint64_t)P + cnt, a.dec_lo, a.dec_hi,
+                                   a.chunk_bytes ? a.chunk_bytes + (d.chunk_last >> 8) : nullptr, sub);
     }
-
-    /* byte-exact move to an arbitrarily aligned destination: head bytes, aligned words, tail bytes */
-    const uint8_t* __restrict__ src = a.stash + a.tab.elem_off[c] + ts;
-    uint8_t* __restrict__ dst = slot + L.esc + P;
-    const uint32_t head = min((uint32_t)(-(int64_t)reinterpret_cast<uintptr_t>(dst)) & 3u, cnt);
-    if (lane < head) dst[lane] = src[lane];
-    const uint32_t nw = (cnt - head) >> 2;
-    const uint32_t sh8 = reinterpret_cast<uintptr_t>(src + head) & 3u;
-    const uint32_t* __restrict__ s32 = reinterpret_cast<const uint32_t*>(
-        reinterpret_cast<uintptr_t>(src + head) & ~(uintptr_t)3);
-    uint32_t* __restrict__ d32 = reinterpret_cast<uint32_t*>(dst + head);
-    for (uint32_t i = lane; i < nw; i += 64u)
-        d32[i] = __builtin_amdgcn_alignbyte(s32[i + 1], s32[i], sh8);   /* reads stay inside the stash slack */
-    const uint32_t done = head + 4u * nw;
-    if (lane < cnt - done) dst[done + lane] = src[done + lane];
-
-    if (t + 1u == a.tab.tile_start[c + 1])
-        finish_chunk<DT>(slot, L, n, (uint64_t)P + cnt, a.dec_lo, a.dec_hi,
-                         a.chunk_bytes ? a.chunk_bytes + c : nullptr, lane);
+    __syncthreads();
+    const uint32_t nbig = s_nbig;
+    for (uint32_t b = 0; b < nbig; ++b) {
+        const uint32_t k = s_big[b];
+        move_words(reinterpret_cast<uint32_t*>(s_dst[k]), reinterpret_cast<const uint32_t*>(s_src[k]), s_nw[k],
+                   s_sh[k], threadIdx.x, kThreads);
+    }
 }
 
 /* One workgroup per chunk: exclusive prefix of the chunk's per-tile zero-point counts. */
@@ -436,99 +498,137 @@ __device__ __forceinline__ uint32_t spread4(uint32_t x)
     return __umul24(x, 0x204081u) & 0x01010101u;
 }
 
+/* What a lane reads for its 8 values of one group. */
+struct DecIn {
+    uint32_t sm0, sm1;       /* 8 sign+mantissa bytes */
+    uint32_t b0, b1, b2;     /* plane bytes */
+    uint32_t lo[4];          /* fp32: 8 low 16-bit words */
+    uint32_t base;           /* IDX entry of the group */
+    uint32_t vmask;          /* bit j = value j exists */
+};
+
+/* The lane's zero-point bytes (up to 8, in element order) and where its mask says they go. */
+struct DecEsc {
+    uint32_t m;              /* bit j = value j is a zero-point */
+    uint32_t pos;            /* list position of the lane's first zero-point */
+    uint32_t d0, d1, d2;     /* the three aligned words covering list bytes [pos, pos + 8) */
+    bool any;                /* the group has zero-points at all */
+    bool bad;                /* the lane's bytes would lie outside the list */
+};
+
 template <int DT, bool FAST>
-__device__ __forceinline__ bool decode_group(const uint8_t* __restrict__ slot, uint8_t* __restrict__ cout,
-                                             const SlotLayout& L, uint64_t n, uint32_t n_esc, uint64_t gstart,
-                                             uint32_t e0, uint32_t lane, const uint2* __restrict__ lut)
+__device__ __forceinline__ DecIn decode_load(const uint8_t* __restrict__ slot, const SlotLayout& L, uint64_t n,
+                                             uint64_t gstart, uint32_t lane)
 {
+    DecIn r;
     const uint64_t e = gstart + lane * kLaneElems;
-    uint2 sm = make_uint2(0, 0);
-    if (FAST || e < pad128(n)) sm = *reinterpret_cast<const uint2*>(slot + L.sm + e);
+    r.sm0 = r.sm1 = r.b0 = r.b1 = r.b2 = 0;
+    r.lo[0] = r.lo[1] = r.lo[2] = r.lo[3] = 0;
+    if (FAST || e < pad128(n)) {
+        const u32x2 v = ld_stream<u32x2>(slot + L.sm + e);
+        r.sm0 = v.x; r.sm1 = v.y;
+    }
     const uint64_t pb = e >> 3;
-    uint32_t b0 = 0, b1 = 0, b2 = 0;
     if (FAST || pb < L.plane_bytes) {
-        b0 = slot[L.p0 + pb];
-        b1 = slot[L.p0 + L.plane_bytes + pb];
-        b2 = slot[L.p0 + 2 * L.plane_bytes + pb];
+        r.b0 = ld_stream<uint8_t>(slot + L.p0 + pb);
+        r.b1 = ld_stream<uint8_t>(slot + L.p0 + L.plane_bytes + pb);
+        r.b2 = ld_stream<uint8_t>(slot + L.p0 + 2 * L.plane_bytes + pb);
     }
-    uint4 lo = make_uint4(0, 0, 0, 0);
     if (DT == ZIPCCL_FP32) {
-        if (FAST || 2 * e < pad128(2 * n)) lo = *reinterpret_cast<const uint4*>(slot + L.lo + 2 * e);
-    }
-    const uint32_t base = reinterpret_cast<const uint32_t*>(slot + L.idx)[gstart / kGroup];
-    uint32_t vmask = 0xFFu;
-    if (!FAST) vmask = e >= n ? 0u : (n - e >= 8 ? 0xFFu : ((1u << (uint32_t)(n - e)) - 1u));
-    const uint32_t m = ~(b0 | b1 | b2) & vmask;    /* code 0 = zero-point; tail bits are not */
-    const uint32_t cnt = __popc(m);
-    const uint32_t inc = wave_incl_scan(cnt);
-    const uint32_t gtot = __builtin_amdgcn_readlane(inc, 63);
-
-    /* code bytes of values 0..3 and 4..7, then exponent = dec[1] - 1 + code */
-    const uint32_t k4 = (e0 - 1u) * 0x01010101u;
-    uint32_t eA = (spread4(b0 & 15u) | (spread4(b1 & 15u) << 1) | (spread4(b2 & 15u) << 2)) + k4;
-    uint32_t eB = (spread4(b0 >> 4) | (spread4(b1 >> 4) << 1) | (spread4(b2 >> 4) << 2)) + k4;
-
-    bool bad = false;
-    if (gtot != 0u) {
-        /* the lane's zero-point exponents are the bytes [pos, pos + cnt) of the list */
-        const uint32_t loff = inc - cnt;
-        const bool base_ok = base <= n_esc;
-        const uint32_t room = base_ok ? n_esc - base : 0u;
-        const bool lane_ok = loff + cnt <= room;
-        bad = !lane_ok && cnt != 0u;
-        if (n_esc != 0u) {
-            const uint32_t pos = lane_ok ? base + loff : 0u;
-            const uint32_t last = (n_esc - 1u) & ~3u;        /* last aligned word holding a list byte */
-            const uint32_t a0 = pos & ~3u;
-            const uint32_t* __restrict__ esc32 = reinterpret_cast<const uint32_t*>(slot + L.esc);
-            const uint32_t d0 = esc32[min(a0, last) >> 2];
-            const uint32_t d1 = esc32[min(a0 + 4u, last) >> 2];
-            const uint32_t d2 = esc32[min(a0 + 8u, last) >> 2];
-            const uint32_t l8 = __builtin_amdgcn_alignbyte(d1, d0, pos & 3u);
-            const uint32_t h8 = __builtin_amdgcn_alignbyte(d2, d1, pos & 3u);
-            const uint32_t mA = m & 15u, mB = m >> 4;
-            const uint32_t nA = __popc(mA);
-            const uint2 tA = lut[mA], tB = lut[mB];
-            const uint32_t xB = nA == 4u ? h8 : __builtin_amdgcn_alignbyte(h8, l8, nA);
-            eA = bfi(tA.y, perm(0u, l8, tA.x), eA);
-            eB = bfi(tB.y, perm(0u, xB, tB.x), eB);
+        if (FAST || 2 * e < pad128(2 * n)) {
+            const u32x4 v = ld_stream<u32x4>(slot + L.lo + 2 * e);
+            r.lo[0] = v.x; r.lo[1] = v.y; r.lo[2] = v.z; r.lo[3] = v.w;
         }
     }
+    r.base = reinterpret_cast<const uint32_t*>(slot + L.idx)[gstart / kGroup];
+    r.vmask = 0xFFu;
+    if (!FAST) r.vmask = e >= n ? 0u : (n - e >= 8 ? 0xFFu : ((1u << (uint32_t)(n - e)) - 1u));
+    return r;
+}
 
+/* Locate the lane's zero-point bytes (wave scan of the per-lane counts) and issue their loads. */
+__device__ __forceinline__ DecEsc decode_locate(const uint8_t* __restrict__ slot, const SlotLayout& L,
+                                                const DecIn& in, uint32_t n_esc)
+{
+    DecEsc r;
+    r.m = ~(in.b0 | in.b1 | in.b2) & in.vmask;     /* code 0 = zero-point; tail bits are not */
+    const uint32_t cnt = __popc(r.m);
+    const uint32_t inc = wave_incl_scan(cnt);
+    r.any = __builtin_amdgcn_readlane(inc, 63) != 0u;
+    r.bad = false;
+    r.pos = r.d0 = r.d1 = r.d2 = 0;
+    if (r.any) {
+        /* the lane's zero-point exponents are the bytes [pos, pos + cnt) of the list */
+        const uint32_t loff = inc - cnt;
+        const uint32_t room = in.base <= n_esc ? n_esc - in.base : 0u;
+        const bool lane_ok = loff + cnt <= room;
+        r.bad = !lane_ok && cnt != 0u;
+        if (n_esc != 0u) {
+            r.pos = lane_ok ? in.base + loff : 0u;
+            const uint32_t last = (n_esc - 1u) & ~3u;       /* last aligned word holding a list byte */
+            const uint32_t a0 = r.pos & ~3u;
+            const uint32_t* __restrict__ esc32 = reinterpret_cast<const uint32_t*>(slot + L.esc);
+            r.d0 = esc32[min(a0, last) >> 2];
+            r.d1 = esc32[min(a0 + 4u, last) >> 2];
+            r.d2 = esc32[min(a0 + 8u, last) >> 2];
+        }
+    }
+    return r;
+}
+
+/* Rebuild the 8 values (section 4, third paragraph) and store them. */
+template <int DT, bool FAST>
+__device__ __forceinline__ void decode_store(uint8_t* __restrict__ cout, const DecIn& in, const DecEsc& es,
+                                             uint64_t gstart, uint32_t e0, uint32_t lane,
+                                             const uint2* __restrict__ lut)
+{
+    const uint64_t e = gstart + lane * kLaneElems;
+    /* code bytes of values 0..3 and 4..7, then exponent = dec[1] - 1 + code */
+    const uint32_t k4 = (e0 - 1u) * 0x01010101u;
+    uint32_t eA = (spread4(in.b0 & 15u) | (spread4(in.b1 & 15u) << 1) | (spread4(in.b2 & 15u) << 2)) + k4;
+    uint32_t eB = (spread4(in.b0 >> 4) | (spread4(in.b1 >> 4) << 1) | (spread4(in.b2 >> 4) << 2)) + k4;
+    if (es.any) {
+        const uint32_t l8 = __builtin_amdgcn_alignbyte(es.d1, es.d0, es.pos & 3u);
+        const uint32_t h8 = __builtin_amdgcn_alignbyte(es.d2, es.d1, es.pos & 3u);
+        const uint32_t mA = es.m & 15u, mB = es.m >> 4;
+        const uint32_t nA = __popc(mA);
+        const uint2 tA = lut[mA], tB = lut[mB];
+        const uint32_t xB = nA == 4u ? h8 : __builtin_amdgcn_alignbyte(h8, l8, nA);
+        eA = bfi(tA.y, perm(0u, l8, tA.x), eA);
+        eB = bfi(tB.y, perm(0u, xB, tB.x), eB);
+    }
     /* recombine with sign and mantissa: low byte = mantissa | E bit 0 << 7, high = sign | E >> 1 */
-    const uint32_t lA = bfi(0x7F7F7F7Fu, sm.x, eA << 7), hA = bfi(0x80808080u, sm.x, eA >> 1);
-    const uint32_t lB = bfi(0x7F7F7F7Fu, sm.y, eB << 7), hB = bfi(0x80808080u, sm.y, eB >> 1);
+    const uint32_t lA = bfi(0x7F7F7F7Fu, in.sm0, eA << 7), hA = bfi(0x80808080u, in.sm0, eA >> 1);
+    const uint32_t lB = bfi(0x7F7F7F7Fu, in.sm1, eB << 7), hB = bfi(0x80808080u, in.sm1, eB >> 1);
     const uint32_t hp[4] = {perm(hA, lA, 0x05010400u), perm(hA, lA, 0x07030602u),
                             perm(hB, lB, 0x05010400u), perm(hB, lB, 0x07030602u)};
-    const uint32_t low[4] = {lo.x, lo.y, lo.z, lo.w};
     if (FAST) {
         if (DT == ZIPCCL_BF16) {
-            *reinterpret_cast<uint4*>(cout + e * 2) = make_uint4(hp[0], hp[1], hp[2], hp[3]);
+            st_stream<u32x4>(cout + e * 2, u32x4{hp[0], hp[1], hp[2], hp[3]});
         } else {
             uint32_t x[8];
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                x[2 * k] = perm(hp[k], low[k], 0x05040100u);
-                x[2 * k + 1] = perm(hp[k], low[k], 0x07060302u);
+                x[2 * k] = perm(hp[k], in.lo[k], 0x05040100u);
+                x[2 * k + 1] = perm(hp[k], in.lo[k], 0x07060302u);
             }
-            *reinterpret_cast<uint4*>(cout + e * 4) = make_uint4(x[0], x[1], x[2], x[3]);
-            *reinterpret_cast<uint4*>(cout + e * 4 + 16) = make_uint4(x[4], x[5], x[6], x[7]);
+            st_stream<u32x4>(cout + e * 4, u32x4{x[0], x[1], x[2], x[3]});
+            st_stream<u32x4>(cout + e * 4 + 16, u32x4{x[4], x[5], x[6], x[7]});
         }
     } else {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            if ((vmask >> j) & 1u) {
+            if ((in.vmask >> j) & 1u) {
                 const uint32_t h = (hp[j >> 1] >> (16 * (j & 1))) & 0xFFFFu;
                 if (DT == ZIPCCL_BF16) {
                     *reinterpret_cast<uint16_t*>(cout + (e + j) * 2) = (uint16_t)h;
                 } else {
-                    const uint32_t l = (low[j >> 1] >> (16 * (j & 1))) & 0xFFFFu;
+                    const uint32_t l = (in.lo[j >> 1] >> (16 * (j & 1))) & 0xFFFFu;
                     *reinterpret_cast<uint32_t*>(cout + (e + j) * 4) = (h << 16) | l;
                 }
             }
         }
     }
-    return bad;
 }
 
 template <int DT>
@@ -569,35 +669,49 @@ __global__ __launch_bounds__(kThreads) void k_decompress(const DecompressArgs a)
     const uint32_t wave = threadIdx.x >> 6;
     bool bad = false;
     if (fast) {
+        /* three phases over the wave's four groups, so that each phase's loads are all in flight together */
+        DecIn in[kGroupsPerWave];
+        DecEsc es[kGroupsPerWave];
+#pragma unroll
+        for (uint32_t u = 0; u < kGroupsPerWave; ++u)
+            in[u] = decode_load<DT, true>(slot, L, n, ts + (uint64_t)(u * kWavesPerBlock + wave) * kGroup, lane);
+#pragma unroll
+        for (uint32_t u = 0; u < kGroupsPerWave; ++u) es[u] = decode_locate(slot, L, in[u], (uint32_t)n_esc);
 #pragma unroll
         for (uint32_t u = 0; u < kGroupsPerWave; ++u) {
-            const uint64_t gstart = ts + (uint64_t)(u * kWavesPerBlock + wave) * kGroup;
-            bad |= decode_group<DT, true>(slot, cout, L, n, (uint32_t)n_esc, gstart, e0, lane, s_lut);
+            decode_store<DT, true>(cout, in[u], es[u], ts + (uint64_t)(u * kWavesPerBlock + wave) * kGroup, e0, lane, s_lut);
+            bad |= es[u].bad;
         }
     } else {
         for (uint32_t u = 0; u < kGroupsPerWave; ++u) {
             const uint64_t gstart = ts + (uint64_t)(u * kWavesPerBlock + wave) * kGroup;
-            if (gstart < n) bad |= decode_group<DT, false>(slot, cout, L, n, (uint32_t)n_esc, gstart, e0, lane, s_lut);
+            if (gstart < n) {
+                const DecIn in = decode_load<DT, false>(slot, L, n, gstart, lane);
+                const DecEsc es = decode_locate(slot, L, in, (uint32_t)n_esc);
+                decode_store<DT, false>(cout, in, es, gstart, e0, lane, s_lut);
+                bad |= es.bad;
+            }
         }
     }
     if (bad && a.status) atomicOr(a.status, (uint32_t)ZIPCCL_ERR_CORRUPT);
 }
 
-__global__ __launch_bounds__(kThreads) void k_fill_zero(uint64_t* p, uint64_t n_words)
+/* Yardstick: plain copy, 16 bytes per lane, one load and one store per thread. */
+__global__ __launch_bounds__(kThreads) void k_copy(const u32x4* __restrict__ src, u32x4* __restrict__ dst, uint64_t n16)
 {
     const uint64_t i = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (i < n_words) p[i] = 0;
+    if (i < n16) dst[i] = src[i];
 }
 
 } // namespace
 
-int launch_fill_zero(void* d_ptr, uint64_t bytes, void* stream)
+int launch_copy(void* d_dst, const void* d_src, uint64_t bytes, void* stream)
 {
-    const uint64_t words = (bytes + 7) / 8;
-    if (words == 0) return (int)hipSuccess;
-    const uint32_t blocks = (uint32_t)((words + kThreads - 1) / kThreads);
-    hipLaunchKernelGGL(k_fill_zero, dim3(blocks), dim3(kThreads), 0, (hipStream_t)stream,
-                       reinterpret_cast<uint64_t*>(d_ptr), words);
+    const uint64_t n16 = bytes / 16;
+    if (n16 == 0) return (int)hipSuccess;
+    const uint64_t blocks = (n16 + kThreads - 1) / kThreads;
+    hipLaunchKernelGGL(k_copy, dim3((uint32_t)blocks), dim3(kThreads), 0, (hipStream_t)stream,
+                       static_cast<const u32x4*>(d_src), static_cast<u32x4*>(d_dst), n16);
     return (int)hipGetLastError();
 }
 
@@ -627,7 +741,7 @@ int launch_tile_scan(const CompressArgs& a, void* stream)
 
 int launch_place(int dt, const CompressArgs& a, uint32_t n_tiles, void* stream)
 {
-    const dim3 grid((n_tiles + kWavesPerBlock - 1) / kWavesPerBlock), block(kThreads);
+    const dim3 grid((n_tiles + 15) / 16), block(kThreads);   /* 16 tiles per workgroup */
     if (dt == ZIPCCL_BF16)
         hipLaunchKernelGGL((k_place<ZIPCCL_BF16>), grid, block, 0, (hipStream_t)stream, a, n_tiles);
     else
