@@ -21,6 +21,8 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0            # MI355X HBM3E, published peak
+KERNELS = {"compress": "zipccl_compress = k_compress + k_tile_scan + k_place (one call, three launches)",
+           "decompress": "zipccl_decompress = k_decompress"}
 PAPER_CONTEXT = ("paper (64x RTX A6000, 200 Gb/s): communication time -1.35x, end-to-end training 1.18x; "
                  "it prints no codec GB/s, so vs_baseline is null")
 
@@ -159,7 +161,7 @@ def main():
     achieved = algo_bytes / (t_dom * 1e-3) / 1e9
     es = 2 if w.dtype == 0 else 4
     traffic = None
-    tfile = os.path.join(ROOT, "profiles", "traffic.json")
+    tfile = os.path.join(ROOT, "profiles", "hbm_traffic.json")     # from the rocprofv3 --pmc runs summarised beside it
     if os.path.exists(tfile):
         traffic = json.load(open(tfile)).get(f"{args.workload}:{dominant}")
 
@@ -174,7 +176,7 @@ def main():
         "compress_ms": round(tc, 4), "decompress_ms": round(td, 4),
         "compress_ms_min": round(float(r["tc_ms"].min()), 4), "decompress_ms_min": round(float(r["td_ms"].min()), 4),
         "compression_ratio": round(w.nbytes / r["comp_bytes"], 5),
-        "roofline": {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+        "roofline": {"bound": "hbm", "kernel": KERNELS[dominant], "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                      "algorithmic_bytes_per_launch": algo_bytes,
                      "compress_frac": round(algo_bytes / (tc * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
