@@ -498,29 +498,62 @@ __device__ __forceinline__ uint32_t spread4(uint32_t x)
     return __umul24(x, 0x204081u) & 0x01010101u;
 }
 
+/* Bytes of LDS per group for its zero-point exponents: 512 + up to 7 of misalignment, rounded up,
+ * + 8 so that a lane's three aligned words never leave the region. */
+constexpr uint32_t kEscRegion = 544;
+
 /* What a lane reads for its 8 values of one group. */
 struct DecIn {
     uint32_t sm0, sm1;       /* 8 sign+mantissa bytes */
     uint32_t b0, b1, b2;     /* plane bytes */
     uint32_t lo[4];          /* fp32: 8 low 16-bit words */
-    uint32_t base;           /* IDX entry of the group */
+    uint32_t base;           /* IDX entry of the group = list position of its first zero-point */
+    uint32_t count;          /* zero-points of the group according to IDX (next entry - this one) */
     uint32_t vmask;          /* bit j = value j exists */
+    bool idx_ok;             /* base <= next <= n_esc and count <= 512 */
 };
 
 /* The lane's zero-point bytes (up to 8, in element order) and where its mask says they go. */
 struct DecEsc {
     uint32_t m;              /* bit j = value j is a zero-point */
-    uint32_t pos;            /* list position of the lane's first zero-point */
-    uint32_t d0, d1, d2;     /* the three aligned words covering list bytes [pos, pos + 8) */
+    uint32_t sh;             /* byte offset of the lane's first zero-point inside d0 */
+    uint32_t d0, d1, d2;     /* three aligned words covering the lane's 8 list bytes */
     bool any;                /* the group has zero-points at all */
-    bool bad;                /* the lane's bytes would lie outside the list */
+    bool bad;                /* planes and IDX disagree about the group */
 };
 
-template <int DT, bool FAST>
-__device__ __forceinline__ DecIn decode_load(const uint8_t* __restrict__ slot, const SlotLayout& L, uint64_t n,
-                                             uint64_t gstart, uint32_t lane)
+/* Phase 0: the group's slice of the zero-point list by IDX alone (scalar loads). */
+__device__ __forceinline__ void decode_index(const uint8_t* __restrict__ slot, const SlotLayout& L, uint64_t n,
+                                             uint32_t n_esc, uint64_t gstart, DecIn& r, uint32_t& next)
 {
-    DecIn r;
+    const uint64_t g = gstart / kGroup, ng = (n + kGroup - 1) / kGroup;
+    const uint32_t* __restrict__ idx = reinterpret_cast<const uint32_t*>(slot + L.idx);
+    r.base = idx[g];
+    next = g + 1 < ng ? idx[g + 1] : n_esc;
+    r.idx_ok = r.base <= next && next <= n_esc && next - r.base <= kGroup;
+    r.count = r.idx_ok ? next - r.base : 0u;
+}
+
+/* Phase 1a: fetch the slice [base, base + count), 8 aligned bytes per lane (+ 8 more by lane 0 when a
+ * full group starts off alignment).  Aligned reads stay inside pad128(n_esc). */
+__device__ __forceinline__ void decode_fetch_list(const uint8_t* __restrict__ slot, const SlotLayout& L,
+                                                  const DecIn& r, uint32_t next, uint32_t lane, u32x2& v, u32x2& tail)
+{
+    v = u32x2{0u, 0u};
+    tail = u32x2{0u, 0u};
+    if (r.count != 0u) {
+        const uint32_t a8 = r.base & ~7u;
+        const uint32_t a = a8 + 8u * lane;
+        if (a < next) v = *reinterpret_cast<const u32x2*>(slot + L.esc + a);
+        if (lane == 0 && a8 + kGroup < next) tail = *reinterpret_cast<const u32x2*>(slot + L.esc + a8 + kGroup);
+    }
+}
+
+/* Phase 1b: the lane's SM bytes, plane bytes and (fp32) low words. */
+template <int DT, bool FAST>
+__device__ __forceinline__ void decode_load(const uint8_t* __restrict__ slot, const SlotLayout& L, uint64_t n,
+                                            uint64_t gstart, uint32_t lane, DecIn& r)
+{
     const uint64_t e = gstart + lane * kLaneElems;
     r.sm0 = r.sm1 = r.b0 = r.b1 = r.b2 = 0;
     r.lo[0] = r.lo[1] = r.lo[2] = r.lo[3] = 0;
@@ -540,38 +573,34 @@ __device__ __forceinline__ DecIn decode_load(const uint8_t* __restrict__ slot, c
             r.lo[0] = v.x; r.lo[1] = v.y; r.lo[2] = v.z; r.lo[3] = v.w;
         }
     }
-    r.base = reinterpret_cast<const uint32_t*>(slot + L.idx)[gstart / kGroup];
     r.vmask = 0xFFu;
     if (!FAST) r.vmask = e >= n ? 0u : (n - e >= 8 ? 0xFFu : ((1u << (uint32_t)(n - e)) - 1u));
-    return r;
 }
 
-/* Locate the lane's zero-point bytes (wave scan of the per-lane counts) and issue their loads. */
-__device__ __forceinline__ DecEsc decode_locate(const uint8_t* __restrict__ slot, const SlotLayout& L,
-                                                const DecIn& in, uint32_t n_esc)
+/* Phase 1c: park the slice in the wave's LDS region so that lanes can pick their bytes by position. */
+__device__ __forceinline__ void decode_park_list(uint8_t* lds, uint32_t lane, const u32x2& v, const u32x2& tail)
+{
+    *reinterpret_cast<u32x2*>(lds + 8u * lane) = v;
+    if (lane == 0) *reinterpret_cast<u32x2*>(lds + kGroup) = tail;
+}
+
+/* Phase 2: wave scan of the per-lane zero-point counts, then the lane's bytes from the LDS region. */
+__device__ __forceinline__ DecEsc decode_locate(const DecIn& in, const uint8_t* lds)
 {
     DecEsc r;
     r.m = ~(in.b0 | in.b1 | in.b2) & in.vmask;     /* code 0 = zero-point; tail bits are not */
     const uint32_t cnt = __popc(r.m);
     const uint32_t inc = wave_incl_scan(cnt);
-    r.any = __builtin_amdgcn_readlane(inc, 63) != 0u;
-    r.bad = false;
-    r.pos = r.d0 = r.d1 = r.d2 = 0;
-    if (r.any) {
-        /* the lane's zero-point exponents are the bytes [pos, pos + cnt) of the list */
-        const uint32_t loff = inc - cnt;
-        const uint32_t room = in.base <= n_esc ? n_esc - in.base : 0u;
-        const bool lane_ok = loff + cnt <= room;
-        r.bad = !lane_ok && cnt != 0u;
-        if (n_esc != 0u) {
-            r.pos = lane_ok ? in.base + loff : 0u;
-            const uint32_t last = (n_esc - 1u) & ~3u;       /* last aligned word holding a list byte */
-            const uint32_t a0 = r.pos & ~3u;
-            const uint32_t* __restrict__ esc32 = reinterpret_cast<const uint32_t*>(slot + L.esc);
-            r.d0 = esc32[min(a0, last) >> 2];
-            r.d1 = esc32[min(a0 + 4u, last) >> 2];
-            r.d2 = esc32[min(a0 + 8u, last) >> 2];
-        }
+    const uint32_t gtot = __builtin_amdgcn_readlane(inc, 63);
+    r.any = gtot != 0u;
+    r.bad = !in.idx_ok || gtot != in.count;        /* planes and IDX must agree */
+    r.sh = r.d0 = r.d1 = r.d2 = 0;
+    if (r.any && !r.bad) {
+        /* the lane's zero-point exponents are the bytes [p, p + cnt) of the region, p <= 7 + 512 - cnt */
+        const uint32_t p = (in.base & 7u) + (inc - cnt);
+        const uint32_t* w = reinterpret_cast<const uint32_t*>(lds + (p & ~3u));
+        r.d0 = w[0]; r.d1 = w[1]; r.d2 = w[2];
+        r.sh = p & 3u;
     }
     return r;
 }
@@ -587,9 +616,9 @@ __device__ __forceinline__ void decode_store(uint8_t* __restrict__ cout, const D
     const uint32_t k4 = (e0 - 1u) * 0x01010101u;
     uint32_t eA = (spread4(in.b0 & 15u) | (spread4(in.b1 & 15u) << 1) | (spread4(in.b2 & 15u) << 2)) + k4;
     uint32_t eB = (spread4(in.b0 >> 4) | (spread4(in.b1 >> 4) << 1) | (spread4(in.b2 >> 4) << 2)) + k4;
-    if (es.any) {
-        const uint32_t l8 = __builtin_amdgcn_alignbyte(es.d1, es.d0, es.pos & 3u);
-        const uint32_t h8 = __builtin_amdgcn_alignbyte(es.d2, es.d1, es.pos & 3u);
+    if (es.any && !es.bad) {
+        const uint32_t l8 = __builtin_amdgcn_alignbyte(es.d1, es.d0, es.sh);
+        const uint32_t h8 = __builtin_amdgcn_alignbyte(es.d2, es.d1, es.sh);
         const uint32_t mA = es.m & 15u, mB = es.m >> 4;
         const uint32_t nA = __popc(mA);
         const uint2 tA = lut[mA], tB = lut[mB];
@@ -636,6 +665,7 @@ __global__ __launch_bounds__(kThreads) void k_decompress(const DecompressArgs a)
 {
     constexpr uint32_t ES = DT == ZIPCCL_BF16 ? 2u : 4u;
     __shared__ uint2 s_lut[16];
+    __shared__ __attribute__((aligned(16))) uint8_t s_esc[kWavesPerBlock][kGroupsPerWave][kEscRegion];
     if (threadIdx.x < 16) s_lut[threadIdx.x] = expand_entry(threadIdx.x);
 
     const uint32_t t = blockIdx.x;
@@ -669,14 +699,27 @@ __global__ __launch_bounds__(kThreads) void k_decompress(const DecompressArgs a)
     const uint32_t wave = threadIdx.x >> 6;
     bool bad = false;
     if (fast) {
-        /* three phases over the wave's four groups, so that each phase's loads are all in flight together */
+        /* phases over the wave's four groups, so that each phase's loads are all in flight together
+           and no vector load depends on another vector load */
         DecIn in[kGroupsPerWave];
         DecEsc es[kGroupsPerWave];
+        uint32_t next[kGroupsPerWave];
+        u32x2 lv[kGroupsPerWave], lt[kGroupsPerWave];
 #pragma unroll
         for (uint32_t u = 0; u < kGroupsPerWave; ++u)
-            in[u] = decode_load<DT, true>(slot, L, n, ts + (uint64_t)(u * kWavesPerBlock + wave) * kGroup, lane);
+            decode_index(slot, L, n, (uint32_t)n_esc, ts + (uint64_t)(u * kWavesPerBlock + wave) * kGroup, in[u], next[u]);
 #pragma unroll
-        for (uint32_t u = 0; u < kGroupsPerWave; ++u) es[u] = decode_locate(slot, L, in[u], (uint32_t)n_esc);
+        for (uint32_t u = 0; u < kGroupsPerWave; ++u) decode_fetch_list(slot, L, in[u], next[u], lane, lv[u], lt[u]);
+#pragma unroll
+        for (uint32_t u = 0; u < kGroupsPerWave; ++u)
+            decode_load<DT, true>(slot, L, n, ts + (uint64_t)(u * kWavesPerBlock + wave) * kGroup, lane, in[u]);
+#pragma unroll
+        for (uint32_t u = 0; u < kGroupsPerWave; ++u) decode_park_list(s_esc[wave][u], lane, lv[u], lt[u]);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+        for (uint32_t u = 0; u < kGroupsPerWave; ++u) es[u] = decode_locate(in[u], s_esc[wave][u]);
 #pragma unroll
         for (uint32_t u = 0; u < kGroupsPerWave; ++u) {
             decode_store<DT, true>(cout, in[u], es[u], ts + (uint64_t)(u * kWavesPerBlock + wave) * kGroup, e0, lane, s_lut);
@@ -686,8 +729,17 @@ __global__ __launch_bounds__(kThreads) void k_decompress(const DecompressArgs a)
         for (uint32_t u = 0; u < kGroupsPerWave; ++u) {
             const uint64_t gstart = ts + (uint64_t)(u * kWavesPerBlock + wave) * kGroup;
             if (gstart < n) {
-                const DecIn in = decode_load<DT, false>(slot, L, n, gstart, lane);
-                const DecEsc es = decode_locate(slot, L, in, (uint32_t)n_esc);
+                DecIn in;
+                uint32_t next;
+                u32x2 lv, lt;
+                decode_index(slot, L, n, (uint32_t)n_esc, gstart, in, next);
+                decode_fetch_list(slot, L, in, next, lane, lv, lt);
+                decode_load<DT, false>(slot, L, n, gstart, lane, in);
+                decode_park_list(s_esc[wave][u], lane, lv, lt);
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                const DecEsc es = decode_locate(in, s_esc[wave][u]);
                 decode_store<DT, false>(cout, in, es, gstart, e0, lane, s_lut);
                 bad |= es.bad;
             }
