@@ -99,18 +99,20 @@ __device__ __forceinline__ uint32_t find_chunk(const ChunkTab& tab, uint32_t t)
  * Values that do not exist read as 0.
  */
 template <int DT, bool FAST>
-__device__ __forceinline__ void load_lane(const uint8_t* __restrict__ cin, uint64_t e, uint64_t n,
+__device__ __forceinline__ void load_lane(const uint8_t* __restrict__ cin, uint64_t gbase, uint32_t lane, uint64_t n,
                                           uint32_t hp[4], uint32_t lp[4], uint32_t& vmask)
 {
+    /* gbase (first value of the group) is wave-uniform: uniform 64-bit base + 32-bit lane offset */
+    const uint64_t e = gbase + lane * kLaneElems;
     if (FAST) {
         vmask = 0xFFu;
         if (DT == ZIPCCL_BF16) {
-            const u32x4 v = ld_stream<u32x4>(cin + e * 2);
+            const u32x4 v = ld_stream<u32x4>((cin + gbase * 2) + lane * 16u);
             hp[0] = v.x; hp[1] = v.y; hp[2] = v.z; hp[3] = v.w;
             lp[0] = lp[1] = lp[2] = lp[3] = 0;
         } else {
-            const u32x4 a = ld_stream<u32x4>(cin + e * 4);
-            const u32x4 b = ld_stream<u32x4>(cin + e * 4 + 16);
+            const u32x4 a = ld_stream<u32x4>((cin + gbase * 4) + lane * 32u);
+            const u32x4 b = ld_stream<u32x4>((cin + gbase * 4 + 16) + lane * 32u);
             const uint32_t x[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
@@ -198,15 +200,17 @@ __device__ __forceinline__ void compress_group(const uint8_t* __restrict__ cin, 
                                                const SlotLayout& L, uint64_t n, uint64_t ts, uint32_t gi,
                                                uint32_t k7, uint32_t lane, CompressShared& sh)
 {
-    const uint64_t e = ts + (uint64_t)gi * kGroup + lane * kLaneElems;
+    const uint64_t gbase = ts + (uint64_t)gi * kGroup;      /* wave-uniform */
+    const uint64_t e = gbase + lane * kLaneElems;
     uint32_t hp[4], lp[4], vmask;
-    load_lane<DT, FAST>(cin, e, n, hp, lp, vmask);
+    load_lane<DT, FAST>(cin, gbase, lane, n, hp, lp, vmask);
     const LaneEnc r = encode8(hp, k7);
     const uint32_t m = r.m & vmask;
     if (STORE) {
-        if (FAST || e < pad128(n)) st_stream<u32x2>(slot + L.sm + e, u32x2{r.sm0, r.sm1});
+        if (FAST || e < pad128(n)) st_stream<u32x2>((slot + L.sm + gbase) + lane * 8u, u32x2{r.sm0, r.sm1});
         if (DT == ZIPCCL_FP32) {
-            if (FAST || 2 * e < pad128(2 * n)) st_stream<u32x4>(slot + L.lo + 2 * e, u32x4{lp[0], lp[1], lp[2], lp[3]});
+            if (FAST || 2 * e < pad128(2 * n))
+                st_stream<u32x4>((slot + L.lo + 2 * gbase) + lane * 16u, u32x4{lp[0], lp[1], lp[2], lp[3]});
         }
         const uint32_t pi = gi * 64u + lane;
         sh.planes[0][pi] = (uint8_t)r.b0;
@@ -287,7 +291,7 @@ __global__ __launch_bounds__(kThreads) void k_compress(const CompressArgs a)
     const SlotLayout L = slot_layout(n, DT);
     const bool fast = (ts + kTile <= n) && ((reinterpret_cast<uintptr_t>(cin) & 15u) == 0);
     const uint32_t lane = lane_id();
-    const uint32_t wave = threadIdx.x >> 6;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   /* keep wave-derived math scalar */
     const uint32_t k7 = ((a.e0 - 1u) << 7) * 0x00010001u;
 
     if (fast) {
@@ -336,16 +340,16 @@ __global__ __launch_bounds__(kThreads) void k_compress(const CompressArgs a)
         const uint32_t k = wave - 1u;
         const uint64_t pb = ts / 8 + lane * 16u;
         if (fast || pb < L.plane_bytes)
-            st_stream<u32x4>(slot + L.p0 + k * L.plane_bytes + pb,
+            st_stream<u32x4>((slot + L.p0 + k * L.plane_bytes + ts / 8) + lane * 16u,
                              *reinterpret_cast<const u32x4*>(&sh.planes[k][lane * 16u]));
     }
     /* zero-point exponents: every wave copies the segments of its own groups, in element order */
-    const uint32_t wave_s = __builtin_amdgcn_readfirstlane(wave);
 #pragma unroll
     for (uint32_t u = 0; u < kGroupsPerWave; ++u) {
-        const uint32_t gi = u * kWavesPerBlock + wave_s;
+        const uint32_t gi = u * kWavesPerBlock + wave;
         const uint32_t cnt = __builtin_amdgcn_readlane(gc, gi);
         uint8_t* dst = esc + __builtin_amdgcn_readlane(gex, gi);
+#pragma unroll 1
         for (uint32_t i = lane; i < cnt; i += 64u) dst[i] = sh.esc[gi][i];
     }
 
@@ -554,22 +558,24 @@ template <int DT, bool FAST>
 __device__ __forceinline__ void decode_load(const uint8_t* __restrict__ slot, const SlotLayout& L, uint64_t n,
                                             uint64_t gstart, uint32_t lane, DecIn& r)
 {
+    /* gstart is wave-uniform: uniform 64-bit base + 32-bit lane offset */
     const uint64_t e = gstart + lane * kLaneElems;
     r.sm0 = r.sm1 = r.b0 = r.b1 = r.b2 = 0;
     r.lo[0] = r.lo[1] = r.lo[2] = r.lo[3] = 0;
     if (FAST || e < pad128(n)) {
-        const u32x2 v = ld_stream<u32x2>(slot + L.sm + e);
+        const u32x2 v = ld_stream<u32x2>((slot + L.sm + gstart) + lane * 8u);
         r.sm0 = v.x; r.sm1 = v.y;
     }
     const uint64_t pb = e >> 3;
     if (FAST || pb < L.plane_bytes) {
-        r.b0 = ld_stream<uint8_t>(slot + L.p0 + pb);
-        r.b1 = ld_stream<uint8_t>(slot + L.p0 + L.plane_bytes + pb);
-        r.b2 = ld_stream<uint8_t>(slot + L.p0 + 2 * L.plane_bytes + pb);
+        const uint8_t* pl = slot + L.p0 + (gstart >> 3);
+        r.b0 = ld_stream<uint8_t>(pl + lane);
+        r.b1 = ld_stream<uint8_t>((pl + L.plane_bytes) + lane);
+        r.b2 = ld_stream<uint8_t>((pl + 2 * L.plane_bytes) + lane);
     }
     if (DT == ZIPCCL_FP32) {
         if (FAST || 2 * e < pad128(2 * n)) {
-            const u32x4 v = ld_stream<u32x4>(slot + L.lo + 2 * e);
+            const u32x4 v = ld_stream<u32x4>((slot + L.lo + 2 * gstart) + lane * 16u);
             r.lo[0] = v.x; r.lo[1] = v.y; r.lo[2] = v.z; r.lo[3] = v.w;
         }
     }
@@ -633,7 +639,7 @@ __device__ __forceinline__ void decode_store(uint8_t* __restrict__ cout, const D
                             perm(hB, lB, 0x05010400u), perm(hB, lB, 0x07030602u)};
     if (FAST) {
         if (DT == ZIPCCL_BF16) {
-            st_stream<u32x4>(cout + e * 2, u32x4{hp[0], hp[1], hp[2], hp[3]});
+            st_stream<u32x4>((cout + gstart * 2) + lane * 16u, u32x4{hp[0], hp[1], hp[2], hp[3]});
         } else {
             uint32_t x[8];
 #pragma unroll
@@ -641,8 +647,8 @@ __device__ __forceinline__ void decode_store(uint8_t* __restrict__ cout, const D
                 x[2 * k] = perm(hp[k], in.lo[k], 0x05040100u);
                 x[2 * k + 1] = perm(hp[k], in.lo[k], 0x07060302u);
             }
-            st_stream<u32x4>(cout + e * 4, u32x4{x[0], x[1], x[2], x[3]});
-            st_stream<u32x4>(cout + e * 4 + 16, u32x4{x[4], x[5], x[6], x[7]});
+            st_stream<u32x4>((cout + gstart * 4) + lane * 32u, u32x4{x[0], x[1], x[2], x[3]});
+            st_stream<u32x4>((cout + gstart * 4 + 16) + lane * 32u, u32x4{x[4], x[5], x[6], x[7]});
         }
     } else {
 #pragma unroll
@@ -696,7 +702,7 @@ __global__ __launch_bounds__(kThreads) void k_decompress(const DecompressArgs a)
 
     const bool fast = (ts + kTile <= n) && ((reinterpret_cast<uintptr_t>(cout) & 15u) == 0);
     const uint32_t lane = lane_id();
-    const uint32_t wave = threadIdx.x >> 6;
+    const uint32_t wave = threadIdx.x >> 6;   /* left in a vector register: measured faster here than scalar addressing */
     bool bad = false;
     if (fast) {
         /* phases over the wave's four groups, so that each phase's loads are all in flight together

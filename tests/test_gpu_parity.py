@@ -211,3 +211,28 @@ def test_runs_on_a_side_stream():
         z.zipccl_decompress(d_out, d_back, w.n_elems, w.dtype, w.n_chunks, None, None, stream=s)
     s.synchronize()
     assert np.array_equal(d_back.cpu().numpy().view(np.uint16), w.data)
+
+
+def test_random_splits_and_contents_fuzz(compress_path):
+    """Seeded fuzz: random chunk splits (empty, tiny, multi-tile, odd sizes), dtypes, tables and value
+    mixes (Gaussian bulk, runs of zero-points, special values), each compared byte for byte."""
+    rng = np.random.default_rng(1234)
+    for case in range(12):
+        dtype = int(rng.integers(0, 2))
+        k = int(rng.integers(1, 12))
+        ce = rng.choice([0, 1, 5, 8, 100, 511, 512, 513, 4096, 8191, 8192, 8200, 20000, 33000], size=k).astype(np.uint64)
+        n = int(ce.sum())
+        sigma = float(np.exp(rng.uniform(np.log(1e-6), np.log(1e3))))
+        f = rng.standard_normal(n, dtype=np.float32) * np.float32(sigma)
+        # runs of values far outside the window (dense zero-point stretches) and specials
+        for _ in range(int(rng.integers(0, 4))):
+            if n:
+                s0 = int(rng.integers(0, n)); ln = int(rng.integers(1, 3000))
+                f[s0:s0 + ln] *= np.float32(1e6)
+        data = W.f32_to_bf16_words(f) if dtype == z.BF16 else f.view(np.uint32).copy()
+        if n > 10:
+            spec = np.array([0x0000, 0x8000, 0x7F80, 0xFF80, 0x7FC1, 0x0001], dtype=np.uint32)
+            pos = rng.integers(0, n, spec.size)
+            data[pos] = spec.astype(data.dtype) if dtype == z.BF16 else (spec << 16 | 0x1234).astype(np.uint32)
+        _say(f"[fuzz {case}] dtype={dtype} chunks={list(ce)} sigma={sigma:.3g} path={compress_path}")
+        check_parity(data, dtype, sigma, k, ce, label=f"fuzz{case}")
