@@ -16,6 +16,9 @@
  *     peer chunk is padded to 128 bytes; section 4.2.3 -- a per-group prefix count of
  *     zero-points is stored so a decoder can find each group's zero-points.
  *   - zo_decompress  : section 4 (third paragraph) -- the inverse.
+ *   - zo_decompress_reduce : section 3.3 and section 5.2 -- the device half of the zipped
+ *     Reduce-Scatter: decode the slices received from every peer and sum them locally in FP32
+ *     (the paper fixes FP32 for the local reduction of BF16 traffic), in peer order.
  *
  * The byte-level layout (where the paper is silent) is the one fixed for this build:
  * little-endian; per chunk a slot of
@@ -294,6 +297,56 @@ int zo_decompress(const void* comp, uint64_t comp_capacity, void* out, uint64_t 
         if (rc != ZO_OK) return rc;
         off += zo_slot_cap(n, dtype, G);
         dst += n * (uint64_t)es;
+    }
+    return ZO_OK;
+}
+
+/* fp32 -> bf16, round to nearest even; NaN keeps its sign and top payload bits and is made quiet. */
+static uint16_t f32_to_bf16_rne(float f)
+{
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    if ((u & 0x7F800000u) == 0x7F800000u && (u & 0x007FFFFFu)) return (uint16_t)((u >> 16) | 0x0040u);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+/*
+ * Section 3.3 / 5.2: local reduction after a zipped All-to-All.  comp holds n_peers slots of n
+ * elements each, back to back at their a-priori offsets (what a rank's receive buffer looks
+ * like); out[i] = ((x_0[i] + x_1[i]) + x_2[i]) + ... in FP32, peers in order, starting from
+ * x_0[i] itself.  bf16 inputs are widened exactly.  out_dtype ZO_FP32 writes floats, ZO_BF16
+ * writes the FP32 sum rounded to nearest even.  scratch holds one decoded slice (n elements
+ * of the input dtype).
+ */
+int zo_decompress_reduce(const void* comp, uint64_t comp_capacity, void* out, uint64_t n, int dtype,
+                         uint32_t n_peers, int out_dtype, void* scratch, float* acc)
+{
+    const int es = elem_size(dtype);
+    if (!es) return ZO_ERR_DTYPE;
+    if (out_dtype != ZO_BF16 && out_dtype != ZO_FP32) return ZO_ERR_DTYPE;
+    if (n_peers == 0 || !comp || (n && (!out || !scratch || !acc))) return ZO_ERR_ARG;
+    if (comp_capacity < 128) return ZO_ERR_CORRUPT;
+    const uint32_t G = get32((const uint8_t*)comp + 12);
+    if (G == 0) return ZO_ERR_CORRUPT;
+    const uint64_t cap = zo_slot_cap(n, dtype, G);
+    for (uint32_t p = 0; p < n_peers; ++p) {
+        const uint64_t off = (uint64_t)p * cap;
+        if (off > comp_capacity) return ZO_ERR_CORRUPT;
+        int rc = decompress_chunk((const uint8_t*)comp + off, comp_capacity - off, n, dtype, (uint8_t*)scratch);
+        if (rc != ZO_OK) return rc;
+        for (uint64_t i = 0; i < n; ++i) {
+            uint32_t bits;
+            if (dtype == ZO_BF16) bits = (uint32_t)((const uint16_t*)scratch)[i] << 16;
+            else bits = ((const uint32_t*)scratch)[i];
+            float x;
+            memcpy(&x, &bits, 4);
+            acc[i] = p == 0 ? x : acc[i] + x;
+        }
+    }
+    for (uint64_t i = 0; i < n; ++i) {
+        if (out_dtype == ZO_FP32) ((float*)out)[i] = acc[i];
+        else ((uint16_t*)out)[i] = f32_to_bf16_rne(acc[i]);
     }
     return ZO_OK;
 }

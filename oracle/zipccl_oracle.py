@@ -56,6 +56,8 @@ def _load():
         lib.zo_compress.argtypes = [vp, u64, i32, u32, u32, vp, vp, vp, u64, vp]
         lib.zo_decompress.restype = i32
         lib.zo_decompress.argtypes = [vp, u64, vp, u64, i32, u32, vp]
+        lib.zo_decompress_reduce.restype = i32
+        lib.zo_decompress_reduce.argtypes = [vp, u64, vp, u64, i32, u32, i32, vp, vp]
         _lib = lib
     return _lib
 
@@ -137,4 +139,19 @@ def decompress(comp, n_elems, dtype, n_chunks=1, chunk_elems=None):
     rc = _load().zo_decompress(_ptr(comp), comp.size, _ptr(out), int(n_elems), dtype, n_chunks, _ptr(ce))
     if rc:
         raise OracleError(rc, "decompress")
+    return out
+
+
+def decompress_reduce(comp, n_elems, dtype, n_peers, out_dtype=FP32):
+    """Decode n_peers back-to-back slots of n_elems values each and sum them in fp32, peers in order.
+    Returns uint32 words of the fp32 sums (out_dtype FP32) or uint16 bf16 words (out_dtype BF16)."""
+    comp = np.ascontiguousarray(comp).view(np.uint8)
+    n = int(n_elems)
+    out = np.zeros(n, dtype=np.uint32 if out_dtype == FP32 else np.uint16)
+    scratch = np.zeros(n, dtype=np.uint16 if dtype == BF16 else np.uint32)
+    acc = np.zeros(n, dtype=np.float32)
+    rc = _load().zo_decompress_reduce(_ptr(comp), comp.size, _ptr(out), n, dtype, int(n_peers), out_dtype,
+                                      _ptr(scratch), _ptr(acc))
+    if rc:
+        raise OracleError(rc, "decompress_reduce")
     return out
