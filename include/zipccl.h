@@ -139,6 +139,22 @@ zipccl_status_t zipccl_decompress(const void* d_comp, size_t comp_capacity,
                                   uint32_t n_chunks, const uint64_t* chunk_elems,
                                   uint32_t* d_status, void* stream);
 
+/*
+ * Decompress and reduce: the local half of the zipped Reduce-Scatter (section 3.3; section 5.2
+ * fixes FP32 for the local reduction of BF16 traffic).  d_comp holds the n_peers slots a rank has
+ * received for its shard, back to back at the a-priori offsets of an equal split (slot p at
+ * p * zipccl_max_compressed_size(n_elems, dt, 1, NULL)), n_elems values each; every slot may carry
+ * its own table.  out[i] = ((x_0[i] + x_1[i]) + x_2[i]) + ... in FP32, peers in slot order, starting
+ * from x_0[i] itself (bf16 inputs are widened exactly), so the result is reproducible bit for bit.
+ *   d_out    device, n_elems values of out_dt: ZIPCCL_FP32 = the sums, ZIPCCL_BF16 = the sums
+ *            rounded to nearest even (NaN made quiet); aligned to its element size
+ *   d_status as in zipccl_decompress; a corrupt slot is left out of the sum
+ * comp_capacity must cover the static part of every slot.  Asynchronous on `stream`.
+ */
+zipccl_status_t zipccl_decompress_reduce(const void* d_comp, size_t comp_capacity, void* d_out, size_t n_elems,
+                                         zipccl_dtype_t dt, uint32_t n_peers, zipccl_dtype_t out_dt,
+                                         uint32_t* d_status, void* stream);
+
 const char* zipccl_status_string(zipccl_status_t s);
 
 /*

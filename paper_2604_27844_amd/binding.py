@@ -58,6 +58,8 @@ def _load():
     lib.zipccl_debug_copy.argtypes = [vp, vp, sz, vp]
     lib.zipccl_debug_compress_path.restype = i32
     lib.zipccl_debug_compress_path.argtypes = [i32]
+    lib.zipccl_decompress_reduce.restype = i32
+    lib.zipccl_decompress_reduce.argtypes = [vp, sz, vp, sz, i32, u32, i32, vp, vp]
     lib.zipccl_status_string.restype = ctypes.c_char_p
     lib.zipccl_status_string.argtypes = [i32]
     return lib
@@ -65,7 +67,7 @@ def _load():
 
 _lib = _load()
 EXPORTS = ("zipccl_build_table", "zipccl_max_compressed_size", "zipccl_chunk_slot_offsets",
-           "zipccl_compress_workspace_size", "zipccl_compress_min_workspace_size", "zipccl_compress", "zipccl_decompress", "zipccl_status_string",
+           "zipccl_compress_workspace_size", "zipccl_compress_min_workspace_size", "zipccl_compress", "zipccl_decompress", "zipccl_decompress_reduce", "zipccl_status_string",
            "zipccl_debug_compress_path", "zipccl_debug_copy")
 
 
@@ -158,3 +160,12 @@ def zipccl_decompress(d_comp, d_out, n_elems, dt, n_chunks=1, chunk_elems=None, 
                                 _dptr(d_status), _stream(stream))
     if rc:
         raise ZipcclError(rc, "zipccl_decompress")
+
+
+def zipccl_decompress_reduce(d_comp, d_out, n_elems, dt, n_peers, out_dt=FP32, d_status=None, stream=None,
+                             comp_capacity=None):
+    cap = d_comp.numel() * d_comp.element_size() if comp_capacity is None else int(comp_capacity)
+    rc = _lib.zipccl_decompress_reduce(_dptr(d_comp), cap, _dptr(d_out), int(n_elems), dt, int(n_peers), out_dt,
+                                       _dptr(d_status), _stream(stream))
+    if rc:
+        raise ZipcclError(rc, "zipccl_decompress_reduce")

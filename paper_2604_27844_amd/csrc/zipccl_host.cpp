@@ -280,6 +280,28 @@ zipccl_status_t zipccl_decompress(const void* d_comp, size_t comp_capacity,
     return ZIPCCL_OK;
 }
 
+zipccl_status_t zipccl_decompress_reduce(const void* d_comp, size_t comp_capacity, void* d_out, size_t n_elems,
+                                         zipccl_dtype_t dt, uint32_t n_peers, zipccl_dtype_t out_dt,
+                                         uint32_t* d_status, void* stream)
+{
+    if (!dtype_ok(dt) || !dtype_ok(out_dt)) return ZIPCCL_ERR_UNSUPPORTED_DTYPE;
+    if (n_peers == 0 || n_elems > ZIPCCL_MAX_CHUNK_ELEMS || !d_comp || (!d_out && n_elems)) return ZIPCCL_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(d_comp) % ZIPCCL_ALIGN) || (reinterpret_cast<uintptr_t>(d_out) % elem_size(out_dt)) ||
+        (reinterpret_cast<uintptr_t>(d_status) % 4))
+        return ZIPCCL_ERR_INVALID_ARG;
+    const SlotLayout L = slot_layout(n_elems, dt);
+    if ((uint64_t)(n_peers - 1) * L.cap + L.esc > comp_capacity) return ZIPCCL_ERR_BUFFER_TOO_SMALL;
+    ReduceArgs a;
+    a.comp = static_cast<const uint8_t*>(d_comp);
+    a.comp_capacity = comp_capacity;
+    a.slot_cap = L.cap;
+    a.out = static_cast<uint8_t*>(d_out);
+    a.status = d_status;
+    a.n = n_elems;
+    a.n_peers = n_peers;
+    return launch_decompress_reduce(dt, out_dt, a, (uint32_t)tiles_of(n_elems), stream) == 0 ? ZIPCCL_OK : ZIPCCL_ERR_DEVICE;
+}
+
 zipccl_status_t zipccl_debug_copy(void* d_dst, const void* d_src, size_t bytes, void* stream)
 {
     if (!d_dst || !d_src || (reinterpret_cast<uintptr_t>(d_dst) % 16) || (reinterpret_cast<uintptr_t>(d_src) % 16) ||

@@ -97,6 +97,16 @@ struct DecompressArgs {
 /* kModeStash: single pass over the input; zero-point exponents go to a stash at a position that
  * does not depend on other tiles, and k_place moves them once the tile prefixes are known.
  * kModeCount + kModeEmit: the same without a stash, reading the input twice. */
+struct ReduceArgs {
+    const uint8_t* comp;     /* n_peers slots of n values each, back to back */
+    uint64_t comp_capacity;  /* readable bytes from comp */
+    uint64_t slot_cap;       /* bytes from one slot to the next */
+    uint8_t* out;            /* n sums */
+    uint32_t* status;        /* may be null */
+    uint64_t n;
+    uint32_t n_peers;
+};
+
 enum CompressMode { kModeCount = 0, kModeEmit = 1, kModeStash = 2 };
 
 /* launchers implemented in zipccl_kernels.hip; return a hipError_t as int */
@@ -105,6 +115,7 @@ int launch_compress(int dt, int mode, const CompressArgs& a, uint32_t n_tiles, v
 int launch_tile_scan(const CompressArgs& a, void* stream);
 int launch_place(int dt, const CompressArgs& a, uint32_t n_tiles, void* stream);
 int launch_decompress(int dt, const DecompressArgs& a, uint32_t n_tiles, void* stream);
+int launch_decompress_reduce(int dt, int out_dt, const ReduceArgs& a, uint32_t n_tiles, void* stream);
 
 } // namespace zipccl
 #endif

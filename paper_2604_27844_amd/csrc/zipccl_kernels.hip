@@ -254,7 +254,7 @@ __device__ __forceinline__ void finish_chunk(uint8_t* __restrict__ slot, const S
             case 3: w = kGroup; break;
             case 4: w = (uint32_t)n; break;
             case 5: w = (uint32_t)(n >> 32); break;
-            case 6: w = (uint32_t)n_esc; break;
+            case 6: w = n_esc; break;
             case 7: w = (uint32_t)(n_esc >> 32); break;
             case 8: w = (uint32_t)cbytes; break;
             case 9: w = (uint32_t)(cbytes >> 32); break;
@@ -611,13 +611,10 @@ __device__ __forceinline__ DecEsc decode_locate(const DecIn& in, const uint8_t* 
     return r;
 }
 
-/* Rebuild the 8 values (section 4, third paragraph) and store them. */
-template <int DT, bool FAST>
-__device__ __forceinline__ void decode_store(uint8_t* __restrict__ cout, const DecIn& in, const DecEsc& es,
-                                             uint64_t gstart, uint32_t e0, uint32_t lane,
-                                             const uint2* __restrict__ lut)
+/* Rebuild the high 16-bit words of the lane's 8 values (section 4, third paragraph), packed in pairs. */
+__device__ __forceinline__ void decode_values(const DecIn& in, const DecEsc& es, uint32_t e0,
+                                              const uint2* __restrict__ lut, uint32_t hp[4])
 {
-    const uint64_t e = gstart + lane * kLaneElems;
     /* code bytes of values 0..3 and 4..7, then exponent = dec[1] - 1 + code */
     const uint32_t k4 = (e0 - 1u) * 0x01010101u;
     uint32_t eA = (spread4(in.b0 & 15u) | (spread4(in.b1 & 15u) << 1) | (spread4(in.b2 & 15u) << 2)) + k4;
@@ -635,8 +632,21 @@ __device__ __forceinline__ void decode_store(uint8_t* __restrict__ cout, const D
     /* recombine with sign and mantissa: low byte = mantissa | E bit 0 << 7, high = sign | E >> 1 */
     const uint32_t lA = bfi(0x7F7F7F7Fu, in.sm0, eA << 7), hA = bfi(0x80808080u, in.sm0, eA >> 1);
     const uint32_t lB = bfi(0x7F7F7F7Fu, in.sm1, eB << 7), hB = bfi(0x80808080u, in.sm1, eB >> 1);
-    const uint32_t hp[4] = {perm(hA, lA, 0x05010400u), perm(hA, lA, 0x07030602u),
-                            perm(hB, lB, 0x05010400u), perm(hB, lB, 0x07030602u)};
+    hp[0] = perm(hA, lA, 0x05010400u);
+    hp[1] = perm(hA, lA, 0x07030602u);
+    hp[2] = perm(hB, lB, 0x05010400u);
+    hp[3] = perm(hB, lB, 0x07030602u);
+}
+
+/* Rebuild the 8 values and store them. */
+template <int DT, bool FAST>
+__device__ __forceinline__ void decode_store(uint8_t* __restrict__ cout, const DecIn& in, const DecEsc& es,
+                                             uint64_t gstart, uint32_t e0, uint32_t lane,
+                                             const uint2* __restrict__ lut)
+{
+    const uint64_t e = gstart + lane * kLaneElems;
+    uint32_t hp[4];
+    decode_values(in, es, e0, lut, hp);
     if (FAST) {
         if (DT == ZIPCCL_BF16) {
             st_stream<u32x4>((cout + gstart * 2) + lane * 16u, u32x4{hp[0], hp[1], hp[2], hp[3]});
@@ -666,6 +676,30 @@ __device__ __forceinline__ void decode_store(uint8_t* __restrict__ cout, const D
     }
 }
 
+/*
+ * Chunk header check (all wave-uniform): the static part is readable (the host checked it), magic,
+ * version, dtype, G and n must match the call, the table must be a window, and the zero-point
+ * list the header promises must fit into the readable bytes.
+ */
+template <int DT>
+__device__ __forceinline__ bool check_header(const uint8_t* __restrict__ slot, const SlotLayout& L, uint64_t n,
+                                             uint64_t slot_off, uint64_t comp_capacity, uint32_t& e0, uint32_t& n_esc)
+{
+    const uint32_t* hw = reinterpret_cast<const uint32_t*>(slot);
+    const uint64_t n_hdr = (uint64_t)hw[4] | ((uint64_t)hw[5] << 32);
+    const uint64_t ne = (uint64_t)hw[6] | ((uint64_t)hw[7] << 32);
+    const uint64_t cbytes = (uint64_t)hw[8] | ((uint64_t)hw[9] << 32);
+    const uint32_t dec_lo = hw[10], dec_hi = hw[11];
+    e0 = (dec_lo >> 8) & 0xFFu;
+    n_esc = (uint32_t)ne;
+    bool ok = hw[0] == kMagic && hw[1] == kVersion && hw[2] == (uint32_t)DT && hw[3] == kGroup;
+    ok = ok && n_hdr == n && ne <= n && cbytes == L.esc + pad128(ne);
+    ok = ok && slot_off + cbytes <= comp_capacity;
+    ok = ok && e0 >= 1u && e0 <= 249u && (dec_lo >> 8) == (e0 | ((e0 + 1u) << 8) | ((e0 + 2u) << 16)) &&
+         dec_hi == ((e0 + 3u) | ((e0 + 4u) << 8) | ((e0 + 5u) << 16) | ((e0 + 6u) << 24));
+    return ok;
+}
+
 template <int DT>
 __global__ __launch_bounds__(kThreads) void k_decompress(const DecompressArgs a)
 {
@@ -682,18 +716,8 @@ __global__ __launch_bounds__(kThreads) void k_decompress(const DecompressArgs a)
     uint8_t* __restrict__ cout = a.out + a.tab.elem_off[c] * ES;
     const SlotLayout L = slot_layout(n, DT);
 
-    /* header check: the static part is readable (the host checked it), the rest must match */
-    const uint32_t* hw = reinterpret_cast<const uint32_t*>(slot);
-    const uint64_t n_hdr = (uint64_t)hw[4] | ((uint64_t)hw[5] << 32);
-    const uint64_t n_esc = (uint64_t)hw[6] | ((uint64_t)hw[7] << 32);
-    const uint64_t cbytes = (uint64_t)hw[8] | ((uint64_t)hw[9] << 32);
-    const uint32_t dec_lo = hw[10], dec_hi = hw[11];
-    const uint32_t e0 = (dec_lo >> 8) & 0xFFu;
-    bool ok = hw[0] == kMagic && hw[1] == kVersion && hw[2] == (uint32_t)DT && hw[3] == kGroup;
-    ok = ok && n_hdr == n && n_esc <= n && cbytes == L.esc + pad128(n_esc);
-    ok = ok && a.tab.slot_off[c] + cbytes <= a.comp_capacity;
-    ok = ok && e0 >= 1u && e0 <= 249u && (dec_lo >> 8) == (e0 | ((e0 + 1u) << 8) | ((e0 + 2u) << 16)) &&
-         dec_hi == ((e0 + 3u) | ((e0 + 4u) << 8) | ((e0 + 5u) << 16) | ((e0 + 6u) << 24));
+    uint32_t e0, n_esc;
+    const bool ok = check_header<DT>(slot, L, n, a.tab.slot_off[c], a.comp_capacity, e0, n_esc);
     __syncthreads();
     if (!ok) {
         if (threadIdx.x == 0 && a.status) atomicOr(a.status, (uint32_t)ZIPCCL_ERR_CORRUPT);
@@ -713,7 +737,7 @@ __global__ __launch_bounds__(kThreads) void k_decompress(const DecompressArgs a)
         u32x2 lv[kGroupsPerWave], lt[kGroupsPerWave];
 #pragma unroll
         for (uint32_t u = 0; u < kGroupsPerWave; ++u)
-            decode_index(slot, L, n, (uint32_t)n_esc, ts + (uint64_t)(u * kWavesPerBlock + wave) * kGroup, in[u], next[u]);
+            decode_index(slot, L, n, n_esc, ts + (uint64_t)(u * kWavesPerBlock + wave) * kGroup, in[u], next[u]);
 #pragma unroll
         for (uint32_t u = 0; u < kGroupsPerWave; ++u) decode_fetch_list(slot, L, in[u], next[u], lane, lv[u], lt[u]);
 #pragma unroll
@@ -738,7 +762,7 @@ __global__ __launch_bounds__(kThreads) void k_decompress(const DecompressArgs a)
                 DecIn in;
                 uint32_t next;
                 u32x2 lv, lt;
-                decode_index(slot, L, n, (uint32_t)n_esc, gstart, in, next);
+                decode_index(slot, L, n, n_esc, gstart, in, next);
                 decode_fetch_list(slot, L, in, next, lane, lv, lt);
                 decode_load<DT, false>(slot, L, n, gstart, lane, in);
                 decode_park_list(s_esc[wave][u], lane, lv, lt);
@@ -754,6 +778,104 @@ __global__ __launch_bounds__(kThreads) void k_decompress(const DecompressArgs a)
     if (bad && a.status) atomicOr(a.status, (uint32_t)ZIPCCL_ERR_CORRUPT);
 }
 
+/* fp32 bits -> bf16 bits, round to nearest even; NaN keeps sign and top payload bits and is made quiet */
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
+{
+    const uint32_t u = __float_as_uint(f);
+    const bool nan = (u & 0x7F800000u) == 0x7F800000u && (u & 0x007FFFFFu) != 0u;
+    return nan ? ((u >> 16) | 0x0040u) : ((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+}
+
+/*
+ * Local reduction of the zipped Reduce-Scatter (paper sections 3.3 and 5.2): decode the slices
+ * received from n_peers peers (slots back to back, n values each) and sum them in FP32, peers in
+ * slot order starting from peer 0's value.  One pass: every compressed byte is read once and
+ * only the sum is written.  Work decomposition as in k_decompress; the peer loop is innermost.
+ */
+template <int DT, int ODT>
+__global__ __launch_bounds__(kThreads) void k_decompress_reduce(const ReduceArgs a)
+{
+    constexpr uint32_t OES = ODT == ZIPCCL_BF16 ? 2u : 4u;
+    __shared__ uint2 s_lut[16];
+    __shared__ __attribute__((aligned(16))) uint8_t s_esc[kWavesPerBlock][kEscRegion];
+    if (threadIdx.x < 16) s_lut[threadIdx.x] = expand_entry(threadIdx.x);
+    __syncthreads();
+
+    const uint64_t n = a.n;
+    const uint64_t ts = (uint64_t)blockIdx.x * kTile;
+    const SlotLayout L = slot_layout(n, DT);
+    const bool fast = (ts + kTile <= n) && ((reinterpret_cast<uintptr_t>(a.out) & 15u) == 0);
+    const uint32_t lane = lane_id();
+    const uint32_t wave = threadIdx.x >> 6;
+    bool bad = false;
+    for (uint32_t u = 0; u < kGroupsPerWave; ++u) {
+        const uint64_t gstart = ts + (uint64_t)(u * kWavesPerBlock + wave) * kGroup;
+        if (gstart >= n) continue;
+        float acc[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] = 0.0f;
+        bool have = false;
+        const uint64_t e = gstart + lane * kLaneElems;
+        const uint32_t vmask = fast ? 0xFFu : (e >= n ? 0u : (n - e >= 8 ? 0xFFu : ((1u << (uint32_t)(n - e)) - 1u)));
+        for (uint32_t p = 0; p < a.n_peers; ++p) {
+            const uint64_t slot_off = (uint64_t)p * a.slot_cap;
+            const uint8_t* __restrict__ slot = a.comp + slot_off;
+            uint32_t e0, n_esc;
+            if (!check_header<DT>(slot, L, n, slot_off, a.comp_capacity, e0, n_esc)) { bad = true; continue; }
+            DecIn in;
+            uint32_t next;
+            u32x2 lv, lt;
+            decode_index(slot, L, n, n_esc, gstart, in, next);
+            decode_fetch_list(slot, L, in, next, lane, lv, lt);
+            if (fast) decode_load<DT, true>(slot, L, n, gstart, lane, in);
+            else decode_load<DT, false>(slot, L, n, gstart, lane, in);
+            decode_park_list(s_esc[wave], lane, lv, lt);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            const DecEsc es = decode_locate(in, s_esc[wave]);
+            __builtin_amdgcn_wave_barrier();
+            bad |= es.bad;
+            uint32_t hp[4];
+            decode_values(in, es, e0, s_lut, hp);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                uint32_t w0, w1;
+                if (DT == ZIPCCL_BF16) { w0 = hp[k] << 16; w1 = hp[k] & 0xFFFF0000u; }
+                else { w0 = perm(hp[k], in.lo[k], 0x05040100u); w1 = perm(hp[k], in.lo[k], 0x07060302u); }
+                const float x0 = __uint_as_float(w0), x1 = __uint_as_float(w1);
+                acc[2 * k] = have ? acc[2 * k] + x0 : x0;
+                acc[2 * k + 1] = have ? acc[2 * k + 1] + x1 : x1;
+            }
+            have = true;
+        }
+        uint8_t* __restrict__ og = a.out + gstart * OES;
+        if (fast) {
+            if (ODT == ZIPCCL_FP32) {
+                st_stream<u32x4>(og + lane * 32u, u32x4{__float_as_uint(acc[0]), __float_as_uint(acc[1]),
+                                                        __float_as_uint(acc[2]), __float_as_uint(acc[3])});
+                st_stream<u32x4>((og + 16) + lane * 32u, u32x4{__float_as_uint(acc[4]), __float_as_uint(acc[5]),
+                                                               __float_as_uint(acc[6]), __float_as_uint(acc[7])});
+            } else {
+                uint32_t o[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) o[k] = f32_to_bf16_bits(acc[2 * k]) | (f32_to_bf16_bits(acc[2 * k + 1]) << 16);
+                st_stream<u32x4>(og + lane * 16u, u32x4{o[0], o[1], o[2], o[3]});
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                if ((vmask >> j) & 1u) {
+                    const uint64_t i = lane * kLaneElems + j;
+                    if (ODT == ZIPCCL_FP32) *reinterpret_cast<float*>(og + i * 4) = acc[j];
+                    else *reinterpret_cast<uint16_t*>(og + i * 2) = (uint16_t)f32_to_bf16_bits(acc[j]);
+                }
+            }
+        }
+    }
+    if (bad && a.status) atomicOr(a.status, (uint32_t)ZIPCCL_ERR_CORRUPT);
+}
+
 /* Yardstick: plain copy, 16 bytes per lane, one load and one store per thread. */
 __global__ __launch_bounds__(kThreads) void k_copy(const u32x4* __restrict__ src, u32x4* __restrict__ dst, uint64_t n16)
 {
@@ -762,6 +884,21 @@ __global__ __launch_bounds__(kThreads) void k_copy(const u32x4* __restrict__ src
 }
 
 } // namespace
+
+int launch_decompress_reduce(int dt, int out_dt, const ReduceArgs& a, uint32_t n_tiles, void* stream)
+{
+    const dim3 grid(n_tiles), block(kThreads);
+    hipStream_t s = (hipStream_t)stream;
+    if (dt == ZIPCCL_BF16 && out_dt == ZIPCCL_FP32)
+        hipLaunchKernelGGL((k_decompress_reduce<ZIPCCL_BF16, ZIPCCL_FP32>), grid, block, 0, s, a);
+    else if (dt == ZIPCCL_BF16)
+        hipLaunchKernelGGL((k_decompress_reduce<ZIPCCL_BF16, ZIPCCL_BF16>), grid, block, 0, s, a);
+    else if (out_dt == ZIPCCL_FP32)
+        hipLaunchKernelGGL((k_decompress_reduce<ZIPCCL_FP32, ZIPCCL_FP32>), grid, block, 0, s, a);
+    else
+        hipLaunchKernelGGL((k_decompress_reduce<ZIPCCL_FP32, ZIPCCL_BF16>), grid, block, 0, s, a);
+    return (int)hipGetLastError();
+}
 
 int launch_copy(void* d_dst, const void* d_src, uint64_t bytes, void* stream)
 {

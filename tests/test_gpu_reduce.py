@@ -1,0 +1,104 @@
+"""GPU parity of zipccl_decompress_reduce against the oracle: FP32 sums in peer order are
+reproducible, so the bar is bit equality (elements whose sum is NaN: both sides NaN)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2604_27844_amd.binding as z
+from paper_2604_27844_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    from gpu_util import DEV
+
+
+def _peers(rng, P, n, dtype, sigmas):
+    out = []
+    for p in range(P):
+        f = rng.standard_normal(n, dtype=np.float32) * np.float32(sigmas[p % len(sigmas)])
+        out.append(W.f32_to_bf16_words(f) if dtype == z.BF16 else f.view(np.uint32).copy())
+    return out
+
+
+def _receive_buffer(peers, dtype, sigmas):
+    """Each peer compresses its slice with its own table (on the GPU); slots end up back to back."""
+    n = peers[0].size
+    cap1 = z.zipccl_max_compressed_size(n, dtype, 1)
+    buf = torch.full((cap1 * len(peers),), 0xA5, dtype=torch.uint8, device=DEV)
+    ws = torch.empty(z.zipccl_compress_workspace_size(n, dtype, 1), dtype=torch.uint8, device=DEV)
+    for p, x in enumerate(peers):
+        signed = np.int16 if dtype == z.BF16 else np.int32
+        d_in = torch.from_numpy(x.view(signed)).to(DEV)
+        z.zipccl_compress(d_in, n, dtype, 1, None, z.zipccl_build_table(sigmas[p % len(sigmas)], dtype),
+                          buf[p * cap1:(p + 1) * cap1], None, ws)
+        torch.cuda.synchronize()
+    return buf
+
+
+def _check(peers, dtype, sigmas, out_dt, label):
+    n, P = peers[0].size, len(peers)
+    buf = _receive_buffer(peers, dtype, sigmas)
+    want = oracle.decompress_reduce(buf.cpu().numpy(), n, dtype, P, out_dt)
+    d_out = torch.full((n,), 0x3C3C if out_dt == z.BF16 else 0x3C3C3C3C,
+                       dtype=torch.int16 if out_dt == z.BF16 else torch.int32, device=DEV)
+    d_st = torch.zeros(1, dtype=torch.int32, device=DEV)
+    z.zipccl_decompress_reduce(buf, d_out, n, dtype, P, out_dt, d_st)
+    torch.cuda.synchronize()
+    assert int(d_st.item()) == 0, label
+    got = d_out.cpu().numpy().view(np.uint16 if out_dt == z.BF16 else np.uint32)
+    if out_dt == z.FP32:
+        nan_w, nan_g = np.isnan(want.view(np.float32)), np.isnan(got.view(np.float32))
+    else:
+        f = lambda a: (a.astype(np.uint32) << 16).view(np.float32)
+        nan_w, nan_g = np.isnan(f(want)), np.isnan(f(got))
+    assert np.array_equal(nan_w, nan_g), label
+    ok = nan_w | (got == want)
+    assert ok.all(), f"{label}: {np.count_nonzero(~ok)} sums differ, first at {np.nonzero(~ok)[0][:5]}"
+
+
+@pytest.mark.parametrize("dtype", [z.BF16, z.FP32], ids=["bf16", "fp32"])
+@pytest.mark.parametrize("out_dt", [z.FP32, z.BF16], ids=["out_fp32", "out_bf16"])
+def test_reduce_parity(dtype, out_dt):
+    rng = np.random.default_rng(40 + dtype)
+    for P, n in ((1, 5000), (2, 8192), (3, 8193), (8, 3 * 8192 + 700), (5, 1), (4, 511), (16, 40000)):
+        print(f"[reduce] dtype={dtype} out={out_dt} P={P} n={n}", flush=True)
+        sig = [0.02, 0.02, 0.05, 1e-3]
+        _check(_peers(rng, P, n, dtype, sig), dtype, sig, out_dt, f"P={P} n={n}")
+
+
+def test_reduce_order_specials_and_cancellation():
+    n = 8192 + 37
+    big = np.full(n, W.f32_to_bf16_words(np.array([2.0 ** 30], dtype=np.float32))[0], dtype=np.uint16)
+    neg = big | np.uint16(0x8000)
+    one = np.full(n, 0x3F80, dtype=np.uint16)
+    for order in ([big, neg, one], [one, big, neg]):
+        _check(order, z.BF16, [1.0], z.FP32, "order")
+    rng = np.random.default_rng(3)
+    peers = [rng.integers(0, 65536, n, dtype=np.uint16, endpoint=False) for _ in range(4)]   # Inf, NaN, subnormals
+    _check(peers, z.BF16, [1.0], z.FP32, "specials")
+    _check(peers, z.BF16, [1.0], z.BF16, "specials bf16 out")
+    words = [rng.integers(0, 2 ** 32, n, dtype=np.uint64).astype(np.uint32) for _ in range(3)]
+    _check(words, z.FP32, [1.0], z.FP32, "fp32 specials")
+
+
+def test_reduce_flags_a_corrupt_slot_and_checks_arguments():
+    rng = np.random.default_rng(5)
+    n, P = 10000, 3
+    peers = _peers(rng, P, n, z.BF16, [0.02])
+    buf = _receive_buffer(peers, z.BF16, [0.02])
+    cap1 = z.zipccl_max_compressed_size(n, z.BF16, 1)
+    bad = buf.clone()
+    bad[cap1 + 1] = 0x00                                      # magic of peer 1
+    d_out = torch.zeros(n, dtype=torch.int32, device=DEV)
+    d_st = torch.zeros(1, dtype=torch.int32, device=DEV)
+    z.zipccl_decompress_reduce(bad, d_out, n, z.BF16, P, z.FP32, d_st)
+    torch.cuda.synchronize()
+    assert int(d_st.item()) == 4
+    with pytest.raises(z.ZipcclError) as ei:
+        z.zipccl_decompress_reduce(buf, d_out, n, z.BF16, P + 1, z.FP32, d_st)   # a fourth slot is not there
+    assert ei.value.code == 3
+    with pytest.raises(z.ZipcclError) as ei:
+        z.zipccl_decompress_reduce(buf, d_out, n, z.BF16, 0, z.FP32, d_st)
+    assert ei.value.code == 1
