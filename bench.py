@@ -91,6 +91,50 @@ def run_gpu(w, steps, warmup):
                 d_out=d_out, d_cb=d_cb, table=table)
 
 
+def run_reduce(w, peers, steps):
+    """The first widening beyond the codec: decode `peers` received slices and sum them in FP32
+    (zipccl_decompress_reduce).  The workload is cut into `peers` equal slices standing for the
+    peers' contributions to one shard."""
+    import torch
+    import paper_2604_27844_amd.binding as z
+    if w.dtype != z.BF16 or w.n_elems % peers:
+        return None
+    dev = torch.device("cuda:0")
+    n = w.n_elems // peers
+    d_in = torch.from_numpy(w.data.view(np.int16)).to(dev)
+    table = z.zipccl_build_table(w.sigma, w.dtype)
+    cap = z.zipccl_max_compressed_size(w.n_elems, w.dtype, peers)
+    d_comp = torch.empty(cap, dtype=torch.uint8, device=dev)
+    d_cb = torch.zeros(peers, dtype=torch.int64, device=dev)
+    d_ws = torch.empty(z.zipccl_compress_workspace_size(w.n_elems, w.dtype, peers), dtype=torch.uint8, device=dev)
+    z.zipccl_compress(d_in, w.n_elems, w.dtype, peers, None, table, d_comp, d_cb, d_ws)
+    d_sum = torch.empty(n, dtype=torch.float32, device=dev)
+    d_st = torch.zeros(1, dtype=torch.int32, device=dev)
+    stream = torch.cuda.current_stream()
+    z.zipccl_decompress_reduce(d_comp, d_sum, n, w.dtype, peers, z.FP32, d_st, stream=stream)
+    torch.cuda.synchronize()
+    assert int(d_st.item()) == 0
+    ref = d_in[:n].view(torch.bfloat16).float()
+    for p in range(1, peers):
+        ref = ref + d_in[p * n:(p + 1) * n].view(torch.bfloat16).float()
+    assert torch.equal(ref.view(torch.int32), d_sum.view(torch.int32)), "fused reduce differs from peer-ordered FP32 sum"
+    del ref
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(steps)]
+    for k in range(steps):
+        evs[k][0].record(stream)
+        z.zipccl_decompress_reduce(d_comp, d_sum, n, w.dtype, peers, z.FP32, d_st, stream=stream)
+        evs[k][1].record(stream)
+    torch.cuda.synchronize()
+    ms = float(np.mean([e[0].elapsed_time(e[1]) for e in evs]))
+    comp_bytes = int(d_cb.sum().item())
+    algo = comp_bytes + 4 * n
+    return {"peers": peers, "n_per_peer": n, "ms": round(ms, 4),
+            "uncompressed_in_GBps": round(w.nbytes / (ms * 1e-3) / 1e9, 1),
+            "algorithmic_bytes": algo, "hbm_GBps": round(algo / (ms * 1e-3) / 1e9, 1),
+            "hbm_frac": round(algo / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+            "checked": "bit-equal to the peer-ordered FP32 sum of the inputs"}
+
+
 def run_oracle(w, gpu_out=None, gpu_cb=None):
     """The oracle as it stands: single thread over the whole workload, then one chunk per host thread."""
     import oracle
@@ -200,6 +244,10 @@ def main():
                                "host_cores": o["host_cores"], "ratio": round(o["ratio"], 5),
                                "gpu_bytes_match_oracle": o["matches_gpu"]}
     del r
+    torch.cuda.empty_cache()
+    red = run_reduce(w, 8, max(3, args.steps // 2))
+    if red:
+        out["decompress_reduce"] = red
 
     if args.all:
         extra = {}

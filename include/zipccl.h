@@ -149,7 +149,8 @@ zipccl_status_t zipccl_decompress(const void* d_comp, size_t comp_capacity,
  *   d_out    device, n_elems values of out_dt: ZIPCCL_FP32 = the sums, ZIPCCL_BF16 = the sums
  *            rounded to nearest even (NaN made quiet); aligned to its element size
  *   d_status as in zipccl_decompress; a corrupt slot is left out of the sum
- * comp_capacity must cover the static part of every slot.  Asynchronous on `stream`.
+ * comp_capacity must cover the static part of every slot; 1 <= n_peers <= 1024.
+ * Asynchronous on `stream`.
  */
 zipccl_status_t zipccl_decompress_reduce(const void* d_comp, size_t comp_capacity, void* d_out, size_t n_elems,
                                          zipccl_dtype_t dt, uint32_t n_peers, zipccl_dtype_t out_dt,

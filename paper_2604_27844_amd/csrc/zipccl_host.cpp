@@ -285,7 +285,8 @@ zipccl_status_t zipccl_decompress_reduce(const void* d_comp, size_t comp_capacit
                                          uint32_t* d_status, void* stream)
 {
     if (!dtype_ok(dt) || !dtype_ok(out_dt)) return ZIPCCL_ERR_UNSUPPORTED_DTYPE;
-    if (n_peers == 0 || n_elems > ZIPCCL_MAX_CHUNK_ELEMS || !d_comp || (!d_out && n_elems)) return ZIPCCL_ERR_INVALID_ARG;
+    if (n_peers == 0 || n_peers > kMaxPeers || n_elems > ZIPCCL_MAX_CHUNK_ELEMS || !d_comp || (!d_out && n_elems))
+        return ZIPCCL_ERR_INVALID_ARG;
     if ((reinterpret_cast<uintptr_t>(d_comp) % ZIPCCL_ALIGN) || (reinterpret_cast<uintptr_t>(d_out) % elem_size(out_dt)) ||
         (reinterpret_cast<uintptr_t>(d_status) % 4))
         return ZIPCCL_ERR_INVALID_ARG;

@@ -26,6 +26,7 @@ constexpr uint32_t kMaxBatch = 128;                 /* chunks per kernel launch 
 constexpr uint32_t kVersion = 1;
 constexpr uint32_t kMagic = 0x4C43505Au;            /* "ZPCL" little-endian */
 constexpr uint32_t kWorkspaceHeader = 256;          /* bytes before the per-tile arrays */
+constexpr uint32_t kMaxPeers = 1024;                /* slots one zipccl_decompress_reduce call can sum */
 constexpr uint32_t kStashSlack = 64;                /* readable bytes past the last stash byte */
 
 /* header field offsets */

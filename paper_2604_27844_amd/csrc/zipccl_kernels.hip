@@ -798,34 +798,57 @@ __global__ __launch_bounds__(kThreads) void k_decompress_reduce(const ReduceArgs
     constexpr uint32_t OES = ODT == ZIPCCL_BF16 ? 2u : 4u;
     __shared__ uint2 s_lut[16];
     __shared__ __attribute__((aligned(16))) uint8_t s_esc[kWavesPerBlock][kEscRegion];
+    __shared__ uint32_t s_e0[kMaxPeers];      /* dec[1] of peer p's slot, 0 = header rejected */
+    __shared__ uint32_t s_nesc[kMaxPeers];    /* zero-points of peer p's slot */
     if (threadIdx.x < 16) s_lut[threadIdx.x] = expand_entry(threadIdx.x);
-    __syncthreads();
 
     const uint64_t n = a.n;
     const uint64_t ts = (uint64_t)blockIdx.x * kTile;
     const SlotLayout L = slot_layout(n, DT);
+    bool bad = false;
+    /* every slot's header is checked once per workgroup, one peer per thread */
+    for (uint32_t p = threadIdx.x; p < a.n_peers; p += kThreads) {
+        const uint64_t slot_off = (uint64_t)p * a.slot_cap;
+        uint32_t e0, n_esc;
+        const bool ok = check_header<DT>(a.comp + slot_off, L, n, slot_off, a.comp_capacity, e0, n_esc);
+        s_e0[p] = ok ? e0 : 0u;
+        s_nesc[p] = n_esc;
+        bad |= !ok;
+    }
+    __syncthreads();
+
     const bool fast = (ts + kTile <= n) && ((reinterpret_cast<uintptr_t>(a.out) & 15u) == 0);
     const uint32_t lane = lane_id();
     const uint32_t wave = threadIdx.x >> 6;
-    bool bad = false;
+    const uint64_t ng = (n + kGroup - 1) / kGroup;
     for (uint32_t u = 0; u < kGroupsPerWave; ++u) {
         const uint64_t gstart = ts + (uint64_t)(u * kWavesPerBlock + wave) * kGroup;
         if (gstart >= n) continue;
+        const uint64_t g = gstart / kGroup;
         float acc[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) acc[j] = 0.0f;
         bool have = false;
         const uint64_t e = gstart + lane * kLaneElems;
         const uint32_t vmask = fast ? 0xFFu : (e >= n ? 0u : (n - e >= 8 ? 0xFFu : ((1u << (uint32_t)(n - e)) - 1u)));
+        /* the IDX entries of the next peer are fetched one iteration ahead (scalar loads) */
+        const uint32_t* idx0 = reinterpret_cast<const uint32_t*>(a.comp + L.idx);
+        uint32_t nb = idx0[g], nn = g + 1 < ng ? idx0[g + 1] : 0u;
         for (uint32_t p = 0; p < a.n_peers; ++p) {
-            const uint64_t slot_off = (uint64_t)p * a.slot_cap;
-            const uint8_t* __restrict__ slot = a.comp + slot_off;
-            uint32_t e0, n_esc;
-            if (!check_header<DT>(slot, L, n, slot_off, a.comp_capacity, e0, n_esc)) { bad = true; continue; }
+            const uint8_t* __restrict__ slot = a.comp + (uint64_t)p * a.slot_cap;
+            const uint32_t e0 = s_e0[p], n_esc = s_nesc[p];
+            const uint32_t base = nb, next = g + 1 < ng ? nn : n_esc;
+            if (p + 1 < a.n_peers) {
+                const uint32_t* idxn = reinterpret_cast<const uint32_t*>(slot + a.slot_cap + L.idx);
+                nb = idxn[g];
+                if (g + 1 < ng) nn = idxn[g + 1];
+            }
+            if (e0 == 0u) continue;                      /* rejected slot: left out of the sum */
             DecIn in;
-            uint32_t next;
             u32x2 lv, lt;
-            decode_index(slot, L, n, n_esc, gstart, in, next);
+            in.base = base;
+            in.idx_ok = base <= next && next <= n_esc && next - base <= kGroup;
+            in.count = in.idx_ok ? next - base : 0u;
             decode_fetch_list(slot, L, in, next, lane, lv, lt);
             if (fast) decode_load<DT, true>(slot, L, n, gstart, lane, in);
             else decode_load<DT, false>(slot, L, n, gstart, lane, in);
