@@ -502,6 +502,18 @@ __device__ __forceinline__ uint32_t spread4(uint32_t x)
     return __umul24(x, 0x204081u) & 0x01010101u;
 }
 
+/* Decoder tables in LDS, built once per workgroup (one entry per thread). */
+struct DecTables {
+    uint2 spread[256];   /* plane byte -> its 8 bits in bit 0 of 8 bytes (.x = values 0..3, .y = values 4..7) */
+    uint2 expand[16];    /* 4-bit zero-point mask -> v_perm selector and byte mask, see expand_entry */
+};
+
+__device__ __forceinline__ void build_tables(DecTables& t)
+{
+    t.spread[threadIdx.x] = make_uint2(spread4(threadIdx.x & 15u), spread4(threadIdx.x >> 4));   /* kThreads == 256 */
+    if (threadIdx.x < 16) t.expand[threadIdx.x] = expand_entry(threadIdx.x);
+}
+
 /* Bytes of LDS per group for its zero-point exponents: 512 + up to 7 of misalignment, rounded up,
  * + 8 so that a lane's three aligned words never leave the region. */
 constexpr uint32_t kEscRegion = 544;
@@ -613,12 +625,14 @@ __device__ __forceinline__ DecEsc decode_locate(const DecIn& in, const uint8_t* 
 
 /* Rebuild the high 16-bit words of the lane's 8 values (section 4, third paragraph), packed in pairs. */
 __device__ __forceinline__ void decode_values(const DecIn& in, const DecEsc& es, uint32_t e0,
-                                              const uint2* __restrict__ lut, uint32_t hp[4])
+                                              const DecTables& tab, uint32_t hp[4])
 {
-    /* code bytes of values 0..3 and 4..7, then exponent = dec[1] - 1 + code */
+    /* code bytes of values 0..3 and 4..7 (plane bits spread by table), then exponent = dec[1] - 1 + code */
     const uint32_t k4 = (e0 - 1u) * 0x01010101u;
-    uint32_t eA = (spread4(in.b0 & 15u) | (spread4(in.b1 & 15u) << 1) | (spread4(in.b2 & 15u) << 2)) + k4;
-    uint32_t eB = (spread4(in.b0 >> 4) | (spread4(in.b1 >> 4) << 1) | (spread4(in.b2 >> 4) << 2)) + k4;
+    const uint2 t0 = tab.spread[in.b0], t1 = tab.spread[in.b1], t2 = tab.spread[in.b2];
+    uint32_t eA = (t0.x | (t1.x << 1) | (t2.x << 2)) + k4;
+    uint32_t eB = (t0.y | (t1.y << 1) | (t2.y << 2)) + k4;
+    const uint2* __restrict__ lut = tab.expand;
     if (es.any && !es.bad) {
         const uint32_t l8 = __builtin_amdgcn_alignbyte(es.d1, es.d0, es.sh);
         const uint32_t h8 = __builtin_amdgcn_alignbyte(es.d2, es.d1, es.sh);
@@ -641,12 +655,11 @@ __device__ __forceinline__ void decode_values(const DecIn& in, const DecEsc& es,
 /* Rebuild the 8 values and store them. */
 template <int DT, bool FAST>
 __device__ __forceinline__ void decode_store(uint8_t* __restrict__ cout, const DecIn& in, const DecEsc& es,
-                                             uint64_t gstart, uint32_t e0, uint32_t lane,
-                                             const uint2* __restrict__ lut)
+                                             uint64_t gstart, uint32_t e0, uint32_t lane, const DecTables& tab)
 {
     const uint64_t e = gstart + lane * kLaneElems;
     uint32_t hp[4];
-    decode_values(in, es, e0, lut, hp);
+    decode_values(in, es, e0, tab, hp);
     if (FAST) {
         if (DT == ZIPCCL_BF16) {
             st_stream<u32x4>((cout + gstart * 2) + lane * 16u, u32x4{hp[0], hp[1], hp[2], hp[3]});
@@ -704,9 +717,9 @@ template <int DT>
 __global__ __launch_bounds__(kThreads) void k_decompress(const DecompressArgs a)
 {
     constexpr uint32_t ES = DT == ZIPCCL_BF16 ? 2u : 4u;
-    __shared__ uint2 s_lut[16];
+    __shared__ DecTables s_tab;
     __shared__ __attribute__((aligned(16))) uint8_t s_esc[kWavesPerBlock][kGroupsPerWave][kEscRegion];
-    if (threadIdx.x < 16) s_lut[threadIdx.x] = expand_entry(threadIdx.x);
+    build_tables(s_tab);
 
     const uint32_t t = blockIdx.x;
     const uint32_t c = find_chunk(a.tab, t);
@@ -752,7 +765,7 @@ __global__ __launch_bounds__(kThreads) void k_decompress(const DecompressArgs a)
         for (uint32_t u = 0; u < kGroupsPerWave; ++u) es[u] = decode_locate(in[u], s_esc[wave][u]);
 #pragma unroll
         for (uint32_t u = 0; u < kGroupsPerWave; ++u) {
-            decode_store<DT, true>(cout, in[u], es[u], ts + (uint64_t)(u * kWavesPerBlock + wave) * kGroup, e0, lane, s_lut);
+            decode_store<DT, true>(cout, in[u], es[u], ts + (uint64_t)(u * kWavesPerBlock + wave) * kGroup, e0, lane, s_tab);
             bad |= es[u].bad;
         }
     } else {
@@ -770,7 +783,7 @@ __global__ __launch_bounds__(kThreads) void k_decompress(const DecompressArgs a)
                 __builtin_amdgcn_wave_barrier();
                 __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
                 const DecEsc es = decode_locate(in, s_esc[wave][u]);
-                decode_store<DT, false>(cout, in, es, gstart, e0, lane, s_lut);
+                decode_store<DT, false>(cout, in, es, gstart, e0, lane, s_tab);
                 bad |= es.bad;
             }
         }
@@ -796,11 +809,11 @@ template <int DT, int ODT>
 __global__ __launch_bounds__(kThreads) void k_decompress_reduce(const ReduceArgs a)
 {
     constexpr uint32_t OES = ODT == ZIPCCL_BF16 ? 2u : 4u;
-    __shared__ uint2 s_lut[16];
+    __shared__ DecTables s_tab;
     __shared__ __attribute__((aligned(16))) uint8_t s_esc[kWavesPerBlock][kEscRegion];
     __shared__ uint32_t s_e0[kMaxPeers];      /* dec[1] of peer p's slot, 0 = header rejected */
     __shared__ uint32_t s_nesc[kMaxPeers];    /* zero-points of peer p's slot */
-    if (threadIdx.x < 16) s_lut[threadIdx.x] = expand_entry(threadIdx.x);
+    build_tables(s_tab);
 
     const uint64_t n = a.n;
     const uint64_t ts = (uint64_t)blockIdx.x * kTile;
@@ -860,7 +873,7 @@ __global__ __launch_bounds__(kThreads) void k_decompress_reduce(const ReduceArgs
             __builtin_amdgcn_wave_barrier();
             bad |= es.bad;
             uint32_t hp[4];
-            decode_values(in, es, e0, s_lut, hp);
+            decode_values(in, es, e0, s_tab, hp);
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 uint32_t w0, w1;
