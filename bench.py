@@ -182,6 +182,7 @@ def main():
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (parity/debug only)")
     ap.add_argument("--all", action="store_true", help="also time the other >=256 MB workloads (extra object)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--chunks", type=int, default=0, help="override the workload's chunk count with an equal split")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build is a single-GPU codec path; run with --gpus 1 "
@@ -194,6 +195,8 @@ def main():
 
     log(f"generating workload {args.workload} (scale {args.scale})")
     w = workloads.make(args.workload, args.scale)
+    if args.chunks:
+        w.n_chunks, w.chunk_elems = args.chunks, None
     log(f"{w.name}: n={w.n_elems} ({w.nbytes / 2**20:.0f} MiB), {w.n_chunks} chunks, sigma={w.sigma}")
     r = run_gpu(w, args.steps, args.warmup)
     gb = w.nbytes / 1e9

@@ -457,27 +457,58 @@ __global__ __launch_bounds__(kThreads) void k_place(const CompressArgs a, uint32
     }
 }
 
-/* One workgroup per chunk: exclusive prefix of the chunk's per-tile zero-point counts. */
+/*
+ * Exclusive prefix of every chunk's per-tile zero-point counts.  Workgroup (x, y) owns segment x
+ * (kScanSeg tiles) of chunk y: it sums the chunk's counts before its segment itself (the count
+ * array is small and cache-resident, and this keeps workgroups independent of each other), then
+ * scans its segment.
+ */
+constexpr uint32_t kScanSeg = 4 * kThreads;
+
 __global__ __launch_bounds__(kThreads) void k_tile_scan(const CompressArgs a)
 {
-    __shared__ uint32_t s_part[kThreads];
-    const uint32_t c = blockIdx.x;
+    __shared__ uint32_t s_wave[kWavesPerBlock];
+    const uint32_t c = blockIdx.y;
     const uint32_t first = a.tab.tile_start[c], end = a.tab.tile_start[c + 1];
-    const uint32_t nt = end - first;
-    const uint32_t per = (nt + kThreads - 1) / kThreads;
-    const uint32_t b = first + threadIdx.x * per;
-    uint32_t sum = 0;
-    for (uint32_t i = 0; i < per; ++i)
-        if (b + i < end) sum += a.tile_total[b + i];
-    s_part[threadIdx.x] = sum;
+    const uint32_t seg0 = first + blockIdx.x * kScanSeg;
+    if (seg0 >= end) return;
+    const uint32_t lane = lane_id(), wave = threadIdx.x >> 6;
+
+    /* counts of the chunk before this segment */
+    uint32_t part[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    uint32_t i = first + threadIdx.x;
+    for (; i + 7u * kThreads < seg0; i += 8u * kThreads) {     /* eight independent loads in flight per thread */
+#pragma unroll
+        for (uint32_t k = 0; k < 8; ++k) part[k] += a.tile_total[i + k * kThreads];
+    }
+    for (; i < seg0; i += kThreads) part[0] += a.tile_total[i];
+    uint32_t before = ((part[0] + part[1]) + (part[2] + part[3])) + ((part[4] + part[5]) + (part[6] + part[7]));
+    before = wave_incl_scan(before);
+    if (lane == 63) s_wave[wave] = before;
     __syncthreads();
-    uint32_t run = 0;
-    for (uint32_t i = 0; i < threadIdx.x; ++i) run += s_part[i];
-    for (uint32_t i = 0; i < per; ++i)
-        if (b + i < end) {
-            a.tile_prefix[b + i] = run;
-            run += a.tile_total[b + i];
-        }
+    uint32_t base = 0;
+#pragma unroll
+    for (uint32_t w = 0; w < kWavesPerBlock; ++w) base += s_wave[w];
+    __syncthreads();
+
+    /* scan of the segment: four consecutive tiles per thread */
+    const uint32_t i0 = seg0 + 4u * threadIdx.x;
+    uint32_t v[4], mine = 0;
+#pragma unroll
+    for (uint32_t k = 0; k < 4; ++k) {
+        v[k] = i0 + k < end ? a.tile_total[i0 + k] : 0u;
+        mine += v[k];
+    }
+    const uint32_t inc = wave_incl_scan(mine);
+    if (lane == 63) s_wave[wave] = inc;
+    __syncthreads();
+    uint32_t run = base + inc - mine;
+    for (uint32_t w = 0; w < wave; ++w) run += s_wave[w];
+#pragma unroll
+    for (uint32_t k = 0; k < 4; ++k) {
+        if (i0 + k < end) a.tile_prefix[i0 + k] = run;
+        run += v[k];
+    }
 }
 
 /*
@@ -966,7 +997,13 @@ int launch_compress(int dt, int mode, const CompressArgs& a, uint32_t n_tiles, v
 
 int launch_tile_scan(const CompressArgs& a, void* stream)
 {
-    hipLaunchKernelGGL(k_tile_scan, dim3(a.tab.n_chunks), dim3(kThreads), 0, (hipStream_t)stream, a);
+    uint32_t max_tiles = 1;
+    for (uint32_t c = 0; c < a.tab.n_chunks; ++c) {
+        const uint32_t nt = a.tab.tile_start[c + 1] - a.tab.tile_start[c];
+        max_tiles = nt > max_tiles ? nt : max_tiles;
+    }
+    const dim3 grid((max_tiles + kScanSeg - 1) / kScanSeg, a.tab.n_chunks);
+    hipLaunchKernelGGL(k_tile_scan, grid, dim3(kThreads), 0, (hipStream_t)stream, a);
     return (int)hipGetLastError();
 }
 

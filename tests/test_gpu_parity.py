@@ -236,3 +236,14 @@ def test_random_splits_and_contents_fuzz(compress_path):
             data[pos] = spec.astype(data.dtype) if dtype == z.BF16 else (spec << 16 | 0x1234).astype(np.uint32)
         _say(f"[fuzz {case}] dtype={dtype} chunks={list(ce)} sigma={sigma:.3g} path={compress_path}")
         check_parity(data, dtype, sigma, k, ce, label=f"fuzz{case}")
+
+
+def test_one_chunk_spanning_several_scan_segments(compress_path):
+    # 2500 tiles in a single chunk: the per-chunk prefix of tile counts crosses scan segments,
+    # plus a second, shorter chunk so that segment grids of unequal chunks are covered
+    ce = np.array([2500 * 8192 + 123, 1030 * 8192], dtype=np.uint64)
+    rng = np.random.default_rng(77)
+    data = W.f32_to_bf16_words(rng.standard_normal(int(ce.sum()), dtype=np.float32) * np.float32(0.5))
+    data[5_000_000:5_020_000] = 0x7F80                      # a dense stretch of zero-points
+    _say(f"[segments] n={data.size} path={compress_path}")
+    check_parity(data, z.BF16, 0.5, 2, ce, label="scan segments")
