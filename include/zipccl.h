@@ -156,6 +156,24 @@ zipccl_status_t zipccl_decompress_reduce(const void* d_comp, size_t comp_capacit
                                          zipccl_dtype_t dt, uint32_t n_peers, zipccl_dtype_t out_dt,
                                          uint32_t* d_status, void* stream);
 
+/*
+ * Adaptive switcher for Reduce-Scatter (section 5.2).  Host only, pure.  Linear cost models
+ *   T_RS(d)  = alpha_rs  + beta_rs  * d                  (Eq.6, native Reduce-Scatter)
+ *   T_A2A(d) = alpha_a2a + beta_a2a * e * s * d          (Eq.7, zipped All-to-All + local reduce)
+ * with d the data size in bytes, alpha in seconds, beta in seconds per byte, e the compression
+ * factor of the zipped All-to-All (compressed / original bytes: 1 / compression ratio) and s the
+ * precision scale factor (0.5 when the native collective moves a format twice as wide).
+ * zipccl_switch_prefers_zipped returns 1 when T_A2A(d) < T_RS(d), 0 otherwise, -1 on bad
+ * arguments (null model, negative or non-finite inputs); t_rs / t_a2a (nullable) receive the times.
+ * zipccl_fit_link_model is the profiling step: ordinary least squares of t = alpha + beta d over
+ * k >= 2 measured (d, t) pairs with at least two distinct sizes.
+ */
+typedef struct { double alpha_rs, beta_rs, alpha_a2a, beta_a2a; } zipccl_link_model_t;
+int zipccl_switch_prefers_zipped(const zipccl_link_model_t* m, double d_bytes, double e, double s,
+                                 double* t_rs, double* t_a2a);
+zipccl_status_t zipccl_fit_link_model(const double* d_bytes, const double* t_seconds, size_t k,
+                                      double* alpha, double* beta);
+
 const char* zipccl_status_string(zipccl_status_t s);
 
 /*

@@ -26,6 +26,11 @@ class zipccl_table_t(ctypes.Structure):
     _fields_ = [("dec", ctypes.c_uint8 * 8)]
 
 
+class zipccl_link_model_t(ctypes.Structure):
+    _fields_ = [("alpha_rs", ctypes.c_double), ("beta_rs", ctypes.c_double),
+                ("alpha_a2a", ctypes.c_double), ("beta_a2a", ctypes.c_double)]
+
+
 def lib_path():
     return build_lib.LIB
 
@@ -60,6 +65,12 @@ def _load():
     lib.zipccl_debug_compress_path.argtypes = [i32]
     lib.zipccl_decompress_reduce.restype = i32
     lib.zipccl_decompress_reduce.argtypes = [vp, sz, vp, sz, i32, u32, i32, vp, vp]
+    dp = ctypes.POINTER(ctypes.c_double)
+    lib.zipccl_switch_prefers_zipped.restype = i32
+    lib.zipccl_switch_prefers_zipped.argtypes = [ctypes.POINTER(zipccl_link_model_t), ctypes.c_double,
+                                                 ctypes.c_double, ctypes.c_double, dp, dp]
+    lib.zipccl_fit_link_model.restype = i32
+    lib.zipccl_fit_link_model.argtypes = [dp, dp, sz, dp, dp]
     lib.zipccl_status_string.restype = ctypes.c_char_p
     lib.zipccl_status_string.argtypes = [i32]
     return lib
@@ -68,6 +79,7 @@ def _load():
 _lib = _load()
 EXPORTS = ("zipccl_build_table", "zipccl_max_compressed_size", "zipccl_chunk_slot_offsets",
            "zipccl_compress_workspace_size", "zipccl_compress_min_workspace_size", "zipccl_compress", "zipccl_decompress", "zipccl_decompress_reduce", "zipccl_status_string",
+           "zipccl_switch_prefers_zipped", "zipccl_fit_link_model",
            "zipccl_debug_compress_path", "zipccl_debug_copy")
 
 
@@ -169,3 +181,21 @@ def zipccl_decompress_reduce(d_comp, d_out, n_elems, dt, n_peers, out_dt=FP32, d
                                        _dptr(d_status), _stream(stream))
     if rc:
         raise ZipcclError(rc, "zipccl_decompress_reduce")
+
+
+def zipccl_switch_prefers_zipped(alpha_rs, beta_rs, alpha_a2a, beta_a2a, d_bytes, e, s):
+    """Returns (decision, t_rs, t_a2a); decision is 1, 0 or -1 (bad arguments)."""
+    m = zipccl_link_model_t(alpha_rs, beta_rs, alpha_a2a, beta_a2a)
+    t_rs, t_a2a = ctypes.c_double(), ctypes.c_double()
+    r = _lib.zipccl_switch_prefers_zipped(ctypes.byref(m), d_bytes, e, s, ctypes.byref(t_rs), ctypes.byref(t_a2a))
+    return int(r), t_rs.value, t_a2a.value
+
+
+def zipccl_fit_link_model(d_bytes, t_seconds):
+    d = (ctypes.c_double * len(d_bytes))(*d_bytes)
+    t = (ctypes.c_double * len(t_seconds))(*t_seconds)
+    a, b = ctypes.c_double(), ctypes.c_double()
+    rc = _lib.zipccl_fit_link_model(d, t, len(d_bytes), ctypes.byref(a), ctypes.byref(b))
+    if rc:
+        raise ZipcclError(rc, "zipccl_fit_link_model")
+    return a.value, b.value

@@ -311,6 +311,43 @@ zipccl_status_t zipccl_debug_copy(void* d_dst, const void* d_src, size_t bytes, 
     return launch_copy(d_dst, d_src, bytes, stream) == 0 ? ZIPCCL_OK : ZIPCCL_ERR_DEVICE;
 }
 
+int zipccl_switch_prefers_zipped(const zipccl_link_model_t* m, double d_bytes, double e, double s,
+                                 double* t_rs, double* t_a2a)
+{
+    auto ok = [](double v) { return std::isfinite(v) && v >= 0.0; };
+    if (!m || !ok(m->alpha_rs) || !ok(m->beta_rs) || !ok(m->alpha_a2a) || !ok(m->beta_a2a) || !ok(d_bytes) ||
+        !ok(e) || !ok(s))
+        return -1;
+    const double rs = m->alpha_rs + m->beta_rs * d_bytes;                  /* Eq.6 */
+    const double a2a = m->alpha_a2a + m->beta_a2a * e * s * d_bytes;       /* Eq.7 */
+    if (t_rs) *t_rs = rs;
+    if (t_a2a) *t_a2a = a2a;
+    return a2a < rs ? 1 : 0;
+}
+
+zipccl_status_t zipccl_fit_link_model(const double* d_bytes, const double* t_seconds, size_t k,
+                                      double* alpha, double* beta)
+{
+    if (!d_bytes || !t_seconds || !alpha || !beta || k < 2) return ZIPCCL_ERR_INVALID_ARG;
+    double md = 0.0, mt = 0.0;
+    for (size_t i = 0; i < k; ++i) {
+        if (!std::isfinite(d_bytes[i]) || !std::isfinite(t_seconds[i])) return ZIPCCL_ERR_INVALID_ARG;
+        md += d_bytes[i];
+        mt += t_seconds[i];
+    }
+    md /= (double)k;
+    mt /= (double)k;
+    double sxx = 0.0, sxy = 0.0;
+    for (size_t i = 0; i < k; ++i) {
+        sxx += (d_bytes[i] - md) * (d_bytes[i] - md);
+        sxy += (d_bytes[i] - md) * (t_seconds[i] - mt);
+    }
+    if (!(sxx > 0.0)) return ZIPCCL_ERR_INVALID_ARG;
+    *beta = sxy / sxx;
+    *alpha = mt - *beta * md;
+    return ZIPCCL_OK;
+}
+
 int zipccl_debug_compress_path(int path)
 {
     const int prev = compress_path().load();
