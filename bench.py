@@ -135,6 +135,30 @@ def run_reduce(w, peers, steps):
             "checked": "bit-equal to the peer-ordered FP32 sum of the inputs"}
 
 
+def run_estimate(w, steps):
+    """sigma / table from the data on the device (zipccl_estimate_table): one read of the tensor."""
+    import torch
+    import paper_2604_27844_amd.binding as z
+    dev = torch.device("cuda:0")
+    d_in = torch.from_numpy(w.data.view(np.int16 if w.dtype == z.BF16 else np.int32)).to(dev)
+    d_tab = torch.zeros(8, dtype=torch.uint8, device=dev)
+    d_sig = torch.zeros(1, dtype=torch.float64, device=dev)
+    d_ws = torch.empty(z.zipccl_estimate_workspace_size(), dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream()
+    z.zipccl_estimate_table(d_in, w.n_elems, w.dtype, d_tab, d_sig, d_ws, stream=stream)
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(steps)]
+    for k in range(steps):
+        evs[k][0].record(stream)
+        z.zipccl_estimate_table(d_in, w.n_elems, w.dtype, d_tab, d_sig, d_ws, stream=stream)
+        evs[k][1].record(stream)
+    torch.cuda.synchronize()
+    ms = float(np.mean([e[0].elapsed_time(e[1]) for e in evs]))
+    return {"ms": round(ms, 4), "sigma": float(d_sig.item()), "dec1": int(d_tab[1].item()),
+            "hbm_GBps": round(w.nbytes / (ms * 1e-3) / 1e9, 1),
+            "hbm_frac": round(w.nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
+
+
 def run_oracle(w, gpu_out=None, gpu_cb=None):
     """The oracle as it stands: single thread over the whole workload, then one chunk per host thread."""
     import oracle
@@ -251,6 +275,7 @@ def main():
     red = run_reduce(w, 8, max(3, args.steps // 2))
     if red:
         out["decompress_reduce"] = red
+    out["estimate_table"] = run_estimate(w, max(3, args.steps // 2))
 
     if args.all:
         extra = {}

@@ -121,6 +121,30 @@ zipccl_status_t zipccl_compress(const void* d_in, size_t n_elems, zipccl_dtype_t
                                 void* d_workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Table from the data (section 4.1, last sentence: sigma of the tensor by torch.std, i.e. the
+ * unbiased sample standard deviation), computed and kept on the device so that no host
+ * round trip sits between estimate and compress.  One pass over the tensor in FP64, then the
+ * window by Eq.5 / Eq.2 exactly as zipccl_build_table does.  A sigma that is not a positive
+ * finite number (constant tensor, NaN/Inf in the data, fewer than two values) selects the
+ * lowest window (dec[1] = 1).
+ *   d_in         device, n_elems values of dt, aligned to the element size
+ *   d_table      device, 8-byte aligned: receives the table
+ *   d_sigma      device double, 8-byte aligned, may be NULL: receives sigma (NaN if undefined)
+ *   d_workspace  device, 8-byte aligned, >= zipccl_estimate_workspace_size() bytes
+ * zipccl_compress_device_table is zipccl_compress with the table read from device memory
+ * (as written by zipccl_estimate_table earlier on the same stream).
+ */
+size_t zipccl_estimate_workspace_size(void);
+zipccl_status_t zipccl_estimate_table(const void* d_in, size_t n_elems, zipccl_dtype_t dt,
+                                      zipccl_table_t* d_table, double* d_sigma,
+                                      void* d_workspace, size_t workspace_bytes, void* stream);
+zipccl_status_t zipccl_compress_device_table(const void* d_in, size_t n_elems, zipccl_dtype_t dt,
+                                             uint32_t n_chunks, const uint64_t* chunk_elems,
+                                             const zipccl_table_t* d_table,
+                                             void* d_out, size_t out_capacity, uint64_t* d_chunk_bytes,
+                                             void* d_workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Decompress (section 4, third paragraph): code != 0 -> exponent from the table in the chunk
  * header, code == 0 -> next exponent of the zero-point list, found through IDX; recombined
  * with the stored sign and mantissa bits.

@@ -57,6 +57,12 @@ def _load():
     lib.zipccl_compress_min_workspace_size.argtypes = [sz, i32, u32, vp]
     lib.zipccl_compress.restype = i32
     lib.zipccl_compress.argtypes = [vp, sz, i32, u32, vp, tp, vp, sz, vp, vp, sz, vp]
+    lib.zipccl_compress_device_table.restype = i32
+    lib.zipccl_compress_device_table.argtypes = [vp, sz, i32, u32, vp, vp, vp, sz, vp, vp, sz, vp]
+    lib.zipccl_estimate_workspace_size.restype = sz
+    lib.zipccl_estimate_workspace_size.argtypes = []
+    lib.zipccl_estimate_table.restype = i32
+    lib.zipccl_estimate_table.argtypes = [vp, sz, i32, vp, vp, vp, sz, vp]
     lib.zipccl_decompress.restype = i32
     lib.zipccl_decompress.argtypes = [vp, sz, vp, sz, i32, u32, vp, vp, vp]
     lib.zipccl_debug_copy.restype = i32
@@ -80,6 +86,7 @@ _lib = _load()
 EXPORTS = ("zipccl_build_table", "zipccl_max_compressed_size", "zipccl_chunk_slot_offsets",
            "zipccl_compress_workspace_size", "zipccl_compress_min_workspace_size", "zipccl_compress", "zipccl_decompress", "zipccl_decompress_reduce", "zipccl_status_string",
            "zipccl_switch_prefers_zipped", "zipccl_fit_link_model",
+           "zipccl_estimate_workspace_size", "zipccl_estimate_table", "zipccl_compress_device_table",
            "zipccl_debug_compress_path", "zipccl_debug_copy")
 
 
@@ -199,3 +206,28 @@ def zipccl_fit_link_model(d_bytes, t_seconds):
     if rc:
         raise ZipcclError(rc, "zipccl_fit_link_model")
     return a.value, b.value
+
+
+def zipccl_estimate_workspace_size():
+    return int(_lib.zipccl_estimate_workspace_size())
+
+
+def zipccl_estimate_table(d_in, n_elems, dt, d_table, d_sigma, d_workspace, stream=None):
+    """d_table: 8-byte GPU tensor; d_sigma: float64 GPU tensor of one element or None."""
+    wsb = d_workspace.numel() * d_workspace.element_size()
+    rc = _lib.zipccl_estimate_table(_dptr(d_in), int(n_elems), dt, _dptr(d_table), _dptr(d_sigma),
+                                    _dptr(d_workspace), wsb, _stream(stream))
+    if rc:
+        raise ZipcclError(rc, "zipccl_estimate_table")
+
+
+def zipccl_compress_device_table(d_in, n_elems, dt, n_chunks, chunk_elems, d_table, d_out, d_chunk_bytes,
+                                 d_workspace, stream=None):
+    _keep, p = _host_u64(chunk_elems)
+    cap = d_out.numel() * d_out.element_size()
+    wsb = d_workspace.numel() * d_workspace.element_size()
+    rc = _lib.zipccl_compress_device_table(_dptr(d_in), int(n_elems), dt, int(n_chunks), p, _dptr(d_table),
+                                           _dptr(d_out), cap, _dptr(d_chunk_bytes), _dptr(d_workspace), wsb,
+                                           _stream(stream))
+    if rc:
+        raise ZipcclError(rc, "zipccl_compress_device_table")

@@ -178,16 +178,22 @@ size_t zipccl_compress_min_workspace_size(size_t n_elems, zipccl_dtype_t dt, uin
     return (size_t)plan_workspace(ce, n_elems).min_bytes;
 }
 
-zipccl_status_t zipccl_compress(const void* d_in, size_t n_elems, zipccl_dtype_t dt,
-                                uint32_t n_chunks, const uint64_t* chunk_elems,
-                                const zipccl_table_t* table,
-                                void* d_out, size_t out_capacity, uint64_t* d_chunk_bytes,
-                                void* d_workspace, size_t workspace_bytes, void* stream)
+} // extern "C"
+
+namespace {
+
+/* compress with the table either on the host (checked here) or in device memory (d_table) */
+zipccl_status_t compress_impl(const void* d_in, size_t n_elems, zipccl_dtype_t dt,
+                              uint32_t n_chunks, const uint64_t* chunk_elems,
+                              const zipccl_table_t* table, const zipccl_table_t* d_table,
+                              void* d_out, size_t out_capacity, uint64_t* d_chunk_bytes,
+                              void* d_workspace, size_t workspace_bytes, void* stream)
 {
     if (!dtype_ok(dt)) return ZIPCCL_ERR_UNSUPPORTED_DTYPE;
     std::vector<uint64_t> ce;
     if (!resolve_split(n_elems, n_chunks, chunk_elems, ce)) return ZIPCCL_ERR_INVALID_ARG;
-    if (!table_ok(table) || !d_out || !d_workspace || (!d_in && n_elems)) return ZIPCCL_ERR_INVALID_ARG;
+    if (d_table ? (reinterpret_cast<uintptr_t>(d_table) % 8) != 0 : !table_ok(table)) return ZIPCCL_ERR_INVALID_ARG;
+    if (!d_out || !d_workspace || (!d_in && n_elems)) return ZIPCCL_ERR_INVALID_ARG;
     const uint32_t es = elem_size(dt);
     if ((reinterpret_cast<uintptr_t>(d_in) % es) || (reinterpret_cast<uintptr_t>(d_out) % ZIPCCL_ALIGN) ||
         (reinterpret_cast<uintptr_t>(d_workspace) % 16) || (reinterpret_cast<uintptr_t>(d_chunk_bytes) % 8))
@@ -209,9 +215,13 @@ zipccl_status_t zipccl_compress(const void* d_in, size_t n_elems, zipccl_dtype_t
 
     CompressArgs a;
     std::memset(&a, 0, sizeof a);
-    a.e0 = table->dec[1];
-    std::memcpy(&a.dec_lo, table->dec, 4);
-    std::memcpy(&a.dec_hi, table->dec + 4, 4);
+    if (d_table) {
+        a.d_table = reinterpret_cast<const uint32_t*>(d_table);
+    } else {
+        a.e0 = table->dec[1];
+        std::memcpy(&a.dec_lo, table->dec, 4);
+        std::memcpy(&a.dec_hi, table->dec + 4, 4);
+    }
     uint64_t elem_base = 0, tile_base = 0;
     uint8_t* const ws = static_cast<uint8_t*>(d_workspace);
     for (uint32_t c0 = 0; c0 < n_chunks; c0 += kMaxBatch) {
@@ -237,6 +247,54 @@ zipccl_status_t zipccl_compress(const void* d_in, size_t n_elems, zipccl_dtype_t
         tile_base += nt;
     }
     return ZIPCCL_OK;
+}
+
+} // namespace
+
+extern "C" {
+
+zipccl_status_t zipccl_compress(const void* d_in, size_t n_elems, zipccl_dtype_t dt,
+                                uint32_t n_chunks, const uint64_t* chunk_elems,
+                                const zipccl_table_t* table,
+                                void* d_out, size_t out_capacity, uint64_t* d_chunk_bytes,
+                                void* d_workspace, size_t workspace_bytes, void* stream)
+{
+    return compress_impl(d_in, n_elems, dt, n_chunks, chunk_elems, table, nullptr, d_out, out_capacity,
+                         d_chunk_bytes, d_workspace, workspace_bytes, stream);
+}
+
+zipccl_status_t zipccl_compress_device_table(const void* d_in, size_t n_elems, zipccl_dtype_t dt,
+                                             uint32_t n_chunks, const uint64_t* chunk_elems,
+                                             const zipccl_table_t* d_table,
+                                             void* d_out, size_t out_capacity, uint64_t* d_chunk_bytes,
+                                             void* d_workspace, size_t workspace_bytes, void* stream)
+{
+    if (!d_table) return ZIPCCL_ERR_INVALID_ARG;
+    return compress_impl(d_in, n_elems, dt, n_chunks, chunk_elems, nullptr, d_table, d_out, out_capacity,
+                         d_chunk_bytes, d_workspace, workspace_bytes, stream);
+}
+
+size_t zipccl_estimate_workspace_size(void) { return 16 * (size_t)kMomentBlocks; }
+
+zipccl_status_t zipccl_estimate_table(const void* d_in, size_t n_elems, zipccl_dtype_t dt,
+                                      zipccl_table_t* d_table, double* d_sigma,
+                                      void* d_workspace, size_t workspace_bytes, void* stream)
+{
+    if (!dtype_ok(dt)) return ZIPCCL_ERR_UNSUPPORTED_DTYPE;
+    if (!d_table || !d_workspace || (!d_in && n_elems)) return ZIPCCL_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(d_in) % elem_size(dt)) || (reinterpret_cast<uintptr_t>(d_table) % 8) ||
+        (reinterpret_cast<uintptr_t>(d_sigma) % 8) || (reinterpret_cast<uintptr_t>(d_workspace) % 8))
+        return ZIPCCL_ERR_INVALID_ARG;
+    if (workspace_bytes < zipccl_estimate_workspace_size()) return ZIPCCL_ERR_BUFFER_TOO_SMALL;
+    MomentArgs a;
+    a.in = static_cast<const uint8_t*>(d_in);
+    a.n = n_elems;
+    a.partial = static_cast<double*>(d_workspace);
+    const uint64_t want = (n_elems + 16383) / 16384;             /* about 64 values per thread at least */
+    a.n_blocks = (uint32_t)(want < 1 ? 1 : (want > kMomentBlocks ? kMomentBlocks : want));
+    a.table = reinterpret_cast<uint8_t*>(d_table);
+    a.sigma = d_sigma;
+    return launch_estimate(dt, a, stream) == 0 ? ZIPCCL_OK : ZIPCCL_ERR_DEVICE;
 }
 
 zipccl_status_t zipccl_decompress(const void* d_comp, size_t comp_capacity,

@@ -84,7 +84,19 @@ struct CompressArgs {
     uint32_t* err;           /* workspace status word */
     uint32_t e0;             /* dec[1] */
     uint32_t dec_lo, dec_hi; /* dec[0..3], dec[4..7] packed little-endian */
+    const uint32_t* d_table; /* when not null: the table lives in device memory (two words), e0/dec_* unused */
     ChunkTab tab;
+};
+
+constexpr uint32_t kMomentBlocks = 2048;             /* workgroups (and partial sums) of the sigma estimate */
+
+struct MomentArgs {
+    const uint8_t* in;
+    uint64_t n;
+    double* partial;         /* 2 doubles per workgroup: sum x, sum x^2 */
+    uint32_t n_blocks;
+    uint8_t* table;          /* device zipccl_table_t (8 bytes) */
+    double* sigma;           /* may be null */
 };
 
 struct DecompressArgs {
@@ -112,6 +124,7 @@ enum CompressMode { kModeCount = 0, kModeEmit = 1, kModeStash = 2 };
 
 /* launchers implemented in zipccl_kernels.hip; return a hipError_t as int */
 int launch_copy(void* d_dst, const void* d_src, uint64_t bytes, void* stream);
+int launch_estimate(int dt, const MomentArgs& a, void* stream);
 int launch_compress(int dt, int mode, const CompressArgs& a, uint32_t n_tiles, void* stream);
 int launch_tile_scan(const CompressArgs& a, void* stream);
 int launch_place(int dt, const CompressArgs& a, uint32_t n_tiles, void* stream);

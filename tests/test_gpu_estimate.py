@@ -1,0 +1,89 @@
+"""GPU parity of the device-side sigma estimate and table choice against the oracle.
+
+sigma is floating point (FP64 sums in a different order): tolerance 1e-10 relative, derived from
+N * 2^-53 growth of a recursive FP64 sum over <= 2^27 values with |mean| <= sigma.  The table is
+an integer decision taken from sigma in FP64 on both sides; inputs are chosen away from the
+decision boundaries (sigma = 0.82335 * 2^k) so the tolerance cannot flip it.  Compressing with
+the device table must give exactly the bytes of compressing with the oracle's table.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle import sigma as osg
+import paper_2604_27844_amd.binding as z
+from paper_2604_27844_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    from gpu_util import DEV, to_device_words
+
+
+def _estimate(d_in, n, dtype):
+    d_tab = torch.full((8,), 0xEE, dtype=torch.uint8, device=DEV)
+    d_sig = torch.zeros(1, dtype=torch.float64, device=DEV)
+    d_ws = torch.empty(z.zipccl_estimate_workspace_size(), dtype=torch.uint8, device=DEV)
+    z.zipccl_estimate_table(d_in, n, dtype, d_tab, d_sig, d_ws)
+    torch.cuda.synchronize()
+    return d_tab, list(d_tab.cpu().numpy()), float(d_sig.item())
+
+
+def _away_from_boundary(s):
+    frac = (math.log2(s / 0.82335)) % 1.0
+    return min(frac, 1 - frac) > 1e-6
+
+
+@pytest.mark.parametrize("name,scale", [("c1", 1.0), ("c2", 1 / 8), ("c3", 1 / 32), ("c4", 1 / 64), ("c5", 1 / 64),
+                                        ("c5_fp32", 1 / 32)])
+def test_estimate_matches_oracle_on_workloads(name, scale):
+    w = W.make(name, scale)
+    dec, s = osg.estimate_table(w.data, w.dtype)
+    assert _away_from_boundary(s)
+    d_in = to_device_words(w.data)
+    d_tab, got_dec, got_s = _estimate(d_in, w.n_elems, w.dtype)
+    assert got_s == pytest.approx(s, rel=1e-10)
+    assert got_dec == list(dec)
+    # compress with the device table == oracle compress with the oracle's estimated table
+    cap = z.zipccl_max_compressed_size(w.n_elems, w.dtype, w.n_chunks, w.chunk_elems)
+    d_out = torch.full((cap,), 0xA5, dtype=torch.uint8, device=DEV)
+    d_cb = torch.zeros(w.n_chunks, dtype=torch.int64, device=DEV)
+    d_ws = torch.empty(z.zipccl_compress_workspace_size(w.n_elems, w.dtype, w.n_chunks, w.chunk_elems),
+                       dtype=torch.uint8, device=DEV)
+    z.zipccl_compress_device_table(d_in, w.n_elems, w.dtype, w.n_chunks, w.chunk_elems, d_tab, d_out, d_cb, d_ws)
+    torch.cuda.synchronize()
+    ref, ref_cb, off = oracle.compress(w.data, w.dtype, dec, w.n_chunks, w.chunk_elems)
+    got = d_out.cpu().numpy()
+    assert np.array_equal(d_cb.cpu().numpy().astype(np.uint64), ref_cb)
+    for c in range(w.n_chunks):
+        a, b = int(off[c]), int(off[c]) + int(ref_cb[c])
+        assert np.array_equal(got[a:b], ref[a:b]), c
+
+
+def test_estimate_edge_cases():
+    rng = np.random.default_rng(3)
+    cases = {
+        "two values": np.array([0x3F80, 0x4040], dtype=np.uint16),
+        "odd start / tail": W.f32_to_bf16_words(rng.standard_normal(12345, dtype=np.float32) * np.float32(3.0)),
+        "nonzero mean": W.f32_to_bf16_words(rng.standard_normal(50000, dtype=np.float32) * np.float32(0.05) + np.float32(1.0)),
+        "constant": np.full(1000, 0x3F80, dtype=np.uint16),
+        "one value": np.array([0x3F80], dtype=np.uint16),
+        "with inf": np.array([0x3F80, 0x7F80, 0x3F80, 0x0000], dtype=np.uint16),
+        "empty": np.zeros(0, dtype=np.uint16),
+    }
+    for label, x in cases.items():
+        dec, s = osg.estimate_table(x, z.BF16)
+        d_in = to_device_words(x)
+        # a view that starts 2 bytes into an allocation: the element-wise path
+        d_off = torch.zeros(x.size + 1, dtype=torch.int16, device=DEV)
+        d_off[1:] = d_in
+        for d in (d_in, d_off[1:]):
+            _, got_dec, got_s = _estimate(d, x.size, z.BF16)
+            assert got_dec == list(dec), label
+            if math.isnan(s):
+                assert math.isnan(got_s), label
+            else:
+                assert got_s == pytest.approx(s, rel=1e-10, abs=1e-300), label
