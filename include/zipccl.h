@@ -91,6 +91,18 @@ size_t zipccl_max_compressed_size(size_t n_elems, zipccl_dtype_t dt, uint32_t n_
 zipccl_status_t zipccl_chunk_slot_offsets(size_t n_elems, zipccl_dtype_t dt, uint32_t n_chunks,
                                           const uint64_t* chunk_elems, uint64_t* slot_off);
 
+/*
+ * Static / dynamic split of every slot (section 3.2, second All-to-All design; section 4: only the
+ * zero-point list has a data-dependent size).  static_bytes (host, n_chunks entries) receives the
+ * size of HDR..IDX of each chunk, known before compression.  A collective sends
+ * [slot_off[c], slot_off[c] + static_bytes[c]) first, then exchanges chunk_bytes (one u64 per
+ * peer, written by zipccl_compress), then sends the dynamic part
+ * [slot_off[c] + static_bytes[c], slot_off[c] + chunk_bytes[c]); the receiver places both at
+ * the same offsets of its own slot and decodes.
+ */
+zipccl_status_t zipccl_chunk_static_bytes(size_t n_elems, zipccl_dtype_t dt, uint32_t n_chunks,
+                                          const uint64_t* chunk_elems, uint64_t* static_bytes);
+
 /* Bytes of device scratch for zipccl_compress.  With zipccl_compress_workspace_size bytes
  * (about one byte per element) compress reads the input once: zero-point exponents are parked
  * in the scratch until the per-chunk prefix of section 4.2.3 is known.  With less, but at least

@@ -51,6 +51,8 @@ def _load():
     lib.zipccl_max_compressed_size.argtypes = [sz, i32, u32, vp]
     lib.zipccl_chunk_slot_offsets.restype = i32
     lib.zipccl_chunk_slot_offsets.argtypes = [sz, i32, u32, vp, vp]
+    lib.zipccl_chunk_static_bytes.restype = i32
+    lib.zipccl_chunk_static_bytes.argtypes = [sz, i32, u32, vp, vp]
     lib.zipccl_compress_workspace_size.restype = sz
     lib.zipccl_compress_workspace_size.argtypes = [sz, i32, u32, vp]
     lib.zipccl_compress_min_workspace_size.restype = sz
@@ -83,7 +85,7 @@ def _load():
 
 
 _lib = _load()
-EXPORTS = ("zipccl_build_table", "zipccl_max_compressed_size", "zipccl_chunk_slot_offsets",
+EXPORTS = ("zipccl_build_table", "zipccl_max_compressed_size", "zipccl_chunk_slot_offsets", "zipccl_chunk_static_bytes",
            "zipccl_compress_workspace_size", "zipccl_compress_min_workspace_size", "zipccl_compress", "zipccl_decompress", "zipccl_decompress_reduce", "zipccl_status_string",
            "zipccl_switch_prefers_zipped", "zipccl_fit_link_model",
            "zipccl_estimate_workspace_size", "zipccl_estimate_table", "zipccl_compress_device_table",
@@ -231,3 +233,12 @@ def zipccl_compress_device_table(d_in, n_elems, dt, n_chunks, chunk_elems, d_tab
                                            _stream(stream))
     if rc:
         raise ZipcclError(rc, "zipccl_compress_device_table")
+
+
+def zipccl_chunk_static_bytes(n_elems, dt, n_chunks=1, chunk_elems=None):
+    _keep, p = _host_u64(chunk_elems)
+    out = np.zeros(int(n_chunks), dtype=np.uint64)
+    rc = _lib.zipccl_chunk_static_bytes(int(n_elems), dt, int(n_chunks), p, out.ctypes.data_as(ctypes.c_void_p))
+    if rc:
+        raise ZipcclError(rc, "zipccl_chunk_static_bytes")
+    return out

@@ -149,6 +149,16 @@ zipccl_status_t zipccl_chunk_slot_offsets(size_t n_elems, zipccl_dtype_t dt, uin
     return ZIPCCL_OK;
 }
 
+zipccl_status_t zipccl_chunk_static_bytes(size_t n_elems, zipccl_dtype_t dt, uint32_t n_chunks,
+                                          const uint64_t* chunk_elems, uint64_t* static_bytes)
+{
+    if (!dtype_ok(dt)) return ZIPCCL_ERR_UNSUPPORTED_DTYPE;
+    std::vector<uint64_t> ce;
+    if (!static_bytes || !resolve_split(n_elems, n_chunks, chunk_elems, ce)) return ZIPCCL_ERR_INVALID_ARG;
+    for (uint32_t c = 0; c < n_chunks; ++c) static_bytes[c] = slot_layout(ce[c], dt).esc;
+    return ZIPCCL_OK;
+}
+
 size_t zipccl_max_compressed_size(size_t n_elems, zipccl_dtype_t dt, uint32_t n_chunks,
                                   const uint64_t* chunk_elems)
 {

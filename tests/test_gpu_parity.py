@@ -247,3 +247,23 @@ def test_one_chunk_spanning_several_scan_segments(compress_path):
     data[5_000_000:5_020_000] = 0x7F80                      # a dense stretch of zero-points
     _say(f"[segments] n={data.size} path={compress_path}")
     check_parity(data, z.BF16, 0.5, 2, ce, label="scan segments")
+
+
+def test_static_then_dynamic_transfer_as_in_the_second_all_to_all_design():
+    """Send the static parts of all slots first, then the sizes, then the dynamic parts (paper
+    section 3.2, design 2): the receiver rebuilds every slot from the two ranges and decodes."""
+    w = W.make("c3", 1 / 64)
+    d_out, d_cb, _ = gpu_compress(w.data, w.dtype, w.sigma, w.n_chunks, w.chunk_elems)
+    off = z.zipccl_chunk_slot_offsets(w.n_elems, w.dtype, w.n_chunks, w.chunk_elems)
+    st = z.zipccl_chunk_static_bytes(w.n_elems, w.dtype, w.n_chunks, w.chunk_elems)
+    recv = torch.full_like(d_out, 0xEE)
+    for c in range(w.n_chunks):                               # phase 1: static parts, sizes known a priori
+        a = int(off[c])
+        recv[a:a + int(st[c])] = d_out[a:a + int(st[c])]
+    cb = d_cb.cpu().numpy()                                   # phase 2: the size exchange (one u64 per peer)
+    assert np.all(cb.astype(np.uint64) >= st)
+    for c in range(w.n_chunks):                               # phase 3: dynamic parts
+        a, b = int(off[c]) + int(st[c]), int(off[c]) + int(cb[c])
+        recv[a:b] = d_out[a:b]
+    back, status = gpu_decompress(recv, w.n_elems, w.dtype, w.n_chunks, w.chunk_elems)
+    assert status == 0 and np.array_equal(back, w.data)

@@ -69,6 +69,17 @@ def test_sizes_and_offsets_match_oracle():
     assert z.zipccl_compress_min_workspace_size(8192 * 4096 * 2, z.BF16, 2) == 256 + 2 * 4 * 8192
 
 
+def test_static_bytes_match_oracle_layout():
+    # static part = everything but the zero-point list: chunk_bytes of a chunk without zero-points
+    for dt in (z.BF16, z.FP32):
+        ce = np.array([0, 1, 511, 512, 513, 8192, 100000], dtype=np.uint64)
+        st = z.zipccl_chunk_static_bytes(int(ce.sum()), dt, len(ce), ce)
+        assert [int(v) for v in st] == [oracle.chunk_bytes(int(n), 0, dt) for n in ce]
+        assert np.all(st % 128 == 0)
+    with pytest.raises(z.ZipcclError):
+        z.zipccl_chunk_static_bytes(10, z.BF16, 3)
+
+
 def test_argument_errors_return_before_any_launch():
     lib = z._lib
     t = z.zipccl_build_table(1.0)
