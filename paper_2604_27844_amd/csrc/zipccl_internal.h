@@ -25,13 +25,11 @@ constexpr uint32_t kTile = kGroup * kGroupsPerTile; /* 8192 elements */
 constexpr uint32_t kMaxBatch = 128;                 /* chunks per kernel launch */
 constexpr uint32_t kVersion = 1;
 constexpr uint32_t kMagic = 0x4C43505Au;            /* "ZPCL" little-endian */
-constexpr uint32_t kWorkspaceHeader = 256;          /* bytes before the per-tile arrays */
+constexpr uint32_t kWorkspaceHeader = 256;          /* reserved bytes before the per-tile arrays */
 constexpr uint32_t kMaxPeers = 1024;                /* slots one zipccl_decompress_reduce call can sum */
 constexpr uint32_t kStashSlack = 64;                /* readable bytes past the last stash byte */
 
-/* header field offsets */
-constexpr uint32_t kHdrMagic = 0, kHdrVersion = 4, kHdrDtype = 8, kHdrGroup = 12, kHdrN = 16,
-                   kHdrNEsc = 24, kHdrChunkBytes = 32, kHdrDec = 40;
+/* header words (u32 index): 0 magic, 1 version, 2 dtype, 3 G, 4-5 n, 6-7 n_esc, 8-9 chunk_bytes, 10-11 dec[8] */
 
 ZIPCCL_HD uint64_t pad128(uint64_t x) { return (x + 127u) & ~(uint64_t)127u; }
 ZIPCCL_HD uint32_t elem_size(int dt) { return dt == ZIPCCL_BF16 ? 2u : 4u; }
@@ -81,7 +79,6 @@ struct CompressArgs {
     uint32_t* tile_prefix;   /* one u32 per tile: zero-points of its chunk before it */
     uint8_t* stash;          /* stash mode: one byte per input element of this launch (+ slack) */
     struct TileDesc* desc;   /* stash mode: one descriptor per tile, written by k_compress for k_place */
-    uint32_t* err;           /* workspace status word */
     uint32_t e0;             /* dec[1] */
     uint32_t dec_lo, dec_hi; /* dec[0..3], dec[4..7] packed little-endian */
     const uint32_t* d_table; /* when not null: the table lives in device memory (two words), e0/dec_* unused */
