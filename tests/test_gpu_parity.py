@@ -267,3 +267,45 @@ def test_static_then_dynamic_transfer_as_in_the_second_all_to_all_design():
         recv[a:b] = d_out[a:b]
     back, status = gpu_decompress(recv, w.n_elems, w.dtype, w.n_chunks, w.chunk_elems)
     assert status == 0 and np.array_equal(back, w.data)
+
+
+def test_compress_and_decompress_replay_inside_a_hip_graph():
+    """The calls only launch kernels (no allocation, memset or synchronisation), so they can be
+    captured; every replay, on fresh input contents, must equal the oracle."""
+    w0 = W.make("c2", 1 / 16)
+    n, dt, k = w0.n_elems, w0.dtype, w0.n_chunks
+    table = z.zipccl_build_table(w0.sigma, dt)
+    cap = z.zipccl_max_compressed_size(n, dt, k)
+    d_in = to_device_words(w0.data)
+    d_out = torch.empty(cap, dtype=torch.uint8, device=DEV)
+    d_cb = torch.zeros(k, dtype=torch.int64, device=DEV)
+    d_ws = torch.empty(z.zipccl_compress_workspace_size(n, dt, k), dtype=torch.uint8, device=DEV)
+    d_back = torch.zeros_like(d_in)
+    d_st = torch.zeros(1, dtype=torch.int32, device=DEV)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                              # warm-up outside the capture
+        z.zipccl_compress(d_in, n, dt, k, None, table, d_out, d_cb, d_ws)
+        z.zipccl_decompress(d_out, d_back, n, dt, k, None, d_st)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        z.zipccl_compress(d_in, n, dt, k, None, table, d_out, d_cb, d_ws)
+        z.zipccl_decompress(d_out, d_back, n, dt, k, None, d_st)
+    rng = np.random.default_rng(5)
+    for rep in range(3):
+        data = W.f32_to_bf16_words(rng.standard_normal(n, dtype=np.float32) * np.float32(1.0 + rep))
+        d_in.copy_(to_device_words(data))                      # eager work between replays
+        d_out.fill_(0xA5)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        ref, ref_cb, off = oracle.compress(data, dt, oracle.build_table(w0.sigma), k)
+        got = d_out.cpu().numpy()
+        assert np.array_equal(d_cb.cpu().numpy().astype(np.uint64), ref_cb), rep
+        for c in range(k):
+            a, b = int(off[c]), int(off[c]) + int(ref_cb[c])
+            assert np.array_equal(got[a:b], ref[a:b]), (rep, c)
+        assert int(d_st.item()) == 0
+        assert np.array_equal(d_back.cpu().numpy().view(np.uint16), data), rep
