@@ -86,9 +86,9 @@ uint64_t total_tiles(const std::vector<uint64_t>& ce)
     return t;
 }
 
-/* Workspace layout: header | u32 count per tile | u32 prefix per tile | [tile descriptors | stash (one byte per element)]. */
+/* Workspace layout: header | u32 count per tile | u32 prefix per tile | [stash (one byte per element)]. */
 struct WorkspacePlan {
-    uint64_t tiles, total_off, prefix_off, desc_off, stash_off, min_bytes, full_bytes;
+    uint64_t tiles, total_off, prefix_off, stash_off, min_bytes, full_bytes;
 };
 
 WorkspacePlan plan_workspace(const std::vector<uint64_t>& ce, uint64_t n_elems)
@@ -98,9 +98,8 @@ WorkspacePlan plan_workspace(const std::vector<uint64_t>& ce, uint64_t n_elems)
     const uint64_t arr = (4 * w.tiles + 15) & ~15ull;
     w.total_off = kWorkspaceHeader;
     w.prefix_off = w.total_off + arr;
-    w.desc_off = w.prefix_off + arr;
-    w.min_bytes = w.desc_off;
-    w.stash_off = w.desc_off + sizeof(TileDesc) * w.tiles;
+    w.stash_off = w.prefix_off + arr;
+    w.min_bytes = w.stash_off;
     w.full_bytes = w.stash_off + ((n_elems + kStashSlack + 15) & ~15ull);
     return w;
 }
@@ -243,15 +242,14 @@ zipccl_status_t compress_impl(const void* d_in, size_t n_elems, zipccl_dtype_t d
         a.tile_total = reinterpret_cast<uint32_t*>(ws + wp.total_off) + tile_base;
         a.tile_prefix = reinterpret_cast<uint32_t*>(ws + wp.prefix_off) + tile_base;
         a.stash = stash ? ws + wp.stash_off + elem_base : nullptr;
-        a.desc = stash ? reinterpret_cast<TileDesc*>(ws + wp.desc_off) + tile_base : nullptr;
         if (stash) {
-            if (launch_compress(dt, kModeStash, a, nt, stream) != 0) return ZIPCCL_ERR_DEVICE;
+            if (launch_compress(dt, kModeStash, a, stream) != 0) return ZIPCCL_ERR_DEVICE;
             if (launch_tile_scan(a, stream) != 0) return ZIPCCL_ERR_DEVICE;
-            if (launch_place(dt, a, nt, stream) != 0) return ZIPCCL_ERR_DEVICE;
+            if (launch_place(dt, a, stream) != 0) return ZIPCCL_ERR_DEVICE;
         } else {
-            if (launch_compress(dt, kModeCount, a, nt, stream) != 0) return ZIPCCL_ERR_DEVICE;
+            if (launch_compress(dt, kModeCount, a, stream) != 0) return ZIPCCL_ERR_DEVICE;
             if (launch_tile_scan(a, stream) != 0) return ZIPCCL_ERR_DEVICE;
-            if (launch_compress(dt, kModeEmit, a, nt, stream) != 0) return ZIPCCL_ERR_DEVICE;
+            if (launch_compress(dt, kModeEmit, a, stream) != 0) return ZIPCCL_ERR_DEVICE;
         }
         elem_base += a.tab.elem_off[nb];
         tile_base += nt;
@@ -338,11 +336,11 @@ zipccl_status_t zipccl_decompress(const void* d_comp, size_t comp_capacity,
     uint64_t elem_base = 0;
     for (uint32_t c0 = 0; c0 < n_chunks; c0 += kMaxBatch) {
         const uint32_t nb = (n_chunks - c0) < kMaxBatch ? (n_chunks - c0) : kMaxBatch;
-        const uint32_t nt = fill_tab(a.tab, ce, slot_off, c0, nb, dt);
+        fill_tab(a.tab, ce, slot_off, c0, nb, dt);
         a.comp = static_cast<const uint8_t*>(d_comp) + slot_off[c0];
         a.comp_capacity = comp_capacity - slot_off[c0];
         a.out = static_cast<uint8_t*>(d_out) + elem_base * es;
-        if (launch_decompress(dt, a, nt, stream) != 0) return ZIPCCL_ERR_DEVICE;
+        if (launch_decompress(dt, a, stream) != 0) return ZIPCCL_ERR_DEVICE;
         elem_base += a.tab.elem_off[nb];
     }
     return ZIPCCL_OK;

@@ -62,15 +62,6 @@ struct ChunkTab {
     uint64_t slot_off[kMaxBatch + 1];   /* byte offset of slot c, relative to the launch's output */
 };
 
-/* What k_place needs to know about a tile, so that it does no chunk search of its own. */
-struct TileDesc {
-    uint64_t slot;        /* address of the tile's chunk slot */
-    uint64_t n;           /* elements in the chunk */
-    uint64_t stash;       /* address of the tile's stash */
-    uint32_t group0;      /* index of the tile's first group inside the chunk */
-    uint32_t chunk_last;  /* bit 0: last tile of its chunk; bits 8..: chunk index in this launch */
-};
-
 struct CompressArgs {
     const uint8_t* in;       /* first element of the launch's first chunk */
     uint8_t* out;            /* compressed buffer base for this launch */
@@ -78,7 +69,6 @@ struct CompressArgs {
     uint32_t* tile_total;    /* one u32 per tile of this launch: its zero-point count */
     uint32_t* tile_prefix;   /* one u32 per tile: zero-points of its chunk before it */
     uint8_t* stash;          /* stash mode: one byte per input element of this launch (+ slack) */
-    struct TileDesc* desc;   /* stash mode: one descriptor per tile, written by k_compress for k_place */
     uint32_t e0;             /* dec[1] */
     uint32_t dec_lo, dec_hi; /* dec[0..3], dec[4..7] packed little-endian */
     const uint32_t* d_table; /* when not null: the table lives in device memory (two words), e0/dec_* unused */
@@ -122,10 +112,10 @@ enum CompressMode { kModeCount = 0, kModeEmit = 1, kModeStash = 2 };
 /* launchers implemented in zipccl_kernels.hip; return a hipError_t as int */
 int launch_copy(void* d_dst, const void* d_src, uint64_t bytes, void* stream);
 int launch_estimate(int dt, const MomentArgs& a, void* stream);
-int launch_compress(int dt, int mode, const CompressArgs& a, uint32_t n_tiles, void* stream);
+int launch_compress(int dt, int mode, const CompressArgs& a, void* stream);
 int launch_tile_scan(const CompressArgs& a, void* stream);
-int launch_place(int dt, const CompressArgs& a, uint32_t n_tiles, void* stream);
-int launch_decompress(int dt, const DecompressArgs& a, uint32_t n_tiles, void* stream);
+int launch_place(int dt, const CompressArgs& a, void* stream);
+int launch_decompress(int dt, const DecompressArgs& a, void* stream);
 int launch_decompress_reduce(int dt, int out_dt, const ReduceArgs& a, uint32_t n_tiles, void* stream);
 
 } // namespace zipccl

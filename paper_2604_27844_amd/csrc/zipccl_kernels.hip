@@ -81,17 +81,6 @@ __device__ __forceinline__ uint32_t row_incl_scan(uint32_t x)
     return x;
 }
 
-/* largest c with tile_start[c] <= t (every chunk owns at least one tile) */
-__device__ __forceinline__ uint32_t find_chunk(const ChunkTab& tab, uint32_t t)
-{
-    uint32_t lo = 0, hi = tab.n_chunks;
-    while (hi - lo > 1) {
-        const uint32_t mid = (lo + hi) >> 1;
-        if (tab.tile_start[mid] <= t) lo = mid; else hi = mid;
-    }
-    return lo;
-}
-
 /*
  * Load the lane's 8 consecutive values starting at chunk-relative element e.
  * hp[k] packs the high 16-bit words of values 2k (low half) and 2k+1 (high half);
@@ -280,12 +269,15 @@ __global__ __launch_bounds__(kThreads) void k_compress(const CompressArgs a)
     constexpr bool STORE = MODE != kModeCount;
     __shared__ CompressShared sh;
 
-    const uint32_t t = blockIdx.x;
-    const uint32_t c = find_chunk(a.tab, t);
+    /* grid = (tiles of the largest chunk, chunks): no search, the chunk's geometry is three scalar loads */
+    const uint32_t c = blockIdx.y;
     const uint32_t first = a.tab.tile_start[c];
-    const bool last_tile = (t + 1u == a.tab.tile_start[c + 1]);
+    const uint32_t ntc = a.tab.tile_start[c + 1] - first;
+    if (blockIdx.x >= ntc) return;
+    const uint32_t t = first + blockIdx.x;
+    const bool last_tile = blockIdx.x + 1u == ntc;
     const uint64_t n = a.tab.elem_off[c + 1] - a.tab.elem_off[c];
-    const uint64_t ts = (uint64_t)(t - first) * kTile;
+    const uint64_t ts = (uint64_t)blockIdx.x * kTile;
     const uint8_t* __restrict__ cin = a.in + a.tab.elem_off[c] * ES;
     uint8_t* __restrict__ slot = a.out + a.tab.slot_off[c];
     const SlotLayout L = slot_layout(n, DT);
@@ -318,16 +310,7 @@ __global__ __launch_bounds__(kThreads) void k_compress(const CompressArgs a)
         if (threadIdx.x == 0) a.tile_total[t] = tile_total;
         return;
     }
-    if (MODE == kModeStash && threadIdx.x == 0) {
-        a.tile_total[t] = tile_total;
-        TileDesc d;
-        d.slot = reinterpret_cast<uint64_t>(slot);
-        d.n = n;
-        d.stash = reinterpret_cast<uint64_t>(a.stash + a.tab.elem_off[c] + ts);
-        d.group0 = (uint32_t)(ts / kGroup);
-        d.chunk_last = (c << 8) | (last_tile ? 1u : 0u);
-        a.desc[t] = d;
-    }
+    if (MODE == kModeStash && threadIdx.x == 0) a.tile_total[t] = tile_total;
 
     /* kModeEmit knows the zero-points of the chunk before this tile; kModeStash works tile-local */
     const uint32_t P = MODE == kModeEmit ? a.tile_prefix[t] : 0u;
@@ -392,7 +375,7 @@ __device__ __forceinline__ void move_words(uint32_t* __restrict__ d32, const uin
  * bytes) are moved by the whole workgroup afterwards.
  */
 template <int DT>
-__global__ __launch_bounds__(kThreads) void k_place(const CompressArgs a, uint32_t n_tiles)
+__global__ __launch_bounds__(kThreads) void k_place(const CompressArgs a)
 {
     constexpr uint32_t kSub = 16;                       /* lanes per tile */
     constexpr uint32_t kPlaceBig = 1024;                /* bytes a 16-lane group moves on its own */
@@ -403,29 +386,34 @@ __global__ __launch_bounds__(kThreads) void k_place(const CompressArgs a, uint32
     if (threadIdx.x == 0) s_nbig = 0;
     __syncthreads();
 
-    const uint32_t sub = threadIdx.x % kSub;
-    const uint32_t tw = threadIdx.x / kSub;             /* tile inside the workgroup */
-    const uint32_t t = blockIdx.x * (kThreads / kSub) + tw;
+    /* grid = (16-tile groups of the largest chunk, chunks): the chunk's geometry is wave-uniform */
+    const uint32_t c = blockIdx.y;
+    const uint32_t first = a.tab.tile_start[c];
+    const uint32_t ntc = a.tab.tile_start[c + 1] - first;
+    const uint64_t n = a.tab.elem_off[c + 1] - a.tab.elem_off[c];
+    uint8_t* __restrict__ slot = a.out + a.tab.slot_off[c];
+    const SlotLayout L = slot_layout(n, DT);
     const uint32_t dec_lo = a.d_table ? a.d_table[0] : a.dec_lo;
     const uint32_t dec_hi = a.d_table ? a.d_table[1] : a.dec_hi;
-    if (t < n_tiles) {
-        const TileDesc d = a.desc[t];
-        const uint64_t n = d.n;
-        uint8_t* __restrict__ slot = reinterpret_cast<uint8_t*>(d.slot);
-        const SlotLayout L = slot_layout(n, DT);
-        const uint32_t P = a.tile_prefix[t];
-        const uint32_t cnt = a.tile_total[t];
 
-        /* the tile's 16 index entries */
+    const uint32_t sub = threadIdx.x % kSub;
+    const uint32_t tw = threadIdx.x / kSub;             /* tile inside the workgroup */
+    const uint32_t ti = blockIdx.x * (kThreads / kSub) + tw;
+    if (ti < ntc) {
+        const uint32_t t = first + ti;
+        const uint8_t* __restrict__ src = a.stash + a.tab.elem_off[c] + (uint64_t)ti * kTile;
+        /* everything that does not depend on the counts is loaded together with them:
+           the tile's 16 index entries and the first 64 bytes of its stash */
         const uint64_t ng = (n + kGroup - 1) / kGroup;
         uint32_t* __restrict__ idx = reinterpret_cast<uint32_t*>(slot + L.idx);
-        const uint64_t g = (uint64_t)d.group0 + sub;
-        const bool fix_idx = P != 0u && g < ng;
+        const uint64_t g = (uint64_t)ti * kGroupsPerTile + sub;
         uint32_t idx_local = 0;
-        if (fix_idx) idx_local = idx[g];
+        if (g < ng) idx_local = idx[g];
+        const uint32_t P = a.tile_prefix[t];
+        const uint32_t cnt = a.tile_total[t];
+        if (P != 0u && g < ng) idx[g] = idx_local + P;
 
         /* byte-exact move to an arbitrarily aligned destination: head bytes, aligned words, tail bytes */
-        const uint8_t* __restrict__ src = reinterpret_cast<const uint8_t*>(d.stash);
         uint8_t* __restrict__ dst = slot + L.esc + P;
         const uint32_t head = min((uint32_t)(-(int64_t)reinterpret_cast<uintptr_t>(dst)) & 3u, cnt);
         const uint32_t nw = (cnt - head) >> 2;
@@ -449,10 +437,9 @@ __global__ __launch_bounds__(kThreads) void k_place(const CompressArgs a, uint32
         }
         if (sub < head) dst[sub] = hb;
         if (sub < cnt - done) dst[done + sub] = tb;
-        if (fix_idx) idx[g] = idx_local + P;
-        if (d.chunk_last & 1u)
+        if (ti + 1u == ntc)
             finish_chunk<DT, kSub>(slot, L, n, (uint64_t)P + cnt, dec_lo, dec_hi,
-                                   a.chunk_bytes ? a.chunk_bytes + (d.chunk_last >> 8) : nullptr, sub);
+                                   a.chunk_bytes ? a.chunk_bytes + c : nullptr, sub);
     }
     __syncthreads();
     const uint32_t nbig = s_nbig;
@@ -751,17 +738,19 @@ __device__ __forceinline__ bool check_header(const uint8_t* __restrict__ slot, c
 }
 
 template <int DT>
-__global__ __launch_bounds__(kThreads) void k_decompress(const DecompressArgs a)
+__global__ __launch_bounds__(kThreads, DT == ZIPCCL_BF16 ? 8 : 6)   /* waves per SIMD: <= 64 VGPRs for bf16, <= 80 for fp32 */
+void k_decompress(const DecompressArgs a)
 {
     constexpr uint32_t ES = DT == ZIPCCL_BF16 ? 2u : 4u;
     __shared__ DecTables s_tab;
     __shared__ __attribute__((aligned(16))) uint8_t s_esc[kWavesPerBlock][kGroupsPerWave][kEscRegion];
     build_tables(s_tab);
 
-    const uint32_t t = blockIdx.x;
-    const uint32_t c = find_chunk(a.tab, t);
+    /* grid = (tiles of the largest chunk, chunks) */
+    const uint32_t c = blockIdx.y;
+    if (blockIdx.x >= a.tab.tile_start[c + 1] - a.tab.tile_start[c]) return;
     const uint64_t n = a.tab.elem_off[c + 1] - a.tab.elem_off[c];
-    const uint64_t ts = (uint64_t)(t - a.tab.tile_start[c]) * kTile;
+    const uint64_t ts = (uint64_t)blockIdx.x * kTile;
     const uint8_t* __restrict__ slot = a.comp + a.tab.slot_off[c];
     uint8_t* __restrict__ cout = a.out + a.tab.elem_off[c] * ES;
     const SlotLayout L = slot_layout(n, DT);
@@ -1084,9 +1073,20 @@ int launch_copy(void* d_dst, const void* d_src, uint64_t bytes, void* stream)
     return (int)hipGetLastError();
 }
 
-int launch_compress(int dt, int mode, const CompressArgs& a, uint32_t n_tiles, void* stream)
+/* tiles of the largest chunk of the launch */
+static uint32_t max_chunk_tiles(const ChunkTab& tab)
 {
-    const dim3 grid(n_tiles), block(kThreads);
+    uint32_t m = 1;
+    for (uint32_t c = 0; c < tab.n_chunks; ++c) {
+        const uint32_t nt = tab.tile_start[c + 1] - tab.tile_start[c];
+        m = nt > m ? nt : m;
+    }
+    return m;
+}
+
+int launch_compress(int dt, int mode, const CompressArgs& a, void* stream)
+{
+    const dim3 grid(max_chunk_tiles(a.tab), a.tab.n_chunks), block(kThreads);
     hipStream_t s = (hipStream_t)stream;
 #define ZIPCCL_LAUNCH(DT, MODE) hipLaunchKernelGGL((k_compress<DT, MODE>), grid, block, 0, s, a)
     if (dt == ZIPCCL_BF16) {
@@ -1104,29 +1104,24 @@ int launch_compress(int dt, int mode, const CompressArgs& a, uint32_t n_tiles, v
 
 int launch_tile_scan(const CompressArgs& a, void* stream)
 {
-    uint32_t max_tiles = 1;
-    for (uint32_t c = 0; c < a.tab.n_chunks; ++c) {
-        const uint32_t nt = a.tab.tile_start[c + 1] - a.tab.tile_start[c];
-        max_tiles = nt > max_tiles ? nt : max_tiles;
-    }
-    const dim3 grid((max_tiles + kScanSeg - 1) / kScanSeg, a.tab.n_chunks);
+    const dim3 grid((max_chunk_tiles(a.tab) + kScanSeg - 1) / kScanSeg, a.tab.n_chunks);
     hipLaunchKernelGGL(k_tile_scan, grid, dim3(kThreads), 0, (hipStream_t)stream, a);
     return (int)hipGetLastError();
 }
 
-int launch_place(int dt, const CompressArgs& a, uint32_t n_tiles, void* stream)
+int launch_place(int dt, const CompressArgs& a, void* stream)
 {
-    const dim3 grid((n_tiles + 15) / 16), block(kThreads);   /* 16 tiles per workgroup */
+    const dim3 grid((max_chunk_tiles(a.tab) + 15) / 16, a.tab.n_chunks), block(kThreads);   /* 16 tiles per workgroup */
     if (dt == ZIPCCL_BF16)
-        hipLaunchKernelGGL((k_place<ZIPCCL_BF16>), grid, block, 0, (hipStream_t)stream, a, n_tiles);
+        hipLaunchKernelGGL((k_place<ZIPCCL_BF16>), grid, block, 0, (hipStream_t)stream, a);
     else
-        hipLaunchKernelGGL((k_place<ZIPCCL_FP32>), grid, block, 0, (hipStream_t)stream, a, n_tiles);
+        hipLaunchKernelGGL((k_place<ZIPCCL_FP32>), grid, block, 0, (hipStream_t)stream, a);
     return (int)hipGetLastError();
 }
 
-int launch_decompress(int dt, const DecompressArgs& a, uint32_t n_tiles, void* stream)
+int launch_decompress(int dt, const DecompressArgs& a, void* stream)
 {
-    const dim3 grid(n_tiles), block(kThreads);
+    const dim3 grid(max_chunk_tiles(a.tab), a.tab.n_chunks), block(kThreads);
     if (dt == ZIPCCL_BF16)
         hipLaunchKernelGGL((k_decompress<ZIPCCL_BF16>), grid, block, 0, (hipStream_t)stream, a);
     else

@@ -62,9 +62,9 @@ def test_sizes_and_offsets_match_oracle():
     assert z.zipccl_max_compressed_size(10, z.BF16, 2, [4, 5]) == 0       # must sum to n
     assert z.zipccl_max_compressed_size(10, 5, 1) == 0
     # header + (u32 count + u32 prefix) per tile, each array padded to 16 bytes
-    # [+ 32-byte descriptor per tile + stash: 1 byte per element + slack]
+    # [+ stash: 1 byte per element + slack]
     assert z.zipccl_compress_min_workspace_size(8192 * 3 + 1, z.BF16, 1) == 256 + 16 + 16
-    assert z.zipccl_compress_workspace_size(8192 * 3 + 1, z.BF16, 1) == 256 + 32 + 4 * 32 + (8192 * 3 + 1 + 64 + 15) // 16 * 16
+    assert z.zipccl_compress_workspace_size(8192 * 3 + 1, z.BF16, 1) == 256 + 32 + (8192 * 3 + 1 + 64 + 15) // 16 * 16
     assert z.zipccl_compress_min_workspace_size(0, z.BF16, 2, [0, 0]) == 256 + 32
     assert z.zipccl_compress_min_workspace_size(8192 * 4096 * 2, z.BF16, 2) == 256 + 2 * 4 * 8192
 
