@@ -558,7 +558,6 @@ struct DecEsc {
     uint32_t m;              /* bit j = value j is a zero-point */
     uint32_t sh;             /* byte offset of the lane's first zero-point inside d0 */
     uint32_t d0, d1, d2;     /* three aligned words covering the lane's 8 list bytes */
-    bool any;                /* the group has zero-points at all */
     bool bad;                /* planes and IDX disagree about the group */
 };
 
@@ -575,17 +574,19 @@ __device__ __forceinline__ void decode_index(const uint8_t* __restrict__ slot, c
 }
 
 /* Phase 1a: fetch the slice [base, base + count), 8 aligned bytes per lane (+ 8 more by lane 0 when a
- * full group starts off alignment).  Aligned reads stay inside pad128(n_esc). */
+ * full group starts off alignment).  Aligned reads stay inside pad128(n_esc); lanes past the slice read
+ * the 8 bytes in front of the list instead (the end of the static part), so the load needs no predicate. */
 __device__ __forceinline__ void decode_fetch_list(const uint8_t* __restrict__ slot, const SlotLayout& L,
                                                   const DecIn& r, uint32_t next, uint32_t lane, u32x2& v, u32x2& tail)
 {
-    v = u32x2{0u, 0u};
+    const uint32_t end = r.count != 0u ? next : 0u;              /* nothing to fetch for an empty slice */
+    const uint32_t a8 = r.base & ~7u;
+    const uint32_t a = a8 + 8u * lane;
+    const uint8_t* __restrict__ esc = slot + L.esc;
+    v = *reinterpret_cast<const u32x2*>(esc + (a < end ? (int64_t)a : (int64_t)-8));
     tail = u32x2{0u, 0u};
-    if (r.count != 0u) {
-        const uint32_t a8 = r.base & ~7u;
-        const uint32_t a = a8 + 8u * lane;
-        if (a < next) v = *reinterpret_cast<const u32x2*>(slot + L.esc + a);
-        if (lane == 0 && a8 + kGroup < next) tail = *reinterpret_cast<const u32x2*>(slot + L.esc + a8 + kGroup);
+    if (a8 + kGroup < end) {                                      /* wave-uniform and rare */
+        if (lane == 0) tail = *reinterpret_cast<const u32x2*>(esc + a8 + kGroup);
     }
 }
 
@@ -626,7 +627,9 @@ __device__ __forceinline__ void decode_park_list(uint8_t* lds, uint32_t lane, co
     if (lane == 0) *reinterpret_cast<u32x2*>(lds + kGroup) = tail;
 }
 
-/* Phase 2: wave scan of the per-lane zero-point counts, then the lane's bytes from the LDS region. */
+/* Phase 2: wave scan of the per-lane zero-point counts, then the lane's bytes from the LDS region.
+ * Straight-line code (no branch on whether the group has zero-points) so that the four groups a
+ * wave works on can be interleaved by the scheduler. */
 __device__ __forceinline__ DecEsc decode_locate(const DecIn& in, const uint8_t* lds)
 {
     DecEsc r;
@@ -634,16 +637,13 @@ __device__ __forceinline__ DecEsc decode_locate(const DecIn& in, const uint8_t* 
     const uint32_t cnt = __popc(r.m);
     const uint32_t inc = wave_incl_scan(cnt);
     const uint32_t gtot = __builtin_amdgcn_readlane(inc, 63);
-    r.any = gtot != 0u;
     r.bad = !in.idx_ok || gtot != in.count;        /* planes and IDX must agree */
-    r.sh = r.d0 = r.d1 = r.d2 = 0;
-    if (r.any && !r.bad) {
-        /* the lane's zero-point exponents are the bytes [p, p + cnt) of the region, p <= 7 + 512 - cnt */
-        const uint32_t p = (in.base & 7u) + (inc - cnt);
-        const uint32_t* w = reinterpret_cast<const uint32_t*>(lds + (p & ~3u));
-        r.d0 = w[0]; r.d1 = w[1]; r.d2 = w[2];
-        r.sh = p & 3u;
-    }
+    /* the lane's zero-point exponents are the bytes [p, p + cnt) of the region, p <= 7 + 512 - cnt
+       (clamped, so that a corrupt stream still reads inside the region) */
+    const uint32_t p = min((in.base & 7u) + (inc - cnt), kGroup + 7u);
+    const uint32_t* w = reinterpret_cast<const uint32_t*>(lds + (p & ~3u));
+    r.d0 = w[0]; r.d1 = w[1]; r.d2 = w[2];
+    r.sh = p & 3u;
     return r;
 }
 
@@ -657,7 +657,7 @@ __device__ __forceinline__ void decode_values(const DecIn& in, const DecEsc& es,
     uint32_t eA = (t0.x | (t1.x << 1) | (t2.x << 2)) + k4;
     uint32_t eB = (t0.y | (t1.y << 1) | (t2.y << 2)) + k4;
     const uint2* __restrict__ lut = tab.expand;
-    if (es.any && !es.bad) {
+    {   /* zero-point exponents dropped in place; a lane without zero-points selects nothing */
         const uint32_t l8 = __builtin_amdgcn_alignbyte(es.d1, es.d0, es.sh);
         const uint32_t h8 = __builtin_amdgcn_alignbyte(es.d2, es.d1, es.sh);
         const uint32_t mA = es.m & 15u, mB = es.m >> 4;
