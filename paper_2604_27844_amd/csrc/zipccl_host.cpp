@@ -366,7 +366,7 @@ zipccl_status_t zipccl_decompress_reduce(const void* d_comp, size_t comp_capacit
     a.status = d_status;
     a.n = n_elems;
     a.n_peers = n_peers;
-    return launch_decompress_reduce(dt, out_dt, a, (uint32_t)tiles_of(n_elems), stream) == 0 ? ZIPCCL_OK : ZIPCCL_ERR_DEVICE;
+    return launch_decompress_reduce(dt, out_dt, a, stream) == 0 ? ZIPCCL_OK : ZIPCCL_ERR_DEVICE;
 }
 
 zipccl_status_t zipccl_debug_copy(void* d_dst, const void* d_src, size_t bytes, void* stream)

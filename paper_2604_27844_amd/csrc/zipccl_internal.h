@@ -116,7 +116,7 @@ int launch_compress(int dt, int mode, const CompressArgs& a, void* stream);
 int launch_tile_scan(const CompressArgs& a, void* stream);
 int launch_place(int dt, const CompressArgs& a, void* stream);
 int launch_decompress(int dt, const DecompressArgs& a, void* stream);
-int launch_decompress_reduce(int dt, int out_dt, const ReduceArgs& a, uint32_t n_tiles, void* stream);
+int launch_decompress_reduce(int dt, int out_dt, const ReduceArgs& a, void* stream);
 
 } // namespace zipccl
 #endif

@@ -831,9 +831,12 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
  * slot order starting from peer 0's value.  One pass: every compressed byte is read once and
  * only the sum is written.  Work decomposition as in k_decompress; the peer loop is innermost.
  */
-template <int DT, int ODT>
+/* GPW = groups per wave: 4 for large shards, 1 for small ones (four times as many workgroups, each with a
+ * quarter of the sequential peer loop). */
+template <int DT, int ODT, uint32_t GPW>
 __global__ __launch_bounds__(kThreads) void k_decompress_reduce(const ReduceArgs a)
 {
+    constexpr uint32_t kRTile = kGroup * kWavesPerBlock * GPW;
     constexpr uint32_t OES = ODT == ZIPCCL_BF16 ? 2u : 4u;
     __shared__ DecTables s_tab;
     __shared__ __attribute__((aligned(16))) uint8_t s_esc[kWavesPerBlock][kEscRegion];
@@ -842,7 +845,7 @@ __global__ __launch_bounds__(kThreads) void k_decompress_reduce(const ReduceArgs
     build_tables(s_tab);
 
     const uint64_t n = a.n;
-    const uint64_t ts = (uint64_t)blockIdx.x * kTile;
+    const uint64_t ts = (uint64_t)blockIdx.x * kRTile;
     const SlotLayout L = slot_layout(n, DT);
     bool bad = false;
     /* every slot's header is checked once per workgroup, one peer per thread */
@@ -856,11 +859,11 @@ __global__ __launch_bounds__(kThreads) void k_decompress_reduce(const ReduceArgs
     }
     __syncthreads();
 
-    const bool fast = (ts + kTile <= n) && ((reinterpret_cast<uintptr_t>(a.out) & 15u) == 0);
+    const bool fast = (ts + kRTile <= n) && ((reinterpret_cast<uintptr_t>(a.out) & 15u) == 0);
     const uint32_t lane = lane_id();
     const uint32_t wave = threadIdx.x >> 6;
     const uint64_t ng = (n + kGroup - 1) / kGroup;
-    for (uint32_t u = 0; u < kGroupsPerWave; ++u) {
+    for (uint32_t u = 0; u < GPW; ++u) {
         const uint64_t gstart = ts + (uint64_t)(u * kWavesPerBlock + wave) * kGroup;
         if (gstart >= n) continue;
         const uint64_t g = gstart / kGroup;
@@ -1038,18 +1041,24 @@ __global__ __launch_bounds__(kThreads) void k_copy(const u32x4* __restrict__ src
 
 } // namespace
 
-int launch_decompress_reduce(int dt, int out_dt, const ReduceArgs& a, uint32_t n_tiles, void* stream)
+int launch_decompress_reduce(int dt, int out_dt, const ReduceArgs& a, void* stream)
 {
-    const dim3 grid(n_tiles), block(kThreads);
     hipStream_t s = (hipStream_t)stream;
-    if (dt == ZIPCCL_BF16 && out_dt == ZIPCCL_FP32)
-        hipLaunchKernelGGL((k_decompress_reduce<ZIPCCL_BF16, ZIPCCL_FP32>), grid, block, 0, s, a);
-    else if (dt == ZIPCCL_BF16)
-        hipLaunchKernelGGL((k_decompress_reduce<ZIPCCL_BF16, ZIPCCL_BF16>), grid, block, 0, s, a);
-    else if (out_dt == ZIPCCL_FP32)
-        hipLaunchKernelGGL((k_decompress_reduce<ZIPCCL_FP32, ZIPCCL_FP32>), grid, block, 0, s, a);
-    else
-        hipLaunchKernelGGL((k_decompress_reduce<ZIPCCL_FP32, ZIPCCL_BF16>), grid, block, 0, s, a);
+    const dim3 block(kThreads);
+    /* at least ~8 workgroups per CU before a workgroup takes four groups per wave */
+    const bool big = a.n >= (uint64_t)kTile * 2048u;
+    const uint64_t per = big ? kTile : kTile / kGroupsPerWave;
+    const dim3 grid((uint32_t)(a.n == 0 ? 1 : (a.n + per - 1) / per));
+#define ZIPCCL_REDUCE(DT, ODT)                                                                          \
+    do {                                                                                                \
+        if (big) hipLaunchKernelGGL((k_decompress_reduce<DT, ODT, kGroupsPerWave>), grid, block, 0, s, a); \
+        else hipLaunchKernelGGL((k_decompress_reduce<DT, ODT, 1u>), grid, block, 0, s, a);              \
+    } while (0)
+    if (dt == ZIPCCL_BF16 && out_dt == ZIPCCL_FP32) ZIPCCL_REDUCE(ZIPCCL_BF16, ZIPCCL_FP32);
+    else if (dt == ZIPCCL_BF16) ZIPCCL_REDUCE(ZIPCCL_BF16, ZIPCCL_BF16);
+    else if (out_dt == ZIPCCL_FP32) ZIPCCL_REDUCE(ZIPCCL_FP32, ZIPCCL_FP32);
+    else ZIPCCL_REDUCE(ZIPCCL_FP32, ZIPCCL_BF16);
+#undef ZIPCCL_REDUCE
     return (int)hipGetLastError();
 }
 

@@ -68,6 +68,13 @@ def test_reduce_parity(dtype, out_dt):
         _check(_peers(rng, P, n, dtype, sig), dtype, sig, out_dt, f"P={P} n={n}")
 
 
+def test_reduce_large_shard_takes_the_four_groups_per_wave_form():
+    rng = np.random.default_rng(44)
+    n = 2048 * 8192 + 5000                                   # past the size where workgroups take 4 groups per wave
+    sig = [0.02, 0.03]
+    _check(_peers(rng, 2, n, z.BF16, sig), z.BF16, sig, z.FP32, "large shard")
+
+
 def test_reduce_order_specials_and_cancellation():
     n = 8192 + 37
     big = np.full(n, W.f32_to_bf16_words(np.array([2.0 ** 30], dtype=np.float32))[0], dtype=np.uint16)
