@@ -6,8 +6,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libzipccl.so")
-SOURCES = ["zipccl_kernels.hip", "zipccl_host.cpp"]
-HEADERS = [os.path.join(CSRC, "zipccl_internal.h"), os.path.join(ROOT, "include", "zipccl.h")]
+SOURCES = ["zipccl_compress.hip", "zipccl_decompress.hip", "zipccl_aux.hip", "zipccl_host.cpp"]
+HEADERS = [os.path.join(CSRC, "zipccl_internal.h"), os.path.join(CSRC, "zipccl_device.h"),
+           os.path.join(ROOT, "include", "zipccl.h")]
 
 
 def stale():

@@ -1,0 +1,486 @@
+/*
+ * Decompress side of libzipccl.so for gfx950 (CDNA4, wave64): k_decompress (paper section 4, third
+ * paragraph) and k_decompress_reduce (decode + local FP32 reduction of the zipped Reduce-Scatter,
+ * sections 3.3 and 5.2).  No workgroup depends on another.  Work decomposition as on the compress side:
+ * a wave owns a group of 512 values at a time, 8 consecutive values per lane; decoding is SWAR on packed
+ * bytes (table-driven bit spread, v_perm_b32 / v_bfi_b32 recombination) with a DPP wave scan to
+ * locate each lane's zero-point exponents.
+ */
+#include "zipccl_device.h"
+
+namespace zipccl {
+namespace {
+
+/*
+ * Decoder tables in LDS, indexed by a 4-bit zero-point mask q of four values:
+ * .x = v_perm selector putting the r-th byte of a compacted list at the position of the r-th
+ * set bit of q (0x0c = constant 0 elsewhere), .y = 0xff in the bytes of set bits.
+ */
+__device__ __forceinline__ uint2 expand_entry(uint32_t q)
+{
+    uint32_t sel = 0, msk = 0, r = 0;
+#pragma unroll
+    for (uint32_t i = 0; i < 4; ++i) {
+        if ((q >> i) & 1u) { sel |= r << (8 * i); msk |= 0xFFu << (8 * i); ++r; }
+        else sel |= 0x0Cu << (8 * i);
+    }
+    return make_uint2(sel, msk);
+}
+
+/* bits 0..3 of x -> bit 0 of bytes 0..3 */
+__device__ __forceinline__ uint32_t spread4(uint32_t x)
+{
+    return __umul24(x, 0x204081u) & 0x01010101u;
+}
+
+/* Decoder tables in LDS, built once per workgroup (one entry per thread). */
+struct DecTables {
+    uint2 spread[256];   /* plane byte -> its 8 bits in bit 0 of 8 bytes (.x = values 0..3, .y = values 4..7) */
+    uint2 expand[16];    /* 4-bit zero-point mask -> v_perm selector and byte mask, see expand_entry */
+};
+
+__device__ __forceinline__ void build_tables(DecTables& t)
+{
+    t.spread[threadIdx.x] = make_uint2(spread4(threadIdx.x & 15u), spread4(threadIdx.x >> 4));   /* kThreads == 256 */
+    if (threadIdx.x < 16) t.expand[threadIdx.x] = expand_entry(threadIdx.x);
+}
+
+/* Bytes of LDS per group for its zero-point exponents: 512 + up to 7 of misalignment, rounded up,
+ * + 8 so that a lane's three aligned words never leave the region. */
+constexpr uint32_t kEscRegion = 544;
+
+/* What a lane reads for its 8 values of one group. */
+struct DecIn {
+    uint32_t sm0, sm1;       /* 8 sign+mantissa bytes */
+    uint32_t b0, b1, b2;     /* plane bytes */
+    uint32_t lo[4];          /* fp32: 8 low 16-bit words */
+    uint32_t base;           /* IDX entry of the group = list position of its first zero-point */
+    uint32_t count;          /* zero-points of the group according to IDX (next entry - this one) */
+    uint32_t vmask;          /* bit j = value j exists */
+    bool idx_ok;             /* base <= next <= n_esc and count <= 512 */
+};
+
+/* The lane's zero-point bytes (up to 8, in element order) and where its mask says they go. */
+struct DecEsc {
+    uint32_t m;              /* bit j = value j is a zero-point */
+    uint32_t sh;             /* byte offset of the lane's first zero-point inside d0 */
+    uint32_t d0, d1, d2;     /* three aligned words covering the lane's 8 list bytes */
+    bool bad;                /* planes and IDX disagree about the group */
+};
+
+/* Phase 0: the group's slice of the zero-point list by IDX alone (scalar loads). */
+__device__ __forceinline__ void decode_index(const uint8_t* __restrict__ slot, const SlotLayout& L, uint64_t n,
+                                             uint32_t n_esc, uint64_t gstart, DecIn& r, uint32_t& next)
+{
+    const uint64_t g = gstart / kGroup, ng = (n + kGroup - 1) / kGroup;
+    const uint32_t* __restrict__ idx = reinterpret_cast<const uint32_t*>(slot + L.idx);
+    r.base = idx[g];
+    next = g + 1 < ng ? idx[g + 1] : n_esc;
+    r.idx_ok = r.base <= next && next <= n_esc && next - r.base <= kGroup;
+    r.count = r.idx_ok ? next - r.base : 0u;
+}
+
+/* Phase 1a: fetch the slice [base, base + count), 8 aligned bytes per lane (+ 8 more by lane 0 when a
+ * full group starts off alignment).  Aligned reads stay inside pad128(n_esc); lanes past the slice read
+ * the 8 bytes in front of the list instead (the end of the static part), so the load needs no predicate. */
+__device__ __forceinline__ void decode_fetch_list(const uint8_t* __restrict__ slot, const SlotLayout& L,
+                                                  const DecIn& r, uint32_t next, uint32_t lane, u32x2& v, u32x2& tail)
+{
+    const uint32_t end = r.count != 0u ? next : 0u;              /* nothing to fetch for an empty slice */
+    const uint32_t a8 = r.base & ~7u;
+    const uint32_t a = a8 + 8u * lane;
+    const uint8_t* __restrict__ esc = slot + L.esc;
+    v = *reinterpret_cast<const u32x2*>(esc + (a < end ? (int64_t)a : (int64_t)-8));
+    tail = u32x2{0u, 0u};
+    if (a8 + kGroup < end) {                                      /* wave-uniform and rare */
+        if (lane == 0) tail = *reinterpret_cast<const u32x2*>(esc + a8 + kGroup);
+    }
+}
+
+/* Phase 1b: the lane's SM bytes, plane bytes and (fp32) low words. */
+template <int DT, bool FAST>
+__device__ __forceinline__ void decode_load(const uint8_t* __restrict__ slot, const SlotLayout& L, uint64_t n,
+                                            uint64_t gstart, uint32_t lane, DecIn& r)
+{
+    /* gstart is wave-uniform: uniform 64-bit base + 32-bit lane offset */
+    const uint64_t e = gstart + lane * kLaneElems;
+    r.sm0 = r.sm1 = r.b0 = r.b1 = r.b2 = 0;
+    r.lo[0] = r.lo[1] = r.lo[2] = r.lo[3] = 0;
+    if (FAST || e < pad128(n)) {
+        const u32x2 v = ld_stream<u32x2>((slot + L.sm + gstart) + lane * 8u);
+        r.sm0 = v.x; r.sm1 = v.y;
+    }
+    const uint64_t pb = e >> 3;
+    if (FAST || pb < L.plane_bytes) {
+        const uint8_t* pl = slot + L.p0 + (gstart >> 3);
+        r.b0 = ld_stream<uint8_t>(pl + lane);
+        r.b1 = ld_stream<uint8_t>((pl + L.plane_bytes) + lane);
+        r.b2 = ld_stream<uint8_t>((pl + 2 * L.plane_bytes) + lane);
+    }
+    if (DT == ZIPCCL_FP32) {
+        if (FAST || 2 * e < pad128(2 * n)) {
+            const u32x4 v = ld_stream<u32x4>((slot + L.lo + 2 * gstart) + lane * 16u);
+            r.lo[0] = v.x; r.lo[1] = v.y; r.lo[2] = v.z; r.lo[3] = v.w;
+        }
+    }
+    r.vmask = 0xFFu;
+    if (!FAST) r.vmask = e >= n ? 0u : (n - e >= 8 ? 0xFFu : ((1u << (uint32_t)(n - e)) - 1u));
+}
+
+/* Phase 1c: park the slice in the wave's LDS region so that lanes can pick their bytes by position. */
+__device__ __forceinline__ void decode_park_list(uint8_t* lds, uint32_t lane, const u32x2& v, const u32x2& tail)
+{
+    *reinterpret_cast<u32x2*>(lds + 8u * lane) = v;
+    if (lane == 0) *reinterpret_cast<u32x2*>(lds + kGroup) = tail;
+}
+
+/* Phase 2: wave scan of the per-lane zero-point counts, then the lane's bytes from the LDS region.
+ * Straight-line code (no branch on whether the group has zero-points) so that the four groups a
+ * wave works on can be interleaved by the scheduler. */
+__device__ __forceinline__ DecEsc decode_locate(const DecIn& in, const uint8_t* lds)
+{
+    DecEsc r;
+    r.m = ~(in.b0 | in.b1 | in.b2) & in.vmask;     /* code 0 = zero-point; tail bits are not */
+    const uint32_t cnt = __popc(r.m);
+    const uint32_t inc = wave_incl_scan(cnt);
+    const uint32_t gtot = __builtin_amdgcn_readlane(inc, 63);
+    r.bad = !in.idx_ok || gtot != in.count;        /* planes and IDX must agree */
+    /* the lane's zero-point exponents are the bytes [p, p + cnt) of the region, p <= 7 + 512 - cnt
+       (clamped, so that a corrupt stream still reads inside the region) */
+    const uint32_t p = min((in.base & 7u) + (inc - cnt), kGroup + 7u);
+    const uint32_t* w = reinterpret_cast<const uint32_t*>(lds + (p & ~3u));
+    r.d0 = w[0]; r.d1 = w[1]; r.d2 = w[2];
+    r.sh = p & 3u;
+    return r;
+}
+
+/* Rebuild the high 16-bit words of the lane's 8 values (section 4, third paragraph), packed in pairs. */
+__device__ __forceinline__ void decode_values(const DecIn& in, const DecEsc& es, uint32_t e0,
+                                              const DecTables& tab, uint32_t hp[4])
+{
+    /* code bytes of values 0..3 and 4..7 (plane bits spread by table), then exponent = dec[1] - 1 + code */
+    const uint32_t k4 = (e0 - 1u) * 0x01010101u;
+    const uint2 t0 = tab.spread[in.b0], t1 = tab.spread[in.b1], t2 = tab.spread[in.b2];
+    uint32_t eA = (t0.x | (t1.x << 1) | (t2.x << 2)) + k4;
+    uint32_t eB = (t0.y | (t1.y << 1) | (t2.y << 2)) + k4;
+    const uint2* __restrict__ lut = tab.expand;
+    {   /* zero-point exponents dropped in place; a lane without zero-points selects nothing */
+        const uint32_t l8 = __builtin_amdgcn_alignbyte(es.d1, es.d0, es.sh);
+        const uint32_t h8 = __builtin_amdgcn_alignbyte(es.d2, es.d1, es.sh);
+        const uint32_t mA = es.m & 15u, mB = es.m >> 4;
+        const uint32_t nA = __popc(mA);
+        const uint2 tA = lut[mA], tB = lut[mB];
+        const uint32_t xB = nA == 4u ? h8 : __builtin_amdgcn_alignbyte(h8, l8, nA);
+        eA = bfi(tA.y, perm(0u, l8, tA.x), eA);
+        eB = bfi(tB.y, perm(0u, xB, tB.x), eB);
+    }
+    /* recombine with sign and mantissa: low byte = mantissa | E bit 0 << 7, high = sign | E >> 1 */
+    const uint32_t lA = bfi(0x7F7F7F7Fu, in.sm0, eA << 7), hA = bfi(0x80808080u, in.sm0, eA >> 1);
+    const uint32_t lB = bfi(0x7F7F7F7Fu, in.sm1, eB << 7), hB = bfi(0x80808080u, in.sm1, eB >> 1);
+    hp[0] = perm(hA, lA, 0x05010400u);
+    hp[1] = perm(hA, lA, 0x07030602u);
+    hp[2] = perm(hB, lB, 0x05010400u);
+    hp[3] = perm(hB, lB, 0x07030602u);
+}
+
+/* Rebuild the 8 values and store them. */
+template <int DT, bool FAST>
+__device__ __forceinline__ void decode_store(uint8_t* __restrict__ cout, const DecIn& in, const DecEsc& es,
+                                             uint64_t gstart, uint32_t e0, uint32_t lane, const DecTables& tab)
+{
+    const uint64_t e = gstart + lane * kLaneElems;
+    uint32_t hp[4];
+    decode_values(in, es, e0, tab, hp);
+    if (FAST) {
+        if (DT == ZIPCCL_BF16) {
+            st_stream<u32x4>((cout + gstart * 2) + lane * 16u, u32x4{hp[0], hp[1], hp[2], hp[3]});
+        } else {
+            uint32_t x[8];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                x[2 * k] = perm(hp[k], in.lo[k], 0x05040100u);
+                x[2 * k + 1] = perm(hp[k], in.lo[k], 0x07060302u);
+            }
+            st_stream<u32x4>((cout + gstart * 4) + lane * 32u, u32x4{x[0], x[1], x[2], x[3]});
+            st_stream<u32x4>((cout + gstart * 4 + 16) + lane * 32u, u32x4{x[4], x[5], x[6], x[7]});
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            if ((in.vmask >> j) & 1u) {
+                const uint32_t h = (hp[j >> 1] >> (16 * (j & 1))) & 0xFFFFu;
+                if (DT == ZIPCCL_BF16) {
+                    *reinterpret_cast<uint16_t*>(cout + (e + j) * 2) = (uint16_t)h;
+                } else {
+                    const uint32_t l = (in.lo[j >> 1] >> (16 * (j & 1))) & 0xFFFFu;
+                    *reinterpret_cast<uint32_t*>(cout + (e + j) * 4) = (h << 16) | l;
+                }
+            }
+        }
+    }
+}
+
+/*
+ * Chunk header check (all wave-uniform): the static part is readable (the host checked it), magic,
+ * version, dtype, G and n must match the call, the table must be a window, and the zero-point
+ * list the header promises must fit into the readable bytes.
+ */
+template <int DT>
+__device__ __forceinline__ bool check_header(const uint8_t* __restrict__ slot, const SlotLayout& L, uint64_t n,
+                                             uint64_t slot_off, uint64_t comp_capacity, uint32_t& e0, uint32_t& n_esc)
+{
+    const uint32_t* hw = reinterpret_cast<const uint32_t*>(slot);
+    const uint64_t n_hdr = (uint64_t)hw[4] | ((uint64_t)hw[5] << 32);
+    const uint64_t ne = (uint64_t)hw[6] | ((uint64_t)hw[7] << 32);
+    const uint64_t cbytes = (uint64_t)hw[8] | ((uint64_t)hw[9] << 32);
+    const uint32_t dec_lo = hw[10], dec_hi = hw[11];
+    e0 = (dec_lo >> 8) & 0xFFu;
+    n_esc = (uint32_t)ne;
+    bool ok = hw[0] == kMagic && hw[1] == kVersion && hw[2] == (uint32_t)DT && hw[3] == kGroup;
+    ok = ok && n_hdr == n && ne <= n && cbytes == L.esc + pad128(ne);
+    ok = ok && slot_off + cbytes <= comp_capacity;
+    ok = ok && e0 >= 1u && e0 <= 249u && (dec_lo >> 8) == (e0 | ((e0 + 1u) << 8) | ((e0 + 2u) << 16)) &&
+         dec_hi == ((e0 + 3u) | ((e0 + 4u) << 8) | ((e0 + 5u) << 16) | ((e0 + 6u) << 24));
+    return ok;
+}
+
+template <int DT>
+__global__ __launch_bounds__(kThreads, DT == ZIPCCL_BF16 ? 8 : 6)   /* waves per SIMD: <= 64 VGPRs for bf16, <= 80 for fp32 */
+void k_decompress(const DecompressArgs a)
+{
+    constexpr uint32_t ES = DT == ZIPCCL_BF16 ? 2u : 4u;
+    __shared__ DecTables s_tab;
+    __shared__ __attribute__((aligned(16))) uint8_t s_esc[kWavesPerBlock][kGroupsPerWave][kEscRegion];
+    build_tables(s_tab);
+
+    /* grid = (tiles of the largest chunk, chunks) */
+    const uint32_t c = blockIdx.y;
+    if (blockIdx.x >= a.tab.tile_start[c + 1] - a.tab.tile_start[c]) return;
+    const uint64_t n = a.tab.elem_off[c + 1] - a.tab.elem_off[c];
+    const uint64_t ts = (uint64_t)blockIdx.x * kTile;
+    const uint8_t* __restrict__ slot = a.comp + a.tab.slot_off[c];
+    uint8_t* __restrict__ cout = a.out + a.tab.elem_off[c] * ES;
+    const SlotLayout L = slot_layout(n, DT);
+
+    uint32_t e0, n_esc;
+    const bool ok = check_header<DT>(slot, L, n, a.tab.slot_off[c], a.comp_capacity, e0, n_esc);
+    __syncthreads();
+    if (!ok) {
+        if (threadIdx.x == 0 && a.status) atomicOr(a.status, (uint32_t)ZIPCCL_ERR_CORRUPT);
+        return;
+    }
+
+    const bool fast = (ts + kTile <= n) && ((reinterpret_cast<uintptr_t>(cout) & 15u) == 0);
+    const uint32_t lane = lane_id();
+    const uint32_t wave = threadIdx.x >> 6;   /* left in a vector register: measured faster here than scalar addressing */
+    bool bad = false;
+    if (fast) {
+        /* phases over the wave's four groups, so that each phase's loads are all in flight together
+           and no vector load depends on another vector load */
+        DecIn in[kGroupsPerWave];
+        DecEsc es[kGroupsPerWave];
+        uint32_t next[kGroupsPerWave];
+        u32x2 lv[kGroupsPerWave], lt[kGroupsPerWave];
+#pragma unroll
+        for (uint32_t u = 0; u < kGroupsPerWave; ++u)
+            decode_index(slot, L, n, n_esc, ts + (uint64_t)(u * kWavesPerBlock + wave) * kGroup, in[u], next[u]);
+#pragma unroll
+        for (uint32_t u = 0; u < kGroupsPerWave; ++u) decode_fetch_list(slot, L, in[u], next[u], lane, lv[u], lt[u]);
+#pragma unroll
+        for (uint32_t u = 0; u < kGroupsPerWave; ++u)
+            decode_load<DT, true>(slot, L, n, ts + (uint64_t)(u * kWavesPerBlock + wave) * kGroup, lane, in[u]);
+#pragma unroll
+        for (uint32_t u = 0; u < kGroupsPerWave; ++u) decode_park_list(s_esc[wave][u], lane, lv[u], lt[u]);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+        for (uint32_t u = 0; u < kGroupsPerWave; ++u) es[u] = decode_locate(in[u], s_esc[wave][u]);
+#pragma unroll
+        for (uint32_t u = 0; u < kGroupsPerWave; ++u) {
+            decode_store<DT, true>(cout, in[u], es[u], ts + (uint64_t)(u * kWavesPerBlock + wave) * kGroup, e0, lane, s_tab);
+            bad |= es[u].bad;
+        }
+    } else {
+        for (uint32_t u = 0; u < kGroupsPerWave; ++u) {
+            const uint64_t gstart = ts + (uint64_t)(u * kWavesPerBlock + wave) * kGroup;
+            if (gstart < n) {
+                DecIn in;
+                uint32_t next;
+                u32x2 lv, lt;
+                decode_index(slot, L, n, n_esc, gstart, in, next);
+                decode_fetch_list(slot, L, in, next, lane, lv, lt);
+                decode_load<DT, false>(slot, L, n, gstart, lane, in);
+                decode_park_list(s_esc[wave][u], lane, lv, lt);
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                const DecEsc es = decode_locate(in, s_esc[wave][u]);
+                decode_store<DT, false>(cout, in, es, gstart, e0, lane, s_tab);
+                bad |= es.bad;
+            }
+        }
+    }
+    if (bad && a.status) atomicOr(a.status, (uint32_t)ZIPCCL_ERR_CORRUPT);
+}
+
+/* fp32 bits -> bf16 bits, round to nearest even; NaN keeps sign and top payload bits and is made quiet */
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
+{
+    const uint32_t u = __float_as_uint(f);
+    const bool nan = (u & 0x7F800000u) == 0x7F800000u && (u & 0x007FFFFFu) != 0u;
+    return nan ? ((u >> 16) | 0x0040u) : ((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+}
+
+/*
+ * Local reduction of the zipped Reduce-Scatter (paper sections 3.3 and 5.2): decode the slices
+ * received from n_peers peers (slots back to back, n values each) and sum them in FP32, peers in
+ * slot order starting from peer 0's value.  One pass: every compressed byte is read once and
+ * only the sum is written.  Work decomposition as in k_decompress; the peer loop is innermost.
+ */
+/* GPW = groups per wave: 4 for large shards, 1 for small ones (four times as many workgroups, each with a
+ * quarter of the sequential peer loop). */
+template <int DT, int ODT, uint32_t GPW>
+__global__ __launch_bounds__(kThreads) void k_decompress_reduce(const ReduceArgs a)
+{
+    constexpr uint32_t kRTile = kGroup * kWavesPerBlock * GPW;
+    constexpr uint32_t OES = ODT == ZIPCCL_BF16 ? 2u : 4u;
+    __shared__ DecTables s_tab;
+    __shared__ __attribute__((aligned(16))) uint8_t s_esc[kWavesPerBlock][kEscRegion];
+    __shared__ uint32_t s_e0[kMaxPeers];      /* dec[1] of peer p's slot, 0 = header rejected */
+    __shared__ uint32_t s_nesc[kMaxPeers];    /* zero-points of peer p's slot */
+    build_tables(s_tab);
+
+    const uint64_t n = a.n;
+    const uint64_t ts = (uint64_t)blockIdx.x * kRTile;
+    const SlotLayout L = slot_layout(n, DT);
+    bool bad = false;
+    /* every slot's header is checked once per workgroup, one peer per thread */
+    for (uint32_t p = threadIdx.x; p < a.n_peers; p += kThreads) {
+        const uint64_t slot_off = (uint64_t)p * a.slot_cap;
+        uint32_t e0, n_esc;
+        const bool ok = check_header<DT>(a.comp + slot_off, L, n, slot_off, a.comp_capacity, e0, n_esc);
+        s_e0[p] = ok ? e0 : 0u;
+        s_nesc[p] = n_esc;
+        bad |= !ok;
+    }
+    __syncthreads();
+
+    const bool fast = (ts + kRTile <= n) && ((reinterpret_cast<uintptr_t>(a.out) & 15u) == 0);
+    const uint32_t lane = lane_id();
+    const uint32_t wave = threadIdx.x >> 6;
+    const uint64_t ng = (n + kGroup - 1) / kGroup;
+    for (uint32_t u = 0; u < GPW; ++u) {
+        const uint64_t gstart = ts + (uint64_t)(u * kWavesPerBlock + wave) * kGroup;
+        if (gstart >= n) continue;
+        const uint64_t g = gstart / kGroup;
+        float acc[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] = 0.0f;
+        bool have = false;
+        const uint64_t e = gstart + lane * kLaneElems;
+        const uint32_t vmask = fast ? 0xFFu : (e >= n ? 0u : (n - e >= 8 ? 0xFFu : ((1u << (uint32_t)(n - e)) - 1u)));
+        /* the IDX entries of the next peer are fetched one iteration ahead (scalar loads) */
+        const uint32_t* idx0 = reinterpret_cast<const uint32_t*>(a.comp + L.idx);
+        uint32_t nb = idx0[g], nn = g + 1 < ng ? idx0[g + 1] : 0u;
+        for (uint32_t p = 0; p < a.n_peers; ++p) {
+            const uint8_t* __restrict__ slot = a.comp + (uint64_t)p * a.slot_cap;
+            const uint32_t e0 = s_e0[p], n_esc = s_nesc[p];
+            const uint32_t base = nb, next = g + 1 < ng ? nn : n_esc;
+            if (p + 1 < a.n_peers) {
+                const uint32_t* idxn = reinterpret_cast<const uint32_t*>(slot + a.slot_cap + L.idx);
+                nb = idxn[g];
+                if (g + 1 < ng) nn = idxn[g + 1];
+            }
+            if (e0 == 0u) continue;                      /* rejected slot: left out of the sum */
+            DecIn in;
+            u32x2 lv, lt;
+            in.base = base;
+            in.idx_ok = base <= next && next <= n_esc && next - base <= kGroup;
+            in.count = in.idx_ok ? next - base : 0u;
+            decode_fetch_list(slot, L, in, next, lane, lv, lt);
+            if (fast) decode_load<DT, true>(slot, L, n, gstart, lane, in);
+            else decode_load<DT, false>(slot, L, n, gstart, lane, in);
+            decode_park_list(s_esc[wave], lane, lv, lt);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            const DecEsc es = decode_locate(in, s_esc[wave]);
+            __builtin_amdgcn_wave_barrier();
+            bad |= es.bad;
+            uint32_t hp[4];
+            decode_values(in, es, e0, s_tab, hp);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                uint32_t w0, w1;
+                if (DT == ZIPCCL_BF16) { w0 = hp[k] << 16; w1 = hp[k] & 0xFFFF0000u; }
+                else { w0 = perm(hp[k], in.lo[k], 0x05040100u); w1 = perm(hp[k], in.lo[k], 0x07060302u); }
+                const float x0 = __uint_as_float(w0), x1 = __uint_as_float(w1);
+                acc[2 * k] = have ? acc[2 * k] + x0 : x0;
+                acc[2 * k + 1] = have ? acc[2 * k + 1] + x1 : x1;
+            }
+            have = true;
+        }
+        uint8_t* __restrict__ og = a.out + gstart * OES;
+        if (fast) {
+            if (ODT == ZIPCCL_FP32) {
+                st_stream<u32x4>(og + lane * 32u, u32x4{__float_as_uint(acc[0]), __float_as_uint(acc[1]),
+                                                        __float_as_uint(acc[2]), __float_as_uint(acc[3])});
+                st_stream<u32x4>((og + 16) + lane * 32u, u32x4{__float_as_uint(acc[4]), __float_as_uint(acc[5]),
+                                                               __float_as_uint(acc[6]), __float_as_uint(acc[7])});
+            } else {
+                uint32_t o[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) o[k] = f32_to_bf16_bits(acc[2 * k]) | (f32_to_bf16_bits(acc[2 * k + 1]) << 16);
+                st_stream<u32x4>(og + lane * 16u, u32x4{o[0], o[1], o[2], o[3]});
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                if ((vmask >> j) & 1u) {
+                    const uint64_t i = lane * kLaneElems + j;
+                    if (ODT == ZIPCCL_FP32) *reinterpret_cast<float*>(og + i * 4) = acc[j];
+                    else *reinterpret_cast<uint16_t*>(og + i * 2) = (uint16_t)f32_to_bf16_bits(acc[j]);
+                }
+            }
+        }
+    }
+    if (bad && a.status) atomicOr(a.status, (uint32_t)ZIPCCL_ERR_CORRUPT);
+}
+
+} // namespace
+
+int launch_decompress(int dt, const DecompressArgs& a, void* stream)
+{
+    const dim3 grid(max_chunk_tiles(a.tab), a.tab.n_chunks), block(kThreads);
+    if (dt == ZIPCCL_BF16)
+        hipLaunchKernelGGL((k_decompress<ZIPCCL_BF16>), grid, block, 0, (hipStream_t)stream, a);
+    else
+        hipLaunchKernelGGL((k_decompress<ZIPCCL_FP32>), grid, block, 0, (hipStream_t)stream, a);
+    return (int)hipGetLastError();
+}
+
+
+int launch_decompress_reduce(int dt, int out_dt, const ReduceArgs& a, void* stream)
+{
+    hipStream_t s = (hipStream_t)stream;
+    const dim3 block(kThreads);
+    /* at least ~8 workgroups per CU before a workgroup takes four groups per wave */
+    const bool big = a.n >= (uint64_t)kTile * 2048u;
+    const uint64_t per = big ? kTile : kTile / kGroupsPerWave;
+    const dim3 grid((uint32_t)(a.n == 0 ? 1 : (a.n + per - 1) / per));
+#define ZIPCCL_REDUCE(DT, ODT)                                                                          \
+    do {                                                                                                \
+        if (big) hipLaunchKernelGGL((k_decompress_reduce<DT, ODT, kGroupsPerWave>), grid, block, 0, s, a); \
+        else hipLaunchKernelGGL((k_decompress_reduce<DT, ODT, 1u>), grid, block, 0, s, a);              \
+    } while (0)
+    if (dt == ZIPCCL_BF16 && out_dt == ZIPCCL_FP32) ZIPCCL_REDUCE(ZIPCCL_BF16, ZIPCCL_FP32);
+    else if (dt == ZIPCCL_BF16) ZIPCCL_REDUCE(ZIPCCL_BF16, ZIPCCL_BF16);
+    else if (out_dt == ZIPCCL_FP32) ZIPCCL_REDUCE(ZIPCCL_FP32, ZIPCCL_FP32);
+    else ZIPCCL_REDUCE(ZIPCCL_FP32, ZIPCCL_BF16);
+#undef ZIPCCL_REDUCE
+    return (int)hipGetLastError();
+}
+
+
+} // namespace zipccl

@@ -109,7 +109,8 @@ struct ReduceArgs {
 
 enum CompressMode { kModeCount = 0, kModeEmit = 1, kModeStash = 2 };
 
-/* launchers implemented in zipccl_kernels.hip; return a hipError_t as int */
+/* launchers implemented next to their kernels (zipccl_compress.hip, zipccl_decompress.hip, zipccl_aux.hip);
+ * they return a hipError_t as int */
 int launch_copy(void* d_dst, const void* d_src, uint64_t bytes, void* stream);
 int launch_estimate(int dt, const MomentArgs& a, void* stream);
 int launch_compress(int dt, int mode, const CompressArgs& a, void* stream);
