@@ -201,8 +201,9 @@ __device__ __forceinline__ void decode_store(uint8_t* __restrict__ cout, const D
                 x[2 * k] = perm(hp[k], in.lo[k], 0x05040100u);
                 x[2 * k + 1] = perm(hp[k], in.lo[k], 0x07060302u);
             }
-            st_stream<u32x4>((cout + gstart * 4) + lane * 32u, u32x4{x[0], x[1], x[2], x[3]});
-            st_stream<u32x4>((cout + gstart * 4 + 16) + lane * 32u, u32x4{x[4], x[5], x[6], x[7]});
+            /* 32 contiguous bytes per lane: plain stores (streaming ones are slow on this pattern) */
+            *reinterpret_cast<u32x4*>((cout + gstart * 4) + lane * 32u) = u32x4{x[0], x[1], x[2], x[3]};
+            *reinterpret_cast<u32x4*>((cout + gstart * 4 + 16) + lane * 32u) = u32x4{x[4], x[5], x[6], x[7]};
         }
     } else {
 #pragma unroll
@@ -424,10 +425,11 @@ __global__ __launch_bounds__(kThreads) void k_decompress_reduce(const ReduceArgs
         uint8_t* __restrict__ og = a.out + gstart * OES;
         if (fast) {
             if (ODT == ZIPCCL_FP32) {
-                st_stream<u32x4>(og + lane * 32u, u32x4{__float_as_uint(acc[0]), __float_as_uint(acc[1]),
-                                                        __float_as_uint(acc[2]), __float_as_uint(acc[3])});
-                st_stream<u32x4>((og + 16) + lane * 32u, u32x4{__float_as_uint(acc[4]), __float_as_uint(acc[5]),
-                                                               __float_as_uint(acc[6]), __float_as_uint(acc[7])});
+                /* 32 contiguous bytes per lane: plain stores (streaming ones are slow on this pattern) */
+                *reinterpret_cast<u32x4*>(og + lane * 32u) = u32x4{__float_as_uint(acc[0]), __float_as_uint(acc[1]),
+                                                                   __float_as_uint(acc[2]), __float_as_uint(acc[3])};
+                *reinterpret_cast<u32x4*>((og + 16) + lane * 32u) = u32x4{__float_as_uint(acc[4]), __float_as_uint(acc[5]),
+                                                                          __float_as_uint(acc[6]), __float_as_uint(acc[7])};
             } else {
                 uint32_t o[4];
 #pragma unroll
