@@ -7,6 +7,7 @@
  * locate each lane's zero-point exponents.
  */
 #include "zipccl_device.h"
+#include <type_traits>
 
 namespace zipccl {
 namespace {
@@ -45,9 +46,10 @@ __device__ __forceinline__ void build_tables(DecTables& t)
     if (threadIdx.x < 16) t.expand[threadIdx.x] = expand_entry(threadIdx.x);
 }
 
-/* Bytes of LDS per group for its zero-point exponents: 512 + up to 7 of misalignment, rounded up,
- * + 8 so that a lane's three aligned words never leave the region. */
+/* Bytes of LDS per group for its zero-point exponents: 512 + up to 15 of misalignment, rounded up to
+ * whole 16-byte words (33 of them) + 16 so that a lane's three aligned words never leave the region. */
 constexpr uint32_t kEscRegion = 544;
+constexpr uint32_t kListLanes = 33;     /* lanes that fetch 16 bytes of the list each */
 
 /* What a lane reads for its 8 values of one group. */
 struct DecIn {
@@ -80,21 +82,17 @@ __device__ __forceinline__ void decode_index(const uint8_t* __restrict__ slot, c
     r.count = r.idx_ok ? next - r.base : 0u;
 }
 
-/* Phase 1a: fetch the slice [base, base + count), 8 aligned bytes per lane (+ 8 more by lane 0 when a
- * full group starts off alignment).  Aligned reads stay inside pad128(n_esc); lanes past the slice read
- * the 8 bytes in front of the list instead (the end of the static part), so the load needs no predicate. */
+/* Phase 1a: fetch the slice [base, base + count): 16 aligned bytes per lane by the first 33 lanes, which
+ * covers 512 bytes at any alignment.  Aligned reads stay inside pad128(n_esc); lanes past the slice read
+ * the 16 bytes in front of the list instead (the end of the static part), so the load needs no predicate
+ * and every group issues the same number of loads. */
 __device__ __forceinline__ void decode_fetch_list(const uint8_t* __restrict__ slot, const SlotLayout& L,
-                                                  const DecIn& r, uint32_t next, uint32_t lane, u32x2& v, u32x2& tail)
+                                                  const DecIn& r, uint32_t next, uint32_t lane, u32x4& v)
 {
     const uint32_t end = r.count != 0u ? next : 0u;              /* nothing to fetch for an empty slice */
-    const uint32_t a8 = r.base & ~7u;
-    const uint32_t a = a8 + 8u * lane;
+    const uint32_t a = (r.base & ~15u) + 16u * lane;
     const uint8_t* __restrict__ esc = slot + L.esc;
-    v = *reinterpret_cast<const u32x2*>(esc + (a < end ? (int64_t)a : (int64_t)-8));
-    tail = u32x2{0u, 0u};
-    if (a8 + kGroup < end) {                                      /* wave-uniform and rare */
-        if (lane == 0) tail = *reinterpret_cast<const u32x2*>(esc + a8 + kGroup);
-    }
+    v = *reinterpret_cast<const u32x4*>(esc + (a < end ? (int64_t)a : (int64_t)-16));
 }
 
 /* Phase 1b: the lane's SM bytes, plane bytes and (fp32) low words. */
@@ -128,10 +126,9 @@ __device__ __forceinline__ void decode_load(const uint8_t* __restrict__ slot, co
 }
 
 /* Phase 1c: park the slice in the wave's LDS region so that lanes can pick their bytes by position. */
-__device__ __forceinline__ void decode_park_list(uint8_t* lds, uint32_t lane, const u32x2& v, const u32x2& tail)
+__device__ __forceinline__ void decode_park_list(uint8_t* lds, uint32_t lane, const u32x4& v)
 {
-    *reinterpret_cast<u32x2*>(lds + 8u * lane) = v;
-    if (lane == 0) *reinterpret_cast<u32x2*>(lds + kGroup) = tail;
+    if (lane < kListLanes) *reinterpret_cast<u32x4*>(lds + 16u * lane) = v;
 }
 
 /* Phase 2: wave scan of the per-lane zero-point counts, then the lane's bytes from the LDS region.
@@ -145,18 +142,19 @@ __device__ __forceinline__ DecEsc decode_locate(const DecIn& in, const uint8_t* 
     const uint32_t inc = wave_incl_scan(cnt);
     const uint32_t gtot = __builtin_amdgcn_readlane(inc, 63);
     r.bad = !in.idx_ok || gtot != in.count;        /* planes and IDX must agree */
-    /* the lane's zero-point exponents are the bytes [p, p + cnt) of the region, p <= 7 + 512 - cnt
+    /* the lane's zero-point exponents are the bytes [p, p + cnt) of the region, p <= 15 + 512 - cnt
        (clamped, so that a corrupt stream still reads inside the region) */
-    const uint32_t p = min((in.base & 7u) + (inc - cnt), kGroup + 7u);
+    const uint32_t p = min((in.base & 15u) + (inc - cnt), kGroup + 15u);
     const uint32_t* w = reinterpret_cast<const uint32_t*>(lds + (p & ~3u));
     r.d0 = w[0]; r.d1 = w[1]; r.d2 = w[2];
     r.sh = p & 3u;
     return r;
 }
 
-/* Rebuild the high 16-bit words of the lane's 8 values (section 4, third paragraph), packed in pairs. */
-__device__ __forceinline__ void decode_values(const DecIn& in, const DecEsc& es, uint32_t e0,
-                                              const DecTables& tab, uint32_t hp[4])
+/* Rebuild the bytes of the high 16-bit words of the lane's 8 values (section 4, third paragraph):
+ * lA / hA = low / high bytes of values 0..3, lB / hB of values 4..7. */
+__device__ __forceinline__ void decode_bytes(const DecIn& in, const DecEsc& es, uint32_t e0, const DecTables& tab,
+                                             uint32_t& lA, uint32_t& hA, uint32_t& lB, uint32_t& hB)
 {
     /* code bytes of values 0..3 and 4..7 (plane bits spread by table), then exponent = dec[1] - 1 + code */
     const uint32_t k4 = (e0 - 1u) * 0x01010101u;
@@ -175,8 +173,16 @@ __device__ __forceinline__ void decode_values(const DecIn& in, const DecEsc& es,
         eB = bfi(tB.y, perm(0u, xB, tB.x), eB);
     }
     /* recombine with sign and mantissa: low byte = mantissa | E bit 0 << 7, high = sign | E >> 1 */
-    const uint32_t lA = bfi(0x7F7F7F7Fu, in.sm0, eA << 7), hA = bfi(0x80808080u, in.sm0, eA >> 1);
-    const uint32_t lB = bfi(0x7F7F7F7Fu, in.sm1, eB << 7), hB = bfi(0x80808080u, in.sm1, eB >> 1);
+    lA = bfi(0x7F7F7F7Fu, in.sm0, eA << 7); hA = bfi(0x80808080u, in.sm0, eA >> 1);
+    lB = bfi(0x7F7F7F7Fu, in.sm1, eB << 7); hB = bfi(0x80808080u, in.sm1, eB >> 1);
+}
+
+/* The same as four words holding the 8 high 16-bit words in element order. */
+__device__ __forceinline__ void decode_values(const DecIn& in, const DecEsc& es, uint32_t e0,
+                                              const DecTables& tab, uint32_t hp[4])
+{
+    uint32_t lA, hA, lB, hB;
+    decode_bytes(in, es, e0, tab, lA, hA, lB, hB);
     hp[0] = perm(hA, lA, 0x05010400u);
     hp[1] = perm(hA, lA, 0x07030602u);
     hp[2] = perm(hB, lB, 0x05010400u);
@@ -281,17 +287,17 @@ void k_decompress(const DecompressArgs a)
         DecIn in[kGroupsPerWave];
         DecEsc es[kGroupsPerWave];
         uint32_t next[kGroupsPerWave];
-        u32x2 lv[kGroupsPerWave], lt[kGroupsPerWave];
+        u32x4 lv[kGroupsPerWave];
 #pragma unroll
         for (uint32_t u = 0; u < kGroupsPerWave; ++u)
             decode_index(slot, L, n, n_esc, ts + (uint64_t)(u * kWavesPerBlock + wave) * kGroup, in[u], next[u]);
 #pragma unroll
-        for (uint32_t u = 0; u < kGroupsPerWave; ++u) decode_fetch_list(slot, L, in[u], next[u], lane, lv[u], lt[u]);
+        for (uint32_t u = 0; u < kGroupsPerWave; ++u) decode_fetch_list(slot, L, in[u], next[u], lane, lv[u]);
 #pragma unroll
         for (uint32_t u = 0; u < kGroupsPerWave; ++u)
             decode_load<DT, true>(slot, L, n, ts + (uint64_t)(u * kWavesPerBlock + wave) * kGroup, lane, in[u]);
 #pragma unroll
-        for (uint32_t u = 0; u < kGroupsPerWave; ++u) decode_park_list(s_esc[wave][u], lane, lv[u], lt[u]);
+        for (uint32_t u = 0; u < kGroupsPerWave; ++u) decode_park_list(s_esc[wave][u], lane, lv[u]);
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -308,11 +314,11 @@ void k_decompress(const DecompressArgs a)
             if (gstart < n) {
                 DecIn in;
                 uint32_t next;
-                u32x2 lv, lt;
+                u32x4 lv;
                 decode_index(slot, L, n, n_esc, gstart, in, next);
-                decode_fetch_list(slot, L, in, next, lane, lv, lt);
+                decode_fetch_list(slot, L, in, next, lane, lv);
                 decode_load<DT, false>(slot, L, n, gstart, lane, in);
-                decode_park_list(s_esc[wave][u], lane, lv, lt);
+                decode_park_list(s_esc[wave][u], lane, lv);
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                 __builtin_amdgcn_wave_barrier();
                 __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -333,19 +339,155 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
     return nan ? ((u >> 16) | 0x0040u) : ((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
 }
 
+/* What is in flight for one peer's copy of a group: the loads of decode_load and decode_fetch_list,
+ * and the index entries fetched ahead for the peer that uses this buffer next. */
+struct PeerLoads {
+    DecIn in;
+    u32x4 lv;
+    uint32_t next;
+    uint32_t pre_base, pre_next;
+};
+
 /*
  * Local reduction of the zipped Reduce-Scatter (paper sections 3.3 and 5.2): decode the slices
  * received from n_peers peers (slots back to back, n values each) and sum them in FP32, peers in
- * slot order starting from peer 0's value.  One pass: every compressed byte is read once and
- * only the sum is written.  Work decomposition as in k_decompress; the peer loop is innermost.
+ * slot order starting from the first peer's value.  One pass: every compressed byte is read once and
+ * only the sum is written.  A wave owns a group; the peer loop is innermost and software-pipelined:
+ * the loads of peer p + 1 (and, ahead of them, the index entries of peer p + 2) are issued before
+ * peer p is decoded, so that a wave always has a full group of loads in flight.
  */
-/* GPW = groups per wave: 4 for large shards, 1 for small ones (four times as many workgroups, each with a
- * quarter of the sequential peer loop). */
-template <int DT, int ODT, uint32_t GPW>
-__global__ __launch_bounds__(kThreads) void k_decompress_reduce(const ReduceArgs a)
+template <int DT, int ODT, bool FAST>
+__device__ __forceinline__ void reduce_group(const ReduceArgs& a, const SlotLayout& L, uint64_t gstart, uint32_t lane,
+                                             uint8_t* lds, const DecTables& tab, const uint32_t* s_e0,
+                                             const uint32_t* s_nesc, bool& bad)
 {
-    constexpr uint32_t kRTile = kGroup * kWavesPerBlock * GPW;
     constexpr uint32_t OES = ODT == ZIPCCL_BF16 ? 2u : 4u;
+    const uint64_t n = a.n;
+    const uint64_t g = gstart / kGroup, ng = (n + kGroup - 1) / kGroup;
+    const bool last_group = g + 1 >= ng;
+    const uint32_t P = a.n_peers;
+    float acc[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = 0.0f;
+
+    /* group g's index entries in peer p's slot, fetched two peers ahead of their use (wave-uniform) */
+    auto load_idx = [&](uint32_t p, PeerLoads& r) {
+        const uint32_t* __restrict__ idx = reinterpret_cast<const uint32_t*>(a.comp + (uint64_t)p * a.slot_cap + L.idx);
+        r.pre_base = idx[g];
+        r.pre_next = idx[last_group ? g : g + 1];      /* always two loads: every stage issues the same number */
+    };
+    /* issue every vector load peer p's copy of the group needs; a rejected slot fetches no list.  With
+       live == false (past the last peer) the same loads go to the first bytes of the buffer instead and
+       their result is never used: the loop body then has one shape, and a wait for the older loads
+       never has to drain the younger ones. */
+    auto issue = [&](uint32_t p, bool live, PeerLoads& r) {
+        const uint8_t* __restrict__ slot = a.comp + (live ? (uint64_t)p * a.slot_cap : 0u);
+        const uint32_t e0 = live ? __builtin_amdgcn_readfirstlane(s_e0[p]) : 0u;
+        const uint32_t n_esc = __builtin_amdgcn_readfirstlane(s_nesc[p]);
+        const uint32_t base = __builtin_amdgcn_readfirstlane(r.pre_base);
+        r.next = last_group ? n_esc : __builtin_amdgcn_readfirstlane(r.pre_next);
+        r.in.base = base;
+        r.in.idx_ok = e0 != 0u && base <= r.next && r.next <= n_esc && r.next - base <= kGroup;
+        r.in.count = r.in.idx_ok ? r.next - base : 0u;
+        decode_fetch_list(slot, L, r.in, r.next, lane, r.lv);
+        decode_load<DT, FAST>(slot, L, n, live ? gstart : 0u, lane, r.in);
+    };
+    /* decode peer p's copy and add it (FIRST: it starts the sum) */
+    auto consume = [&](uint32_t p, const PeerLoads& r, auto first_tag) {
+        constexpr bool kFirst = decltype(first_tag)::value;
+        const uint32_t e0 = __builtin_amdgcn_readfirstlane(s_e0[p]);
+        decode_park_list(lds, lane, r.lv);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const DecEsc es = decode_locate(r.in, lds);
+        __builtin_amdgcn_wave_barrier();
+        bad |= es.bad;
+        float x[8];
+        if (DT == ZIPCCL_BF16) {
+            uint32_t lA, hA, lB, hB;
+            decode_bytes(r.in, es, e0, tab, lA, hA, lB, hB);
+#pragma unroll
+            for (uint32_t j = 0; j < 4; ++j) {    /* value j as FP32 bits: high byte, low byte, 16 zero bits */
+                const uint32_t sel = ((4u + j) << 24) | (j << 16) | 0x0C0Cu;
+                x[j] = __uint_as_float(perm(hA, lA, sel));
+                x[4 + j] = __uint_as_float(perm(hB, lB, sel));
+            }
+        } else {
+            uint32_t hp[4];
+            decode_values(r.in, es, e0, tab, hp);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                x[2 * k] = __uint_as_float(perm(hp[k], r.in.lo[k], 0x05040100u));
+                x[2 * k + 1] = __uint_as_float(perm(hp[k], r.in.lo[k], 0x07060302u));
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] = kFirst ? x[j] : acc[j] + x[j];
+    };
+
+    /* rejected slots are left out of the sum: start at the first accepted one */
+    uint32_t p = 0;
+    while (p < P && s_e0[p] == 0u) ++p;
+    if (p < P) {
+        /* two load buffers used in turn (a copy from one to the other would have to wait for the loads) */
+        PeerLoads bufA, bufB;
+        bufA.pre_base = bufA.pre_next = bufB.pre_base = bufB.pre_next = 0;
+        /* decode peer p from c while x fills with peer p + 1; c's next user is peer p + 2, whose index
+           entries are requested first, so that they have arrived when that peer's loads are issued */
+        auto stage = [&](PeerLoads& c, PeerLoads& x, auto first_tag) {
+            load_idx(min(p + 2, P - 1u), c);
+            const bool live = p + 1 < P;
+            issue(live ? p + 1 : p, live, x);
+            if (decltype(first_tag)::value || s_e0[p] != 0u) consume(p, c, first_tag);
+            ++p;
+        };
+        load_idx(p, bufA);
+        load_idx(min(p + 1, P - 1u), bufB);
+        issue(p, true, bufA);
+        stage(bufA, bufB, std::true_type{});
+        while (p < P) {
+            stage(bufB, bufA, std::false_type{});
+            if (p >= P) break;
+            stage(bufA, bufB, std::false_type{});
+        }
+    }
+
+    uint8_t* __restrict__ og = a.out + gstart * OES;
+    if (FAST) {
+        if (ODT == ZIPCCL_FP32) {
+            /* 32 contiguous bytes per lane: plain stores (streaming ones are slow on this pattern) */
+            *reinterpret_cast<u32x4*>(og + lane * 32u) = u32x4{__float_as_uint(acc[0]), __float_as_uint(acc[1]),
+                                                               __float_as_uint(acc[2]), __float_as_uint(acc[3])};
+            *reinterpret_cast<u32x4*>((og + 16) + lane * 32u) = u32x4{__float_as_uint(acc[4]), __float_as_uint(acc[5]),
+                                                                      __float_as_uint(acc[6]), __float_as_uint(acc[7])};
+        } else {
+            uint32_t o[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) o[k] = f32_to_bf16_bits(acc[2 * k]) | (f32_to_bf16_bits(acc[2 * k + 1]) << 16);
+            st_stream<u32x4>(og + lane * 16u, u32x4{o[0], o[1], o[2], o[3]});
+        }
+    } else {
+        const uint64_t e = gstart + lane * kLaneElems;
+        const uint32_t vmask = e >= n ? 0u : (n - e >= 8 ? 0xFFu : ((1u << (uint32_t)(n - e)) - 1u));
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            if ((vmask >> j) & 1u) {
+                const uint64_t i = lane * kLaneElems + j;
+                if (ODT == ZIPCCL_FP32) *reinterpret_cast<float*>(og + i * 4) = acc[j];
+                else *reinterpret_cast<uint16_t*>(og + i * 2) = (uint16_t)f32_to_bf16_bits(acc[j]);
+            }
+        }
+    }
+}
+
+/* a.gpw = groups per wave: the larger, the fewer workgroups pay for the header checks and the table
+ * build; 1 for small shards so that there are enough workgroups to fill the chip. */
+template <int DT, int ODT, bool FAST>
+__global__ __launch_bounds__(kThreads, DT == ZIPCCL_BF16 ? 8 : 6) void k_decompress_reduce(const ReduceArgs a)
+{
+    const uint32_t GPW = a.gpw;
+    const uint32_t kRTile = kGroup * kWavesPerBlock * GPW;
     __shared__ DecTables s_tab;
     __shared__ __attribute__((aligned(16))) uint8_t s_esc[kWavesPerBlock][kEscRegion];
     __shared__ uint32_t s_e0[kMaxPeers];      /* dec[1] of peer p's slot, 0 = header rejected */
@@ -353,7 +495,7 @@ __global__ __launch_bounds__(kThreads) void k_decompress_reduce(const ReduceArgs
     build_tables(s_tab);
 
     const uint64_t n = a.n;
-    const uint64_t ts = (uint64_t)blockIdx.x * kRTile;
+    const uint64_t ts = a.first_elem + (uint64_t)blockIdx.x * kRTile;
     const SlotLayout L = slot_layout(n, DT);
     bool bad = false;
     /* every slot's header is checked once per workgroup, one peer per thread */
@@ -367,85 +509,12 @@ __global__ __launch_bounds__(kThreads) void k_decompress_reduce(const ReduceArgs
     }
     __syncthreads();
 
-    const bool fast = (ts + kRTile <= n) && ((reinterpret_cast<uintptr_t>(a.out) & 15u) == 0);
     const uint32_t lane = lane_id();
-    const uint32_t wave = threadIdx.x >> 6;
-    const uint64_t ng = (n + kGroup - 1) / kGroup;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   /* scalar: group addresses are wave-uniform */
+#pragma unroll 1
     for (uint32_t u = 0; u < GPW; ++u) {
         const uint64_t gstart = ts + (uint64_t)(u * kWavesPerBlock + wave) * kGroup;
-        if (gstart >= n) continue;
-        const uint64_t g = gstart / kGroup;
-        float acc[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) acc[j] = 0.0f;
-        bool have = false;
-        const uint64_t e = gstart + lane * kLaneElems;
-        const uint32_t vmask = fast ? 0xFFu : (e >= n ? 0u : (n - e >= 8 ? 0xFFu : ((1u << (uint32_t)(n - e)) - 1u)));
-        /* the IDX entries of the next peer are fetched one iteration ahead (scalar loads) */
-        const uint32_t* idx0 = reinterpret_cast<const uint32_t*>(a.comp + L.idx);
-        uint32_t nb = idx0[g], nn = g + 1 < ng ? idx0[g + 1] : 0u;
-        for (uint32_t p = 0; p < a.n_peers; ++p) {
-            const uint8_t* __restrict__ slot = a.comp + (uint64_t)p * a.slot_cap;
-            const uint32_t e0 = s_e0[p], n_esc = s_nesc[p];
-            const uint32_t base = nb, next = g + 1 < ng ? nn : n_esc;
-            if (p + 1 < a.n_peers) {
-                const uint32_t* idxn = reinterpret_cast<const uint32_t*>(slot + a.slot_cap + L.idx);
-                nb = idxn[g];
-                if (g + 1 < ng) nn = idxn[g + 1];
-            }
-            if (e0 == 0u) continue;                      /* rejected slot: left out of the sum */
-            DecIn in;
-            u32x2 lv, lt;
-            in.base = base;
-            in.idx_ok = base <= next && next <= n_esc && next - base <= kGroup;
-            in.count = in.idx_ok ? next - base : 0u;
-            decode_fetch_list(slot, L, in, next, lane, lv, lt);
-            if (fast) decode_load<DT, true>(slot, L, n, gstart, lane, in);
-            else decode_load<DT, false>(slot, L, n, gstart, lane, in);
-            decode_park_list(s_esc[wave], lane, lv, lt);
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            const DecEsc es = decode_locate(in, s_esc[wave]);
-            __builtin_amdgcn_wave_barrier();
-            bad |= es.bad;
-            uint32_t hp[4];
-            decode_values(in, es, e0, s_tab, hp);
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                uint32_t w0, w1;
-                if (DT == ZIPCCL_BF16) { w0 = hp[k] << 16; w1 = hp[k] & 0xFFFF0000u; }
-                else { w0 = perm(hp[k], in.lo[k], 0x05040100u); w1 = perm(hp[k], in.lo[k], 0x07060302u); }
-                const float x0 = __uint_as_float(w0), x1 = __uint_as_float(w1);
-                acc[2 * k] = have ? acc[2 * k] + x0 : x0;
-                acc[2 * k + 1] = have ? acc[2 * k + 1] + x1 : x1;
-            }
-            have = true;
-        }
-        uint8_t* __restrict__ og = a.out + gstart * OES;
-        if (fast) {
-            if (ODT == ZIPCCL_FP32) {
-                /* 32 contiguous bytes per lane: plain stores (streaming ones are slow on this pattern) */
-                *reinterpret_cast<u32x4*>(og + lane * 32u) = u32x4{__float_as_uint(acc[0]), __float_as_uint(acc[1]),
-                                                                   __float_as_uint(acc[2]), __float_as_uint(acc[3])};
-                *reinterpret_cast<u32x4*>((og + 16) + lane * 32u) = u32x4{__float_as_uint(acc[4]), __float_as_uint(acc[5]),
-                                                                          __float_as_uint(acc[6]), __float_as_uint(acc[7])};
-            } else {
-                uint32_t o[4];
-#pragma unroll
-                for (int k = 0; k < 4; ++k) o[k] = f32_to_bf16_bits(acc[2 * k]) | (f32_to_bf16_bits(acc[2 * k + 1]) << 16);
-                st_stream<u32x4>(og + lane * 16u, u32x4{o[0], o[1], o[2], o[3]});
-            }
-        } else {
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                if ((vmask >> j) & 1u) {
-                    const uint64_t i = lane * kLaneElems + j;
-                    if (ODT == ZIPCCL_FP32) *reinterpret_cast<float*>(og + i * 4) = acc[j];
-                    else *reinterpret_cast<uint16_t*>(og + i * 2) = (uint16_t)f32_to_bf16_bits(acc[j]);
-                }
-            }
-        }
+        if (FAST || gstart < n) reduce_group<DT, ODT, FAST>(a, L, gstart, lane, s_esc[wave], s_tab, s_e0, s_nesc, bad);
     }
     if (bad && a.status) atomicOr(a.status, (uint32_t)ZIPCCL_ERR_CORRUPT);
 }
@@ -467,19 +536,36 @@ int launch_decompress_reduce(int dt, int out_dt, const ReduceArgs& a, void* stre
 {
     hipStream_t s = (hipStream_t)stream;
     const dim3 block(kThreads);
-    /* at least ~8 workgroups per CU before a workgroup takes four groups per wave */
-    const bool big = a.n >= (uint64_t)kTile * 2048u;
-    const uint64_t per = big ? kTile : kTile / kGroupsPerWave;
-    const dim3 grid((uint32_t)(a.n == 0 ? 1 : (a.n + per - 1) / per));
-#define ZIPCCL_REDUCE(DT, ODT)                                                                          \
-    do {                                                                                                \
-        if (big) hipLaunchKernelGGL((k_decompress_reduce<DT, ODT, kGroupsPerWave>), grid, block, 0, s, a); \
-        else hipLaunchKernelGGL((k_decompress_reduce<DT, ODT, 1u>), grid, block, 0, s, a);              \
+    /* at least ~8 workgroups per CU before a workgroup takes more than one group per wave */
+    ReduceArgs b = a;
+    b.gpw = a.n >= (uint64_t)kTile * 2048u ? kGroupsPerWave : 1u;
+    const uint64_t per = (uint64_t)kGroup * kWavesPerBlock * b.gpw;
+    /* whole tiles with an aligned output go to the kernel without bounds checks, the rest (at most one
+       tile, or everything when the output is not 16-byte aligned) to the general one */
+    const bool aligned = (reinterpret_cast<uintptr_t>(a.out) & 15u) == 0;
+    const uint64_t full = aligned ? a.n / per : 0;
+    const uint64_t rest = a.n - full * per;
+#define ZIPCCL_REDUCE(FAST, GRID)                                                                                      \
+    do {                                                                                                               \
+        if (dt == ZIPCCL_BF16 && out_dt == ZIPCCL_FP32)                                                                \
+            hipLaunchKernelGGL((k_decompress_reduce<ZIPCCL_BF16, ZIPCCL_FP32, FAST>), GRID, block, 0, s, b);           \
+        else if (dt == ZIPCCL_BF16)                                                                                    \
+            hipLaunchKernelGGL((k_decompress_reduce<ZIPCCL_BF16, ZIPCCL_BF16, FAST>), GRID, block, 0, s, b);           \
+        else if (out_dt == ZIPCCL_FP32)                                                                                \
+            hipLaunchKernelGGL((k_decompress_reduce<ZIPCCL_FP32, ZIPCCL_FP32, FAST>), GRID, block, 0, s, b);           \
+        else                                                                                                           \
+            hipLaunchKernelGGL((k_decompress_reduce<ZIPCCL_FP32, ZIPCCL_BF16, FAST>), GRID, block, 0, s, b);           \
     } while (0)
-    if (dt == ZIPCCL_BF16 && out_dt == ZIPCCL_FP32) ZIPCCL_REDUCE(ZIPCCL_BF16, ZIPCCL_FP32);
-    else if (dt == ZIPCCL_BF16) ZIPCCL_REDUCE(ZIPCCL_BF16, ZIPCCL_BF16);
-    else if (out_dt == ZIPCCL_FP32) ZIPCCL_REDUCE(ZIPCCL_FP32, ZIPCCL_FP32);
-    else ZIPCCL_REDUCE(ZIPCCL_FP32, ZIPCCL_BF16);
+    if (full) {
+        b.first_elem = 0;
+        const dim3 grid((uint32_t)full);
+        ZIPCCL_REDUCE(true, grid);
+    }
+    if (rest || a.n == 0) {     /* n == 0: one workgroup that only checks the headers */
+        b.first_elem = full * per;
+        const dim3 grid((uint32_t)(rest == 0 ? 1 : (rest + per - 1) / per));
+        ZIPCCL_REDUCE(false, grid);
+    }
 #undef ZIPCCL_REDUCE
     return (int)hipGetLastError();
 }

@@ -105,6 +105,8 @@ struct ReduceArgs {
     uint32_t* status;        /* may be null */
     uint64_t n;
     uint32_t n_peers;
+    uint32_t gpw;            /* groups per wave, set by the launcher */
+    uint64_t first_elem;     /* first value this launch covers, set by the launcher */
 };
 
 enum CompressMode { kModeCount = 0, kModeEmit = 1, kModeStash = 2 };

@@ -109,3 +109,55 @@ def test_reduce_flags_a_corrupt_slot_and_checks_arguments():
     with pytest.raises(z.ZipcclError) as ei:
         z.zipccl_decompress_reduce(buf, d_out, n, z.BF16, 0, z.FP32, d_st)
     assert ei.value.code == 1
+
+
+def test_reduce_leaves_rejected_slots_out_of_the_sum():
+    """A slot whose header is rejected is flagged and skipped; the others are summed in order
+    (first slot rejected: the sum starts at the second).  Sizes cover the bounds-check-free
+    kernel (whole tiles) and the general one (ragged tail)."""
+    rng = np.random.default_rng(6)
+    P = 4
+    for n in (4 * 2048 + 300, 1500):
+        peers = _peers(rng, P, n, z.BF16, [0.02])
+        buf = _receive_buffer(peers, z.BF16, [0.02])
+        cap1 = z.zipccl_max_compressed_size(n, z.BF16, 1)
+        for victim in (0, 2, 3):
+            print(f"[reduce] rejected slot {victim} n={n}", flush=True)
+            bad = buf.clone()
+            bad[victim * cap1 + 2] = 0x00                     # magic of that slot
+            rest = [peers[p] for p in range(P) if p != victim]
+            want = oracle.decompress_reduce(_receive_buffer(rest, z.BF16, [0.02]).cpu().numpy(), n, z.BF16, P - 1, z.FP32)
+            d_out = torch.full((n,), 0x3C3C3C3C, dtype=torch.int32, device=DEV)
+            d_st = torch.zeros(1, dtype=torch.int32, device=DEV)
+            z.zipccl_decompress_reduce(bad, d_out, n, z.BF16, P, z.FP32, d_st)
+            torch.cuda.synchronize()
+            assert int(d_st.item()) == 4
+            assert np.array_equal(d_out.cpu().numpy().view(np.uint32), want)
+
+
+def test_reduce_into_an_output_that_is_only_element_aligned_and_empty_input():
+    rng = np.random.default_rng(7)
+    n, P = 3 * 2048 + 17, 3
+    peers = _peers(rng, P, n, z.BF16, [0.02])
+    buf = _receive_buffer(peers, z.BF16, [0.02])
+    for out_dt, tdt, udt in ((z.BF16, torch.int16, np.uint16), (z.FP32, torch.int32, np.uint32)):
+        want = oracle.decompress_reduce(buf.cpu().numpy(), n, z.BF16, P, out_dt)
+        backing = torch.zeros(n + 8, dtype=tdt, device=DEV)
+        d_st = torch.zeros(1, dtype=torch.int32, device=DEV)
+        z.zipccl_decompress_reduce(buf, backing[1:n + 1], n, z.BF16, P, out_dt, d_st)
+        torch.cuda.synchronize()
+        got = backing.cpu().numpy().view(udt)
+        assert int(d_st.item()) == 0
+        assert np.array_equal(got[1:n + 1], want) and got[0] == 0 and not got[n + 1:].any()
+    # no values: only the headers are checked
+    cap0 = z.zipccl_max_compressed_size(0, z.BF16, 1)
+    empty = torch.zeros(cap0 * 2, dtype=torch.uint8, device=DEV)
+    ws = torch.empty(z.zipccl_compress_workspace_size(0, z.BF16, 1), dtype=torch.uint8, device=DEV)
+    d_in = torch.zeros(1, dtype=torch.int16, device=DEV)
+    for p in range(2):
+        z.zipccl_compress(d_in, 0, z.BF16, 1, None, z.zipccl_build_table(0.02, z.BF16), empty[p * cap0:(p + 1) * cap0], None, ws)
+    d_out = torch.zeros(4, dtype=torch.int32, device=DEV)
+    d_st = torch.zeros(1, dtype=torch.int32, device=DEV)
+    z.zipccl_decompress_reduce(empty, d_out, 0, z.BF16, 2, z.FP32, d_st)
+    torch.cuda.synchronize()
+    assert int(d_st.item()) == 0 and not d_out.cpu().numpy().any()
