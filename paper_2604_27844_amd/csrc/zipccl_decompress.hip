@@ -7,13 +7,12 @@
  * locate each lane's zero-point exponents.
  */
 #include "zipccl_device.h"
-#include <type_traits>
 
 namespace zipccl {
 namespace {
 
 /*
- * Decoder tables in LDS, indexed by a 4-bit zero-point mask q of four values:
+ * Entry of the 4-bit stage of the expand table, for a zero-point mask q of four values:
  * .x = v_perm selector putting the r-th byte of a compacted list at the position of the r-th
  * set bit of q (0x0c = constant 0 elsewhere), .y = 0xff in the bytes of set bits.
  */
@@ -34,16 +33,34 @@ __device__ __forceinline__ uint32_t spread4(uint32_t x)
     return __umul24(x, 0x204081u) & 0x01010101u;
 }
 
-/* Decoder tables in LDS, built once per workgroup (one entry per thread). */
+/*
+ * Decoder tables in LDS, built once per workgroup (one entry of each per thread):
+ * spread[k][b]  = the 8 bits of plane byte b at bit k of 8 bytes (.x = values 0..3, .y = values 4..7),
+ *                 so that the three planes of a lane combine with one OR;
+ * expand[m]     = for the lane's 8-bit zero-point mask m: v_perm selectors (.x for values 0..3, .y for
+ *                 values 4..7) that put the r-th byte of the lane's 8-byte list window at the position
+ *                 of the r-th set bit of m, and the byte masks of the set bits (.z, .w).
+ */
 struct DecTables {
-    uint2 spread[256];   /* plane byte -> its 8 bits in bit 0 of 8 bytes (.x = values 0..3, .y = values 4..7) */
-    uint2 expand[16];    /* 4-bit zero-point mask -> v_perm selector and byte mask, see expand_entry */
+    uint2 spread[3][256];
+    u32x4 expand[256];
+    uint2 expand4[16];   /* building block of expand[] */
 };
 
+/* Contains a workgroup barrier; the caller's next barrier makes the tables visible. */
 __device__ __forceinline__ void build_tables(DecTables& t)
 {
-    t.spread[threadIdx.x] = make_uint2(spread4(threadIdx.x & 15u), spread4(threadIdx.x >> 4));   /* kThreads == 256 */
-    if (threadIdx.x < 16) t.expand[threadIdx.x] = expand_entry(threadIdx.x);
+    const uint32_t b = threadIdx.x;                                   /* kThreads == 256 */
+    if (b < 16) t.expand4[b] = expand_entry(b);
+    const uint32_t lo = spread4(b & 15u), hi = spread4(b >> 4);
+    t.spread[0][b] = make_uint2(lo, hi);
+    t.spread[1][b] = make_uint2(lo << 1, hi << 1);
+    t.spread[2][b] = make_uint2(lo << 2, hi << 2);
+    __syncthreads();
+    /* values 4..7 continue in the window where values 0..3 stopped */
+    const uint2 a = t.expand4[b & 15u], c = t.expand4[b >> 4];
+    const uint32_t skip = __popc(b & 15u) * 0x01010101u;
+    t.expand[b] = u32x4{a.x, c.x + (skip & c.y), a.y, c.y};
 }
 
 /* Bytes of LDS per group for its zero-point exponents: 512 + up to 15 of misalignment, rounded up to
@@ -96,7 +113,9 @@ __device__ __forceinline__ void decode_fetch_list(const uint8_t* __restrict__ sl
 }
 
 /* Phase 1b: the lane's SM bytes, plane bytes and (fp32) low words. */
-template <int DT, bool FAST>
+/* WORDS: b0..b2 receive the aligned 32-bit word holding the lane's plane byte (see plane_bytes_of_words)
+ * instead of the byte itself. */
+template <int DT, bool FAST, bool WORDS = false>
 __device__ __forceinline__ void decode_load(const uint8_t* __restrict__ slot, const SlotLayout& L, uint64_t n,
                                             uint64_t gstart, uint32_t lane, DecIn& r)
 {
@@ -110,10 +129,16 @@ __device__ __forceinline__ void decode_load(const uint8_t* __restrict__ slot, co
     }
     const uint64_t pb = e >> 3;
     if (FAST || pb < L.plane_bytes) {
-        const uint8_t* pl = slot + L.p0 + (gstart >> 3);
-        r.b0 = ld_stream<uint8_t>(pl + lane);
-        r.b1 = ld_stream<uint8_t>((pl + L.plane_bytes) + lane);
-        r.b2 = ld_stream<uint8_t>((pl + 2 * L.plane_bytes) + lane);
+        const uint8_t* pl = slot + L.p0 + (gstart >> 3);     /* 64-byte aligned: a group's 64 plane bytes */
+        if (WORDS) {
+            r.b0 = ld_stream<uint32_t>(pl + (lane & ~3u));
+            r.b1 = ld_stream<uint32_t>((pl + L.plane_bytes) + (lane & ~3u));
+            r.b2 = ld_stream<uint32_t>((pl + 2 * L.plane_bytes) + (lane & ~3u));
+        } else {
+            r.b0 = ld_stream<uint8_t>(pl + lane);
+            r.b1 = ld_stream<uint8_t>((pl + L.plane_bytes) + lane);
+            r.b2 = ld_stream<uint8_t>((pl + 2 * L.plane_bytes) + lane);
+        }
     }
     if (DT == ZIPCCL_FP32) {
         if (FAST || 2 * e < pad128(2 * n)) {
@@ -123,6 +148,15 @@ __device__ __forceinline__ void decode_load(const uint8_t* __restrict__ slot, co
     }
     r.vmask = 0xFFu;
     if (!FAST) r.vmask = e >= n ? 0u : (n - e >= 8 ? 0xFFu : ((1u << (uint32_t)(n - e)) - 1u));
+}
+
+/* After decode_load<.., WORDS = true>: the lane's plane bytes out of the words that hold them. */
+__device__ __forceinline__ void plane_bytes_of_words(DecIn& r, uint32_t lane)
+{
+    const uint32_t sh = 8u * (lane & 3u);
+    r.b0 = __builtin_amdgcn_ubfe(r.b0, sh, 8u);
+    r.b1 = __builtin_amdgcn_ubfe(r.b1, sh, 8u);
+    r.b2 = __builtin_amdgcn_ubfe(r.b2, sh, 8u);
 }
 
 /* Phase 1c: park the slice in the wave's LDS region so that lanes can pick their bytes by position. */
@@ -137,7 +171,7 @@ __device__ __forceinline__ void decode_park_list(uint8_t* lds, uint32_t lane, co
 __device__ __forceinline__ DecEsc decode_locate(const DecIn& in, const uint8_t* lds)
 {
     DecEsc r;
-    r.m = ~(in.b0 | in.b1 | in.b2) & in.vmask;     /* code 0 = zero-point; tail bits are not */
+    r.m = ((in.b0 | in.b1 | in.b2) ^ 0xFFu) & in.vmask;     /* code 0 = zero-point; tail bits are not */
     const uint32_t cnt = __popc(r.m);
     const uint32_t inc = wave_incl_scan(cnt);
     const uint32_t gtot = __builtin_amdgcn_readlane(inc, 63);
@@ -158,19 +192,15 @@ __device__ __forceinline__ void decode_bytes(const DecIn& in, const DecEsc& es, 
 {
     /* code bytes of values 0..3 and 4..7 (plane bits spread by table), then exponent = dec[1] - 1 + code */
     const uint32_t k4 = (e0 - 1u) * 0x01010101u;
-    const uint2 t0 = tab.spread[in.b0], t1 = tab.spread[in.b1], t2 = tab.spread[in.b2];
-    uint32_t eA = (t0.x | (t1.x << 1) | (t2.x << 2)) + k4;
-    uint32_t eB = (t0.y | (t1.y << 1) | (t2.y << 2)) + k4;
-    const uint2* __restrict__ lut = tab.expand;
-    {   /* zero-point exponents dropped in place; a lane without zero-points selects nothing */
+    const uint2 t0 = tab.spread[0][in.b0], t1 = tab.spread[1][in.b1], t2 = tab.spread[2][in.b2];
+    uint32_t eA = (t0.x | t1.x | t2.x) + k4;
+    uint32_t eB = (t0.y | t1.y | t2.y) + k4;
+    {   /* zero-point exponents dropped in place: the lane's list bytes are the 8-byte window l8:h8 */
         const uint32_t l8 = __builtin_amdgcn_alignbyte(es.d1, es.d0, es.sh);
         const uint32_t h8 = __builtin_amdgcn_alignbyte(es.d2, es.d1, es.sh);
-        const uint32_t mA = es.m & 15u, mB = es.m >> 4;
-        const uint32_t nA = __popc(mA);
-        const uint2 tA = lut[mA], tB = lut[mB];
-        const uint32_t xB = nA == 4u ? h8 : __builtin_amdgcn_alignbyte(h8, l8, nA);
-        eA = bfi(tA.y, perm(0u, l8, tA.x), eA);
-        eB = bfi(tB.y, perm(0u, xB, tB.x), eB);
+        const u32x4 x = tab.expand[es.m];
+        eA = bfi(x.z, perm(h8, l8, x.x), eA);
+        eB = bfi(x.w, perm(h8, l8, x.y), eB);
     }
     /* recombine with sign and mantissa: low byte = mantissa | E bit 0 << 7, high = sign | E >> 1 */
     lA = bfi(0x7F7F7F7Fu, in.sm0, eA << 7); hA = bfi(0x80808080u, in.sm0, eA >> 1);
@@ -339,63 +369,94 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
     return nan ? ((u >> 16) | 0x0040u) : ((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
 }
 
-/* What is in flight for one peer's copy of a group: the loads of decode_load and decode_fetch_list,
- * and the index entries fetched ahead for the peer that uses this buffer next. */
-struct PeerLoads {
+/* One accepted slot of a reduce call, in the workgroup's LDS list (slot order). */
+struct PeerMeta {
+    uint32_t off_lo, off_hi;   /* byte offset of the slot in the receive buffer */
+    uint32_t n_esc;            /* zero-points of the slot */
+    uint32_t e0;               /* dec[1] of the slot */
+};
+
+/*
+ * A stage of the reduce pipeline = one peer's copy of one group.  The buffer holds the stage's loads in
+ * flight and what describes it (cur_*), and, fetched ahead, the description and index entries of the
+ * stage that uses the buffer next (pre_*, v_*).  Everything but the loaded words is wave-uniform.
+ */
+struct StageBuf {
     DecIn in;
     u32x4 lv;
-    uint32_t next;
-    uint32_t pre_base, pre_next;
+    uint32_t v_base, v_next;          /* index entries of the next stage (uniform values in vector registers) */
+    uint64_t pre_off, pre_gs;         /* next stage: slot offset, first element of the group */
+    uint32_t pre_nesc, pre_e0;
+    bool pre_last;                    /* next stage is the last peer of its group */
+    uint64_t cur_gs;
+    uint32_t cur_e0;
+    bool cur_last;
 };
 
 /*
  * Local reduction of the zipped Reduce-Scatter (paper sections 3.3 and 5.2): decode the slices
- * received from n_peers peers (slots back to back, n values each) and sum them in FP32, peers in
- * slot order starting from the first peer's value.  One pass: every compressed byte is read once and
- * only the sum is written.  A wave owns a group; the peer loop is innermost and software-pipelined:
- * the loads of peer p + 1 (and, ahead of them, the index entries of peer p + 2) are issued before
- * peer p is decoded, so that a wave always has a full group of loads in flight.
+ * received from the peers (slots back to back, n values each) and sum them in FP32, peers in slot
+ * order.  One pass: every compressed byte is read once and only the sum is written.
+ *
+ * A wave owns n_groups groups (gs0, gs0 + 2048, ...) and walks the stages (group, peer), peers
+ * innermost, as one software pipeline that does not drain between groups: while stage k is decoded,
+ * the loads of stage k + 1 are in flight and the index entries of stage k + 2 have been requested.
+ * Every stage issues the same number of loads, so that a wait for the older ones never has to drain
+ * the younger ones; past the last stage the look-ahead repeats the last stage's requests.
+ * The sum starts at -0.0f, which every first value x turns into x itself.
  */
 template <int DT, int ODT, bool FAST>
-__device__ __forceinline__ void reduce_group(const ReduceArgs& a, const SlotLayout& L, uint64_t gstart, uint32_t lane,
-                                             uint8_t* lds, const DecTables& tab, const uint32_t* s_e0,
-                                             const uint32_t* s_nesc, bool& bad)
+__device__ __forceinline__ void reduce_stages(const ReduceArgs& a, const SlotLayout& L, uint64_t gs0, uint32_t n_groups,
+                                              uint32_t n_acc, uint32_t lane, uint8_t* lds, const DecTables& tab,
+                                              const PeerMeta* s_meta, bool& bad)
 {
     constexpr uint32_t OES = ODT == ZIPCCL_BF16 ? 2u : 4u;
-    const uint64_t n = a.n;
-    const uint64_t g = gstart / kGroup, ng = (n + kGroup - 1) / kGroup;
-    const bool last_group = g + 1 >= ng;
-    const uint32_t P = a.n_peers;
+    constexpr uint64_t kGroupStride = (uint64_t)kGroup * kWavesPerBlock;
+    const uint64_t n = a.n, ng = (n + kGroup - 1) / kGroup;
+    const uint32_t T = n_acc * n_groups;
     float acc[8];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) acc[j] = 0.0f;
+    for (int j = 0; j < 8; ++j) acc[j] = -0.0f;
 
-    /* group g's index entries in peer p's slot, fetched two peers ahead of their use (wave-uniform) */
-    auto load_idx = [&](uint32_t p, PeerLoads& r) {
-        const uint32_t* __restrict__ idx = reinterpret_cast<const uint32_t*>(a.comp + (uint64_t)p * a.slot_cap + L.idx);
-        r.pre_base = idx[g];
-        r.pre_next = idx[last_group ? g : g + 1];      /* always two loads: every stage issues the same number */
+    /* the look-ahead front: describe its stage into r.pre_*, request the stage's index entries, advance */
+    uint32_t jf = 0, adv_left = T - 1u;
+    uint64_t gsf = gs0;
+    auto front = [&](StageBuf& r) {
+        const u32x4 m = *reinterpret_cast<const u32x4*>(&s_meta[jf]);
+        r.pre_off = ((uint64_t)__builtin_amdgcn_readfirstlane(m.y) << 32) | __builtin_amdgcn_readfirstlane(m.x);
+        r.pre_nesc = __builtin_amdgcn_readfirstlane(m.z);
+        r.pre_e0 = __builtin_amdgcn_readfirstlane(m.w);
+        r.pre_gs = gsf;
+        r.pre_last = jf + 1u == n_acc;
+        const uint64_t g = gsf / kGroup;
+        const uint32_t* __restrict__ idx = reinterpret_cast<const uint32_t*>(a.comp + r.pre_off + L.idx);
+        r.v_base = idx[g];
+        r.v_next = idx[g + 1 < ng ? g + 1 : g];
+        if (adv_left != 0u) {
+            --adv_left;
+            if (++jf == n_acc) { jf = 0; gsf += kGroupStride; }
+        }
     };
-    /* issue every vector load peer p's copy of the group needs; a rejected slot fetches no list.  With
-       live == false (past the last peer) the same loads go to the first bytes of the buffer instead and
-       their result is never used: the loop body then has one shape, and a wait for the older loads
-       never has to drain the younger ones. */
-    auto issue = [&](uint32_t p, bool live, PeerLoads& r) {
-        const uint8_t* __restrict__ slot = a.comp + (live ? (uint64_t)p * a.slot_cap : 0u);
-        const uint32_t e0 = live ? __builtin_amdgcn_readfirstlane(s_e0[p]) : 0u;
-        const uint32_t n_esc = __builtin_amdgcn_readfirstlane(s_nesc[p]);
-        const uint32_t base = __builtin_amdgcn_readfirstlane(r.pre_base);
-        r.next = last_group ? n_esc : __builtin_amdgcn_readfirstlane(r.pre_next);
+    /* issue every vector load of the stage r.pre_* describes */
+    auto issue = [&](StageBuf& r) {
+        r.cur_gs = r.pre_gs; r.cur_e0 = r.pre_e0; r.cur_last = r.pre_last;
+        const uint8_t* __restrict__ slot = a.comp + r.pre_off;
+        const uint32_t base = __builtin_amdgcn_readfirstlane(r.v_base);
+        const uint32_t next = r.pre_gs / kGroup + 1 < ng ? __builtin_amdgcn_readfirstlane(r.v_next) : r.pre_nesc;
         r.in.base = base;
-        r.in.idx_ok = e0 != 0u && base <= r.next && r.next <= n_esc && r.next - base <= kGroup;
-        r.in.count = r.in.idx_ok ? r.next - base : 0u;
-        decode_fetch_list(slot, L, r.in, r.next, lane, r.lv);
-        decode_load<DT, FAST>(slot, L, n, live ? gstart : 0u, lane, r.in);
+        r.in.idx_ok = base <= next && next <= r.pre_nesc && next - base <= kGroup;
+        r.in.count = r.in.idx_ok ? next - base : 0u;
+        decode_fetch_list(slot, L, r.in, next, lane, r.lv);
+        decode_load<DT, FAST, true>(slot, L, n, r.pre_gs, lane, r.in);
     };
-    /* decode peer p's copy and add it (FIRST: it starts the sum) */
-    auto consume = [&](uint32_t p, const PeerLoads& r, auto first_tag) {
-        constexpr bool kFirst = decltype(first_tag)::value;
-        const uint32_t e0 = __builtin_amdgcn_readfirstlane(s_e0[p]);
+    /* decode the stage in r and add it; after a group's last peer the sums are stored */
+    auto consume = [&](StageBuf& r) {
+        /* nothing that uses the stage's loaded words may be scheduled before this point (above the loads
+           of the next stage, where it would wait for them to land as well) */
+        asm volatile("" : "+v"(r.lv), "+v"(r.in.sm0), "+v"(r.in.sm1), "+v"(r.in.b0), "+v"(r.in.b1), "+v"(r.in.b2) : : "memory");
+        if (DT == ZIPCCL_FP32)
+            asm volatile("" : "+v"(r.in.lo[0]), "+v"(r.in.lo[1]), "+v"(r.in.lo[2]), "+v"(r.in.lo[3]) : : "memory");
+        plane_bytes_of_words(r.in, lane);
         decode_park_list(lds, lane, r.lv);
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
@@ -406,7 +467,7 @@ __device__ __forceinline__ void reduce_group(const ReduceArgs& a, const SlotLayo
         float x[8];
         if (DT == ZIPCCL_BF16) {
             uint32_t lA, hA, lB, hB;
-            decode_bytes(r.in, es, e0, tab, lA, hA, lB, hB);
+            decode_bytes(r.in, es, r.cur_e0, tab, lA, hA, lB, hB);
 #pragma unroll
             for (uint32_t j = 0; j < 4; ++j) {    /* value j as FP32 bits: high byte, low byte, 16 zero bits */
                 const uint32_t sel = ((4u + j) << 24) | (j << 16) | 0x0C0Cu;
@@ -415,7 +476,7 @@ __device__ __forceinline__ void reduce_group(const ReduceArgs& a, const SlotLayo
             }
         } else {
             uint32_t hp[4];
-            decode_values(r.in, es, e0, tab, hp);
+            decode_values(r.in, es, r.cur_e0, tab, hp);
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 x[2 * k] = __uint_as_float(perm(hp[k], r.in.lo[k], 0x05040100u));
@@ -423,98 +484,127 @@ __device__ __forceinline__ void reduce_group(const ReduceArgs& a, const SlotLayo
             }
         }
 #pragma unroll
-        for (int j = 0; j < 8; ++j) acc[j] = kFirst ? x[j] : acc[j] + x[j];
+        for (int j = 0; j < 8; ++j) acc[j] += x[j];
+        if (r.cur_last) {
+            uint8_t* __restrict__ og = a.out + r.cur_gs * OES;
+            if (FAST) {
+                if (ODT == ZIPCCL_FP32) {
+                    /* 32 contiguous bytes per lane: plain stores (streaming ones are slow on this pattern) */
+                    *reinterpret_cast<u32x4*>(og + lane * 32u) = u32x4{__float_as_uint(acc[0]), __float_as_uint(acc[1]),
+                                                                       __float_as_uint(acc[2]), __float_as_uint(acc[3])};
+                    *reinterpret_cast<u32x4*>((og + 16) + lane * 32u) = u32x4{__float_as_uint(acc[4]), __float_as_uint(acc[5]),
+                                                                              __float_as_uint(acc[6]), __float_as_uint(acc[7])};
+                } else {
+                    uint32_t o[4];
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) o[k] = f32_to_bf16_bits(acc[2 * k]) | (f32_to_bf16_bits(acc[2 * k + 1]) << 16);
+                    st_stream<u32x4>(og + lane * 16u, u32x4{o[0], o[1], o[2], o[3]});
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    if ((r.in.vmask >> j) & 1u) {
+                        const uint64_t i = lane * kLaneElems + j;
+                        if (ODT == ZIPCCL_FP32) *reinterpret_cast<float*>(og + i * 4) = acc[j];
+                        else *reinterpret_cast<uint16_t*>(og + i * 2) = (uint16_t)f32_to_bf16_bits(acc[j]);
+                    }
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[j] = -0.0f;
+        }
     };
 
-    /* rejected slots are left out of the sum: start at the first accepted one */
-    uint32_t p = 0;
-    while (p < P && s_e0[p] == 0u) ++p;
-    if (p < P) {
-        /* two load buffers used in turn (a copy from one to the other would have to wait for the loads) */
-        PeerLoads bufA, bufB;
-        bufA.pre_base = bufA.pre_next = bufB.pre_base = bufB.pre_next = 0;
-        /* decode peer p from c while x fills with peer p + 1; c's next user is peer p + 2, whose index
-           entries are requested first, so that they have arrived when that peer's loads are issued */
-        auto stage = [&](PeerLoads& c, PeerLoads& x, auto first_tag) {
-            load_idx(min(p + 2, P - 1u), c);
-            const bool live = p + 1 < P;
-            issue(live ? p + 1 : p, live, x);
-            if (decltype(first_tag)::value || s_e0[p] != 0u) consume(p, c, first_tag);
-            ++p;
-        };
-        load_idx(p, bufA);
-        load_idx(min(p + 1, P - 1u), bufB);
-        issue(p, true, bufA);
-        stage(bufA, bufB, std::true_type{});
-        while (p < P) {
-            stage(bufB, bufA, std::false_type{});
-            if (p >= P) break;
-            stage(bufA, bufB, std::false_type{});
-        }
-    }
-
-    uint8_t* __restrict__ og = a.out + gstart * OES;
-    if (FAST) {
-        if (ODT == ZIPCCL_FP32) {
-            /* 32 contiguous bytes per lane: plain stores (streaming ones are slow on this pattern) */
-            *reinterpret_cast<u32x4*>(og + lane * 32u) = u32x4{__float_as_uint(acc[0]), __float_as_uint(acc[1]),
-                                                               __float_as_uint(acc[2]), __float_as_uint(acc[3])};
-            *reinterpret_cast<u32x4*>((og + 16) + lane * 32u) = u32x4{__float_as_uint(acc[4]), __float_as_uint(acc[5]),
-                                                                      __float_as_uint(acc[6]), __float_as_uint(acc[7])};
-        } else {
-            uint32_t o[4];
-#pragma unroll
-            for (int k = 0; k < 4; ++k) o[k] = f32_to_bf16_bits(acc[2 * k]) | (f32_to_bf16_bits(acc[2 * k + 1]) << 16);
-            st_stream<u32x4>(og + lane * 16u, u32x4{o[0], o[1], o[2], o[3]});
-        }
-    } else {
-        const uint64_t e = gstart + lane * kLaneElems;
-        const uint32_t vmask = e >= n ? 0u : (n - e >= 8 ? 0xFFu : ((1u << (uint32_t)(n - e)) - 1u));
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            if ((vmask >> j) & 1u) {
-                const uint64_t i = lane * kLaneElems + j;
-                if (ODT == ZIPCCL_FP32) *reinterpret_cast<float*>(og + i * 4) = acc[j];
-                else *reinterpret_cast<uint16_t*>(og + i * 2) = (uint16_t)f32_to_bf16_bits(acc[j]);
-            }
-        }
+    /* two buffers used in turn (a copy from one to the other would have to wait for the loads) */
+    StageBuf bufA, bufB;
+    front(bufA);
+    front(bufB);
+    issue(bufA);
+    for (uint32_t k = 0;;) {
+        if (k + 1u >= T) { consume(bufA); break; }
+        front(bufA);
+        issue(bufB);
+        consume(bufA);
+        ++k;
+        if (k + 1u >= T) { consume(bufB); break; }
+        front(bufB);
+        issue(bufA);
+        consume(bufB);
+        ++k;
     }
 }
 
-/* a.gpw = groups per wave: the larger, the fewer workgroups pay for the header checks and the table
- * build; 1 for small shards so that there are enough workgroups to fill the chip. */
+/*
+ * a.gpw = groups per wave: the larger, the fewer workgroups pay for the header checks and the table
+ * build; 1 for small shards so that there are enough workgroups to fill the chip.  Dynamic LDS: one
+ * PeerMeta per peer.  FAST: every group of the launch is complete and the output 16-byte aligned.
+ */
 template <int DT, int ODT, bool FAST>
-__global__ __launch_bounds__(kThreads, DT == ZIPCCL_BF16 ? 8 : 6) void k_decompress_reduce(const ReduceArgs a)
+__global__ __launch_bounds__(kThreads, !FAST ? 4 : DT == ZIPCCL_BF16 ? 8 : 6) void k_decompress_reduce(const ReduceArgs a)
 {
-    const uint32_t GPW = a.gpw;
-    const uint32_t kRTile = kGroup * kWavesPerBlock * GPW;
+    extern __shared__ __attribute__((aligned(16))) uint8_t s_dyn[];
+    PeerMeta* s_meta = reinterpret_cast<PeerMeta*>(s_dyn);     /* the accepted slots, in slot order */
     __shared__ DecTables s_tab;
     __shared__ __attribute__((aligned(16))) uint8_t s_esc[kWavesPerBlock][kEscRegion];
-    __shared__ uint32_t s_e0[kMaxPeers];      /* dec[1] of peer p's slot, 0 = header rejected */
-    __shared__ uint32_t s_nesc[kMaxPeers];    /* zero-points of peer p's slot */
+    __shared__ uint32_t s_wcnt[kWavesPerBlock];
     build_tables(s_tab);
 
     const uint64_t n = a.n;
+    const uint32_t kRTile = kGroup * kWavesPerBlock * a.gpw;
     const uint64_t ts = a.first_elem + (uint64_t)blockIdx.x * kRTile;
     const SlotLayout L = slot_layout(n, DT);
-    bool bad = false;
-    /* every slot's header is checked once per workgroup, one peer per thread */
-    for (uint32_t p = threadIdx.x; p < a.n_peers; p += kThreads) {
-        const uint64_t slot_off = (uint64_t)p * a.slot_cap;
-        uint32_t e0, n_esc;
-        const bool ok = check_header<DT>(a.comp + slot_off, L, n, slot_off, a.comp_capacity, e0, n_esc);
-        s_e0[p] = ok ? e0 : 0u;
-        s_nesc[p] = n_esc;
-        bad |= !ok;
-    }
-    __syncthreads();
-
     const uint32_t lane = lane_id();
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   /* scalar: group addresses are wave-uniform */
-#pragma unroll 1
-    for (uint32_t u = 0; u < GPW; ++u) {
-        const uint64_t gstart = ts + (uint64_t)(u * kWavesPerBlock + wave) * kGroup;
-        if (FAST || gstart < n) reduce_group<DT, ODT, FAST>(a, L, gstart, lane, s_esc[wave], s_tab, s_e0, s_nesc, bad);
+
+    /* every slot's header is checked once per workgroup, one peer per thread; the accepted ones are
+       listed in slot order (ballot + per-wave counts), the others are left out of the sum */
+    uint32_t n_acc = 0;
+    for (uint32_t r = 0; r < a.n_peers; r += kThreads) {
+        const uint32_t p = r + threadIdx.x;
+        const uint64_t slot_off = (uint64_t)p * a.slot_cap;
+        uint32_t e0 = 0, n_esc = 0;
+        const bool ok = p < a.n_peers && check_header<DT>(a.comp + slot_off, L, n, slot_off, a.comp_capacity, e0, n_esc);
+        const uint64_t votes = __ballot(ok);
+        if (lane == 0) s_wcnt[wave] = (uint32_t)__popcll(votes);
+        __syncthreads();
+        uint32_t before = 0, total = 0;
+#pragma unroll
+        for (uint32_t w = 0; w < kWavesPerBlock; ++w) {
+            const uint32_t c = s_wcnt[w];
+            before += w < wave ? c : 0u;
+            total += c;
+        }
+        if (ok) {
+            const uint32_t pos = n_acc + before + (uint32_t)__popcll(votes & ((1ull << lane) - 1ull));
+            s_meta[pos] = PeerMeta{(uint32_t)slot_off, (uint32_t)(slot_off >> 32), n_esc, e0};
+        }
+        n_acc += total;
+        __syncthreads();
+    }
+    n_acc = __builtin_amdgcn_readfirstlane(n_acc);
+    bool bad = n_acc != a.n_peers;
+
+    /* this wave's groups start at gs0, gs0 + 2048, ...; those that begin inside n count */
+    const uint64_t gs0 = ts + (uint64_t)wave * kGroup;
+    constexpr uint64_t kGroupStride = (uint64_t)kGroup * kWavesPerBlock;
+    uint32_t n_groups = a.gpw;
+    if (!FAST) n_groups = gs0 >= n ? 0u : (uint32_t)min((uint64_t)a.gpw, (n - gs0 + kGroupStride - 1) / kGroupStride);
+    if (n_groups != 0u) {
+        if (n_acc != 0u) {
+            reduce_stages<DT, ODT, FAST>(a, L, gs0, n_groups, n_acc, lane, s_esc[wave], s_tab, s_meta, bad);
+        } else {
+            /* no slot accepted: the sum of nothing */
+            constexpr uint32_t OES = ODT == ZIPCCL_BF16 ? 2u : 4u;
+            for (uint32_t u = 0; u < n_groups; ++u) {
+                const uint64_t e = gs0 + u * kGroupStride + lane * kLaneElems;
+                for (uint32_t j = 0; j < kLaneElems; ++j) {
+                    if (e + j < n) {
+                        if (ODT == ZIPCCL_FP32) *reinterpret_cast<uint32_t*>(a.out + (e + j) * OES) = 0u;
+                        else *reinterpret_cast<uint16_t*>(a.out + (e + j) * OES) = 0u;
+                    }
+                }
+            }
+        }
     }
     if (bad && a.status) atomicOr(a.status, (uint32_t)ZIPCCL_ERR_CORRUPT);
 }
@@ -542,19 +632,20 @@ int launch_decompress_reduce(int dt, int out_dt, const ReduceArgs& a, void* stre
     const uint64_t per = (uint64_t)kGroup * kWavesPerBlock * b.gpw;
     /* whole tiles with an aligned output go to the kernel without bounds checks, the rest (at most one
        tile, or everything when the output is not 16-byte aligned) to the general one */
+    const size_t lds_bytes = sizeof(PeerMeta) * a.n_peers;
     const bool aligned = (reinterpret_cast<uintptr_t>(a.out) & 15u) == 0;
     const uint64_t full = aligned ? a.n / per : 0;
     const uint64_t rest = a.n - full * per;
 #define ZIPCCL_REDUCE(FAST, GRID)                                                                                      \
     do {                                                                                                               \
         if (dt == ZIPCCL_BF16 && out_dt == ZIPCCL_FP32)                                                                \
-            hipLaunchKernelGGL((k_decompress_reduce<ZIPCCL_BF16, ZIPCCL_FP32, FAST>), GRID, block, 0, s, b);           \
+            hipLaunchKernelGGL((k_decompress_reduce<ZIPCCL_BF16, ZIPCCL_FP32, FAST>), GRID, block, lds_bytes, s, b);           \
         else if (dt == ZIPCCL_BF16)                                                                                    \
-            hipLaunchKernelGGL((k_decompress_reduce<ZIPCCL_BF16, ZIPCCL_BF16, FAST>), GRID, block, 0, s, b);           \
+            hipLaunchKernelGGL((k_decompress_reduce<ZIPCCL_BF16, ZIPCCL_BF16, FAST>), GRID, block, lds_bytes, s, b);           \
         else if (out_dt == ZIPCCL_FP32)                                                                                \
-            hipLaunchKernelGGL((k_decompress_reduce<ZIPCCL_FP32, ZIPCCL_FP32, FAST>), GRID, block, 0, s, b);           \
+            hipLaunchKernelGGL((k_decompress_reduce<ZIPCCL_FP32, ZIPCCL_FP32, FAST>), GRID, block, lds_bytes, s, b);           \
         else                                                                                                           \
-            hipLaunchKernelGGL((k_decompress_reduce<ZIPCCL_FP32, ZIPCCL_BF16, FAST>), GRID, block, 0, s, b);           \
+            hipLaunchKernelGGL((k_decompress_reduce<ZIPCCL_FP32, ZIPCCL_BF16, FAST>), GRID, block, lds_bytes, s, b);           \
     } while (0)
     if (full) {
         b.first_elem = 0;
