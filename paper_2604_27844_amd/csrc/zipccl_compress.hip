@@ -320,22 +320,44 @@ __device__ __forceinline__ void move_words(uint32_t* __restrict__ d32, const uin
  * writes header, padding and chunk_bytes.  Tiles dense in zero-points (more than kPlaceBig
  * bytes) are moved by the whole workgroup afterwards.
  */
-template <int DT>
+/* SCAN: there was no k_tile_scan; the workgroup sums the chunk's tile counts before its own tiles itself
+ * (chunks of at most kPlaceScanTiles tiles: the counts are few and cache-resident). */
+template <int DT, bool SCAN>
 __global__ __launch_bounds__(kThreads) void k_place(const CompressArgs a)
 {
     constexpr uint32_t kSub = 16;                       /* lanes per tile */
     constexpr uint32_t kPlaceBig = 1024;                /* bytes a 16-lane group moves on its own */
+    __shared__ uint32_t s_wave[kWavesPerBlock];
+    __shared__ uint32_t s_ex[kThreads / kSub];
     __shared__ uint32_t s_nbig;
     __shared__ uint32_t s_big[kThreads / kSub];
     __shared__ uint64_t s_src[kThreads / kSub], s_dst[kThreads / kSub];
     __shared__ uint32_t s_nw[kThreads / kSub], s_sh[kThreads / kSub];
     if (threadIdx.x == 0) s_nbig = 0;
-    __syncthreads();
 
     /* grid = (16-tile groups of the largest chunk, chunks): the chunk's geometry is wave-uniform */
     const uint32_t c = blockIdx.y;
     const uint32_t first = a.tab.tile_start[c];
     const uint32_t ntc = a.tab.tile_start[c + 1] - first;
+    if (blockIdx.x * (kThreads / kSub) >= ntc) return;  /* a shorter chunk than the largest of the launch */
+    if (SCAN) {
+        /* counts of the chunk's tiles before this workgroup's, and the exclusive prefix inside it */
+        const uint32_t t0 = blockIdx.x * (kThreads / kSub);
+        uint32_t part[4] = {0, 0, 0, 0};
+        uint32_t i = threadIdx.x;
+        for (; i + 3u * kThreads < t0; i += 4u * kThreads) {
+#pragma unroll
+            for (uint32_t k = 0; k < 4; ++k) part[k] += a.tile_total[first + i + k * kThreads];
+        }
+        for (; i < t0; i += kThreads) part[0] += a.tile_total[first + i];
+        const uint32_t inc = wave_incl_scan((part[0] + part[1]) + (part[2] + part[3]));
+        if ((threadIdx.x & 63u) == 63u) s_wave[threadIdx.x >> 6] = inc;
+        if (threadIdx.x < kThreads / kSub) {            /* one row of 16 lanes */
+            const uint32_t mine = t0 + threadIdx.x < ntc ? a.tile_total[first + t0 + threadIdx.x] : 0u;
+            s_ex[threadIdx.x] = row_incl_scan(mine) - mine;
+        }
+    }
+    __syncthreads();
     const uint64_t n = a.tab.elem_off[c + 1] - a.tab.elem_off[c];
     uint8_t* __restrict__ slot = a.out + a.tab.slot_off[c];
     const SlotLayout L = slot_layout(n, DT);
@@ -355,7 +377,9 @@ __global__ __launch_bounds__(kThreads) void k_place(const CompressArgs a)
         const uint64_t g = (uint64_t)ti * kGroupsPerTile + sub;
         uint32_t idx_local = 0;
         if (g < ng) idx_local = idx[g];
-        const uint32_t P = a.tile_prefix[t];
+        uint32_t P;
+        if (SCAN) P = ((s_wave[0] + s_wave[1]) + (s_wave[2] + s_wave[3])) + s_ex[tw];
+        else P = a.tile_prefix[t];
         const uint32_t cnt = a.tile_total[t];
         if (P != 0u && g < ng) idx[g] = idx_local + P;
 
@@ -477,15 +501,18 @@ int launch_tile_scan(const CompressArgs& a, void* stream)
     return (int)hipGetLastError();
 }
 
-int launch_place(int dt, const CompressArgs& a, void* stream)
+int launch_place(int dt, bool scan, const CompressArgs& a, void* stream)
 {
     const dim3 grid((max_chunk_tiles(a.tab) + 15) / 16, a.tab.n_chunks), block(kThreads);   /* 16 tiles per workgroup */
-    if (dt == ZIPCCL_BF16)
-        hipLaunchKernelGGL((k_place<ZIPCCL_BF16>), grid, block, 0, (hipStream_t)stream, a);
-    else
-        hipLaunchKernelGGL((k_place<ZIPCCL_FP32>), grid, block, 0, (hipStream_t)stream, a);
+    hipStream_t s = (hipStream_t)stream;
+    if (dt == ZIPCCL_BF16) {
+        if (scan) hipLaunchKernelGGL((k_place<ZIPCCL_BF16, true>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((k_place<ZIPCCL_BF16, false>), grid, block, 0, s, a);
+    } else {
+        if (scan) hipLaunchKernelGGL((k_place<ZIPCCL_FP32, true>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((k_place<ZIPCCL_FP32, false>), grid, block, 0, s, a);
+    }
     return (int)hipGetLastError();
 }
-
 
 } // namespace zipccl

@@ -7,6 +7,7 @@
 #include <cmath>
 #include <cstdint>
 #include <cstdlib>
+#include <algorithm>
 #include <cstring>
 #include <vector>
 
@@ -243,9 +244,12 @@ zipccl_status_t compress_impl(const void* d_in, size_t n_elems, zipccl_dtype_t d
         a.tile_prefix = reinterpret_cast<uint32_t*>(ws + wp.prefix_off) + tile_base;
         a.stash = stash ? ws + wp.stash_off + elem_base : nullptr;
         if (stash) {
+            uint32_t max_tiles = 0;
+            for (uint32_t c = 0; c < nb; ++c) max_tiles = std::max(max_tiles, a.tab.tile_start[c + 1] - a.tab.tile_start[c]);
+            const bool fused_scan = max_tiles <= kPlaceScanTiles;
             if (launch_compress(dt, kModeStash, a, stream) != 0) return ZIPCCL_ERR_DEVICE;
-            if (launch_tile_scan(a, stream) != 0) return ZIPCCL_ERR_DEVICE;
-            if (launch_place(dt, a, stream) != 0) return ZIPCCL_ERR_DEVICE;
+            if (!fused_scan && launch_tile_scan(a, stream) != 0) return ZIPCCL_ERR_DEVICE;
+            if (launch_place(dt, fused_scan, a, stream) != 0) return ZIPCCL_ERR_DEVICE;
         } else {
             if (launch_compress(dt, kModeCount, a, stream) != 0) return ZIPCCL_ERR_DEVICE;
             if (launch_tile_scan(a, stream) != 0) return ZIPCCL_ERR_DEVICE;

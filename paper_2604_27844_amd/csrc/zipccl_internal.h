@@ -75,6 +75,7 @@ struct CompressArgs {
     ChunkTab tab;
 };
 
+constexpr uint32_t kPlaceScanTiles = 4096;            /* largest chunk (in tiles) for which k_place does the tile scan itself */
 constexpr uint32_t kMomentBlocks = 2048;             /* workgroups (and partial sums) of the sigma estimate */
 
 struct MomentArgs {
@@ -117,7 +118,7 @@ int launch_copy(void* d_dst, const void* d_src, uint64_t bytes, void* stream);
 int launch_estimate(int dt, const MomentArgs& a, void* stream);
 int launch_compress(int dt, int mode, const CompressArgs& a, void* stream);
 int launch_tile_scan(const CompressArgs& a, void* stream);
-int launch_place(int dt, const CompressArgs& a, void* stream);
+int launch_place(int dt, bool scan, const CompressArgs& a, void* stream);
 int launch_decompress(int dt, const DecompressArgs& a, void* stream);
 int launch_decompress_reduce(int dt, int out_dt, const ReduceArgs& a, void* stream);
 

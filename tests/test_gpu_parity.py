@@ -238,10 +238,12 @@ def test_random_splits_and_contents_fuzz(compress_path):
         check_parity(data, dtype, sigma, k, ce, label=f"fuzz{case}")
 
 
-def test_one_chunk_spanning_several_scan_segments(compress_path):
-    # 2500 tiles in a single chunk: the per-chunk prefix of tile counts crosses scan segments,
-    # plus a second, shorter chunk so that segment grids of unequal chunks are covered
-    ce = np.array([2500 * 8192 + 123, 1030 * 8192], dtype=np.uint64)
+@pytest.mark.parametrize("tiles", [2500, 4500], ids=["scan_in_place_kernel", "scan_kernel"])
+def test_one_chunk_spanning_several_scan_segments(compress_path, tiles):
+    # many tiles in a single chunk: the per-chunk prefix of tile counts crosses scan segments (2500 tiles:
+    # summed inside the placement kernel; 4500: by the scan kernel of its own), plus a second, shorter
+    # chunk so that grids over unequal chunks are covered
+    ce = np.array([tiles * 8192 + 123, 1030 * 8192], dtype=np.uint64)
     rng = np.random.default_rng(77)
     data = W.f32_to_bf16_words(rng.standard_normal(int(ce.sum()), dtype=np.float32) * np.float32(0.5))
     data[5_000_000:5_020_000] = 0x7F80                      # a dense stretch of zero-points
