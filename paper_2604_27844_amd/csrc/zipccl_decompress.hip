@@ -76,7 +76,7 @@ struct DecIn {
     uint32_t base;           /* IDX entry of the group = list position of its first zero-point */
     uint32_t count;          /* zero-points of the group according to IDX (next entry - this one) */
     uint32_t vmask;          /* bit j = value j exists */
-    bool idx_ok;             /* base <= next <= n_esc and count <= 512 */
+    uint32_t idx_bad;        /* nonzero unless base <= next <= n_esc and next - base <= 512 */
 };
 
 /* The lane's zero-point bytes (up to 8, in element order) and where its mask says they go. */
@@ -84,8 +84,17 @@ struct DecEsc {
     uint32_t m;              /* bit j = value j is a zero-point */
     uint32_t sh;             /* byte offset of the lane's first zero-point inside d0 */
     uint32_t d0, d1, d2;     /* three aligned words covering the lane's 8 list bytes */
-    bool bad;                /* planes and IDX disagree about the group */
+    uint32_t bad;            /* nonzero: planes and IDX disagree about the group */
 };
+
+/* r.base and next bound the group's slice of the zero-point list: check them, set r.count.
+ * (next - base wraps to a large number when next < base) */
+__device__ __forceinline__ void check_index(DecIn& r, uint32_t next, uint32_t n_esc)
+{
+    const uint32_t d = next - r.base;
+    r.idx_bad = (uint32_t)(d > kGroup) | (uint32_t)(next > n_esc);
+    r.count = r.idx_bad ? 0u : d;
+}
 
 /* Phase 0: the group's slice of the zero-point list by IDX alone (scalar loads). */
 __device__ __forceinline__ void decode_index(const uint8_t* __restrict__ slot, const SlotLayout& L, uint64_t n,
@@ -95,8 +104,7 @@ __device__ __forceinline__ void decode_index(const uint8_t* __restrict__ slot, c
     const uint32_t* __restrict__ idx = reinterpret_cast<const uint32_t*>(slot + L.idx);
     r.base = idx[g];
     next = g + 1 < ng ? idx[g + 1] : n_esc;
-    r.idx_ok = r.base <= next && next <= n_esc && next - r.base <= kGroup;
-    r.count = r.idx_ok ? next - r.base : 0u;
+    check_index(r, next, n_esc);
 }
 
 /* Phase 1a: fetch the slice [base, base + count): 16 aligned bytes per lane by the first 33 lanes, which
@@ -175,7 +183,7 @@ __device__ __forceinline__ DecEsc decode_locate(const DecIn& in, const uint8_t* 
     const uint32_t cnt = __popc(r.m);
     const uint32_t inc = wave_incl_scan(cnt);
     const uint32_t gtot = __builtin_amdgcn_readlane(inc, 63);
-    r.bad = !in.idx_ok || gtot != in.count;        /* planes and IDX must agree */
+    r.bad = in.idx_bad | (gtot ^ in.count);   /* planes and IDX must agree */
     /* the lane's zero-point exponents are the bytes [p, p + cnt) of the region, p <= 15 + 512 - cnt
        (clamped, so that a corrupt stream still reads inside the region) */
     const uint32_t p = min((in.base & 15u) + (inc - cnt), kGroup + 15u);
@@ -310,7 +318,7 @@ void k_decompress(const DecompressArgs a)
     const bool fast = (ts + kTile <= n) && ((reinterpret_cast<uintptr_t>(cout) & 15u) == 0);
     const uint32_t lane = lane_id();
     const uint32_t wave = threadIdx.x >> 6;   /* left in a vector register: measured faster here than scalar addressing */
-    bool bad = false;
+    uint32_t bad = 0;
     if (fast) {
         /* phases over the wave's four groups, so that each phase's loads are all in flight together
            and no vector load depends on another vector load */
@@ -369,27 +377,29 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
     return nan ? ((u >> 16) | 0x0040u) : ((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
 }
 
-/* One accepted slot of a reduce call, in the workgroup's LDS list (slot order). */
-struct PeerMeta {
-    uint32_t off_lo, off_hi;   /* byte offset of the slot in the receive buffer */
-    uint32_t n_esc;            /* zero-points of the slot */
-    uint32_t e0;               /* dec[1] of the slot */
-};
+/* A 32-bit load through the constant address space: for a wave-uniform address the compiler issues it
+ * as a scalar load whatever stores the kernel contains.  Only for memory no kernel writes while this one
+ * runs (the compressed input). */
+__device__ __forceinline__ uint32_t load_const_u32(const uint8_t* p)
+{
+    typedef const uint32_t __attribute__((address_space(4))) * cptr;
+    return *reinterpret_cast<cptr>(reinterpret_cast<uintptr_t>(p));
+}
 
 /*
  * A stage of the reduce pipeline = one peer's copy of one group.  The buffer holds the stage's loads in
- * flight and what describes it (cur_*), and, fetched ahead, the description and index entries of the
- * stage that uses the buffer next (pre_*, v_*).  Everything but the loaded words is wave-uniform.
+ * flight and what describes it (cur_*), and, fetched ahead with scalar loads, the description and index
+ * entries of the stage that uses the buffer next (pre_*).  Everything but the loaded words is wave-uniform.
  */
 struct StageBuf {
     DecIn in;
     u32x4 lv;
-    uint32_t v_base, v_next;          /* index entries of the next stage (uniform values in vector registers) */
-    uint64_t pre_off, pre_gs;         /* next stage: slot offset, first element of the group */
-    uint32_t pre_nesc, pre_e0;
-    bool pre_last;                    /* next stage is the last peer of its group */
-    uint64_t cur_gs;
-    uint32_t cur_e0;
+    uint64_t pre_off;                 /* next stage: slot offset, */
+    uint32_t pre_g;                   /* group, */
+    uint32_t pre_base, pre_next;      /* the group's index entry and the following one, */
+    uint32_t pre_nesc, pre_dec;       /* the slot's zero-point count and header word holding dec[0..3] */
+    bool pre_last;                    /* and whether it is the last peer of its group */
+    uint32_t cur_g, cur_e0;
     bool cur_last;
 };
 
@@ -408,54 +418,90 @@ struct StageBuf {
 template <int DT, int ODT, bool FAST>
 __device__ __forceinline__ void reduce_stages(const ReduceArgs& a, const SlotLayout& L, uint64_t gs0, uint32_t n_groups,
                                               uint32_t n_acc, uint32_t lane, uint8_t* lds, const DecTables& tab,
-                                              const PeerMeta* s_meta, bool& bad)
+                                              const uint32_t* s_peer, bool all_ok, uint32_t& bad)
 {
     constexpr uint32_t OES = ODT == ZIPCCL_BF16 ? 2u : 4u;
-    constexpr uint64_t kGroupStride = (uint64_t)kGroup * kWavesPerBlock;
-    const uint64_t n = a.n, ng = (n + kGroup - 1) / kGroup;
+    const uint64_t n = a.n;
+    const uint32_t ng = (uint32_t)((n + kGroup - 1) / kGroup);     /* n < 2^32: group numbers fit 32 bits */
     const uint32_t T = n_acc * n_groups;
     float acc[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) acc[j] = -0.0f;
 
-    /* the look-ahead front: describe its stage into r.pre_*, request the stage's index entries, advance */
+    /* the look-ahead front: describe its stage into r.pre_* (the slot's header was checked by the
+       workgroup; zero-point count, table and index entries come by scalar loads), then advance.
+       The index position moves along with the stage instead of being recomputed. */
     uint32_t jf = 0, adv_left = T - 1u;
-    uint64_t gsf = gs0;
+    uint32_t gf = (uint32_t)(gs0 / kGroup);
+    uint64_t idx_f = L.idx + 4u * (uint64_t)gf;                /* of IDX[gf] in a slot */
+    uint32_t next_f = gf + 1u < ng ? 4u : 0u;                  /* from there to the following entry, if any */
     auto front = [&](StageBuf& r) {
-        const u32x4 m = *reinterpret_cast<const u32x4*>(&s_meta[jf]);
-        r.pre_off = ((uint64_t)__builtin_amdgcn_readfirstlane(m.y) << 32) | __builtin_amdgcn_readfirstlane(m.x);
-        r.pre_nesc = __builtin_amdgcn_readfirstlane(m.z);
-        r.pre_e0 = __builtin_amdgcn_readfirstlane(m.w);
-        r.pre_gs = gsf;
+        /* some slot rejected: the j-th accepted one is not slot j */
+        const uint32_t p = all_ok ? jf : __builtin_amdgcn_readfirstlane(s_peer[jf]);
+        r.pre_off = (uint64_t)p * a.slot_cap;
+        const uint8_t* __restrict__ slot = a.comp + r.pre_off;
+        r.pre_nesc = load_const_u32(slot + 24);
+        r.pre_dec = load_const_u32(slot + 40);
+        r.pre_g = gf;
         r.pre_last = jf + 1u == n_acc;
-        const uint64_t g = gsf / kGroup;
-        const uint32_t* __restrict__ idx = reinterpret_cast<const uint32_t*>(a.comp + r.pre_off + L.idx);
-        r.v_base = idx[g];
-        r.v_next = idx[g + 1 < ng ? g + 1 : g];
+        r.pre_base = load_const_u32(slot + idx_f);
+        r.pre_next = load_const_u32(slot + idx_f + next_f);
         if (adv_left != 0u) {
             --adv_left;
-            if (++jf == n_acc) { jf = 0; gsf += kGroupStride; }
+            ++jf;
+            if (jf == n_acc) {
+                jf = 0;
+                gf += kWavesPerBlock;
+                idx_f += 4u * kWavesPerBlock;
+                next_f = gf + 1u < ng ? 4u : 0u;
+            }
         }
     };
-    /* issue every vector load of the stage r.pre_* describes */
+    /* issue every vector load of the stage r.pre_* describes.  FAST: the lanes' offsets inside a slot
+       (section + group + lane) are kept in vector registers and renewed when the group changes, so that
+       a stage adds nothing but the slot's address. */
+    uint32_t g_iss = 0xFFFFFFFFu;
+    uint64_t v_sm = 0, v_p0 = 0, v_p1 = 0, v_p2 = 0, v_lo = 0;
     auto issue = [&](StageBuf& r) {
-        r.cur_gs = r.pre_gs; r.cur_e0 = r.pre_e0; r.cur_last = r.pre_last;
+        r.cur_g = r.pre_g; r.cur_e0 = (r.pre_dec >> 8) & 0xFFu; r.cur_last = r.pre_last;
         const uint8_t* __restrict__ slot = a.comp + r.pre_off;
-        const uint32_t base = __builtin_amdgcn_readfirstlane(r.v_base);
-        const uint32_t next = r.pre_gs / kGroup + 1 < ng ? __builtin_amdgcn_readfirstlane(r.v_next) : r.pre_nesc;
-        r.in.base = base;
-        r.in.idx_ok = base <= next && next <= r.pre_nesc && next - base <= kGroup;
-        r.in.count = r.in.idx_ok ? next - base : 0u;
-        decode_fetch_list(slot, L, r.in, next, lane, r.lv);
-        decode_load<DT, FAST, true>(slot, L, n, r.pre_gs, lane, r.in);
+        const uint32_t next = r.pre_g + 1u < ng ? r.pre_next : r.pre_nesc;
+        r.in.base = r.pre_base;
+        check_index(r.in, next, r.pre_nesc);
+        if (FAST) {
+            if (r.pre_g != g_iss) {
+                g_iss = r.pre_g;
+                const uint64_t gs = (uint64_t)g_iss * kGroup;
+                v_sm = L.sm + gs + lane * 8u;
+                v_p0 = L.p0 + (gs >> 3) + (lane & ~3u);
+                v_p1 = v_p0 + L.plane_bytes;
+                v_p2 = v_p1 + L.plane_bytes;
+                v_lo = L.lo + 2 * gs + lane * 16u;
+            }
+            /* the list as in decode_fetch_list, relative to 16 bytes before it */
+            const uint32_t end = r.in.count != 0u ? next : 0u;
+            const uint32_t a16 = (r.in.base & ~15u) + 16u * lane;
+            r.lv = *reinterpret_cast<const u32x4*>((slot + (L.esc - 16)) + (a16 < end ? a16 + 16u : 0u));
+            const u32x2 sm = ld_stream<u32x2>(slot + v_sm);
+            r.in.sm0 = sm.x; r.in.sm1 = sm.y;
+            r.in.b0 = ld_stream<uint32_t>(slot + v_p0);
+            r.in.b1 = ld_stream<uint32_t>(slot + v_p1);
+            r.in.b2 = ld_stream<uint32_t>(slot + v_p2);
+            if (DT == ZIPCCL_FP32) {
+                const u32x4 lo = ld_stream<u32x4>(slot + v_lo);
+                r.in.lo[0] = lo.x; r.in.lo[1] = lo.y; r.in.lo[2] = lo.z; r.in.lo[3] = lo.w;
+            }
+            r.in.vmask = 0xFFu;
+        } else {
+            decode_fetch_list(slot, L, r.in, next, lane, r.lv);
+            decode_load<DT, false, true>(slot, L, n, (uint64_t)r.pre_g * kGroup, lane, r.in);
+        }
     };
     /* decode the stage in r and add it; after a group's last peer the sums are stored */
     auto consume = [&](StageBuf& r) {
-        /* nothing that uses the stage's loaded words may be scheduled before this point (above the loads
+        /* nothing that uses the stage's loaded words may be scheduled before this point (among the loads
            of the next stage, where it would wait for them to land as well) */
-        asm volatile("" : "+v"(r.lv), "+v"(r.in.sm0), "+v"(r.in.sm1), "+v"(r.in.b0), "+v"(r.in.b1), "+v"(r.in.b2) : : "memory");
-        if (DT == ZIPCCL_FP32)
-            asm volatile("" : "+v"(r.in.lo[0]), "+v"(r.in.lo[1]), "+v"(r.in.lo[2]), "+v"(r.in.lo[3]) : : "memory");
+        __builtin_amdgcn_sched_barrier(0);
         plane_bytes_of_words(r.in, lane);
         decode_park_list(lds, lane, r.lv);
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -486,7 +532,7 @@ __device__ __forceinline__ void reduce_stages(const ReduceArgs& a, const SlotLay
 #pragma unroll
         for (int j = 0; j < 8; ++j) acc[j] += x[j];
         if (r.cur_last) {
-            uint8_t* __restrict__ og = a.out + r.cur_gs * OES;
+            uint8_t* __restrict__ og = a.out + (uint64_t)r.cur_g * kGroup * OES;
             if (FAST) {
                 if (ODT == ZIPCCL_FP32) {
                     /* 32 contiguous bytes per lane: plain stores (streaming ones are slow on this pattern) */
@@ -515,35 +561,46 @@ __device__ __forceinline__ void reduce_stages(const ReduceArgs& a, const SlotLay
         }
     };
 
-    /* two buffers used in turn (a copy from one to the other would have to wait for the loads) */
+    /* two buffers used in turn (a copy from one to the other would have to wait for the loads).
+       front()'s scalar loads return out of order, so any wait for one of them (or for an LDS access)
+       waits for all: a stage requests them first, then issues its vector loads with what the previous
+       stage's requests brought (long complete: the LDS waits of its decode saw to that), then decodes. */
     StageBuf bufA, bufB;
     front(bufA);
     front(bufB);
+    __builtin_amdgcn_s_waitcnt(0xC07F);  /* lgkmcnt(0): nothing pending when the loop is entered */
     issue(bufA);
-    for (uint32_t k = 0;;) {
-        if (k + 1u >= T) { consume(bufA); break; }
+    uint32_t k = 0;                      /* stage whose loads bufA holds */
+    while (k + 2u < T) {                 /* two stages, each with a real stage to look ahead to */
         front(bufA);
+        asm volatile("" ::: "memory");
         issue(bufB);
         consume(bufA);
-        ++k;
-        if (k + 1u >= T) { consume(bufB); break; }
         front(bufB);
+        asm volatile("" ::: "memory");
         issue(bufA);
         consume(bufB);
-        ++k;
+        k += 2u;
+    }
+    if (k + 2u == T) {                   /* two stages left */
+        issue(bufB);
+        consume(bufA);
+        consume(bufB);
+    } else {
+        consume(bufA);
     }
 }
 
 /*
  * a.gpw = groups per wave: the larger, the fewer workgroups pay for the header checks and the table
  * build; 1 for small shards so that there are enough workgroups to fill the chip.  Dynamic LDS: one
- * PeerMeta per peer.  FAST: every group of the launch is complete and the output 16-byte aligned.
+ * 32-bit word per peer.  FAST: every group of the launch is complete and the output 16-byte aligned.
  */
 template <int DT, int ODT, bool FAST>
 __global__ __launch_bounds__(kThreads, !FAST ? 4 : DT == ZIPCCL_BF16 ? 8 : 6) void k_decompress_reduce(const ReduceArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t s_dyn[];
-    PeerMeta* s_meta = reinterpret_cast<PeerMeta*>(s_dyn);     /* the accepted slots, in slot order */
+    uint32_t* s_peer = reinterpret_cast<uint32_t*>(s_dyn);     /* the accepted slots, in slot order */
     __shared__ DecTables s_tab;
     __shared__ __attribute__((aligned(16))) uint8_t s_esc[kWavesPerBlock][kEscRegion];
     __shared__ uint32_t s_wcnt[kWavesPerBlock];
@@ -576,13 +633,13 @@ __global__ __launch_bounds__(kThreads, !FAST ? 4 : DT == ZIPCCL_BF16 ? 8 : 6) vo
         }
         if (ok) {
             const uint32_t pos = n_acc + before + (uint32_t)__popcll(votes & ((1ull << lane) - 1ull));
-            s_meta[pos] = PeerMeta{(uint32_t)slot_off, (uint32_t)(slot_off >> 32), n_esc, e0};
+            s_peer[pos] = p;
         }
         n_acc += total;
         __syncthreads();
     }
     n_acc = __builtin_amdgcn_readfirstlane(n_acc);
-    bool bad = n_acc != a.n_peers;
+    uint32_t bad = n_acc != a.n_peers;
 
     /* this wave's groups start at gs0, gs0 + 2048, ...; those that begin inside n count */
     const uint64_t gs0 = ts + (uint64_t)wave * kGroup;
@@ -591,7 +648,7 @@ __global__ __launch_bounds__(kThreads, !FAST ? 4 : DT == ZIPCCL_BF16 ? 8 : 6) vo
     if (!FAST) n_groups = gs0 >= n ? 0u : (uint32_t)min((uint64_t)a.gpw, (n - gs0 + kGroupStride - 1) / kGroupStride);
     if (n_groups != 0u) {
         if (n_acc != 0u) {
-            reduce_stages<DT, ODT, FAST>(a, L, gs0, n_groups, n_acc, lane, s_esc[wave], s_tab, s_meta, bad);
+            reduce_stages<DT, ODT, FAST>(a, L, gs0, n_groups, n_acc, lane, s_esc[wave], s_tab, s_peer, n_acc == a.n_peers, bad);
         } else {
             /* no slot accepted: the sum of nothing */
             constexpr uint32_t OES = ODT == ZIPCCL_BF16 ? 2u : 4u;
@@ -632,7 +689,7 @@ int launch_decompress_reduce(int dt, int out_dt, const ReduceArgs& a, void* stre
     const uint64_t per = (uint64_t)kGroup * kWavesPerBlock * b.gpw;
     /* whole tiles with an aligned output go to the kernel without bounds checks, the rest (at most one
        tile, or everything when the output is not 16-byte aligned) to the general one */
-    const size_t lds_bytes = sizeof(PeerMeta) * a.n_peers;
+    const size_t lds_bytes = sizeof(uint32_t) * a.n_peers;
     const bool aligned = (reinterpret_cast<uintptr_t>(a.out) & 15u) == 0;
     const uint64_t full = aligned ? a.n / per : 0;
     const uint64_t rest = a.n - full * per;
