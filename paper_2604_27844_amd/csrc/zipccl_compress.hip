@@ -129,16 +129,16 @@ struct CompressShared {
     uint32_t gcnt[kGroupsPerTile];         /* zero-points per group */
 };
 
-/* One group of one wave: load, encode, store SM/LO, stage planes and zero-points in LDS. */
+/* One group of one wave, its values already loaded (load_lane): encode, store SM/LO, stage planes and
+ * zero-points in LDS. */
 template <int DT, bool FAST, bool STORE>
-__device__ __forceinline__ void compress_group(const uint8_t* __restrict__ cin, uint8_t* __restrict__ slot,
-                                               const SlotLayout& L, uint64_t n, uint64_t ts, uint32_t gi,
-                                               uint32_t k7, uint32_t lane, CompressShared& sh)
+__device__ __forceinline__ void compress_group(uint8_t* __restrict__ slot, const SlotLayout& L, uint64_t n,
+                                               uint64_t ts, uint32_t gi, uint32_t k7, uint32_t lane,
+                                               CompressShared& sh, const uint32_t hp[4], const uint32_t lp[4],
+                                               uint32_t vmask)
 {
     const uint64_t gbase = ts + (uint64_t)gi * kGroup;      /* wave-uniform */
     const uint64_t e = gbase + lane * kLaneElems;
-    uint32_t hp[4], lp[4], vmask;
-    load_lane<DT, FAST>(cin, gbase, lane, n, hp, lp, vmask);
     const LaneEnc r = encode8(hp, k7);
     const uint32_t m = r.m & vmask;
     if (STORE) {
@@ -237,13 +237,23 @@ __global__ __launch_bounds__(kThreads) void k_compress(const CompressArgs a)
     const uint32_t k7 = ((e0 - 1u) << 7) * 0x00010001u;
 
     if (fast) {
+        /* all four groups' loads go out before the first is encoded: four times the bytes in flight per
+           wave, and no wait for a load ever includes the stores of the group before */
+        uint32_t hp[kGroupsPerWave][4], lp[kGroupsPerWave][4], vm[kGroupsPerWave];
 #pragma unroll
         for (uint32_t u = 0; u < kGroupsPerWave; ++u)
-            compress_group<DT, true, STORE>(cin, slot, L, n, ts, u * kWavesPerBlock + wave, k7, lane, sh);
+            load_lane<DT, true>(cin, ts + (uint64_t)(u * kWavesPerBlock + wave) * kGroup, lane, n, hp[u], lp[u], vm[u]);
+#pragma unroll
+        for (uint32_t u = 0; u < kGroupsPerWave; ++u)
+            compress_group<DT, true, STORE>(slot, L, n, ts, u * kWavesPerBlock + wave, k7, lane, sh, hp[u], lp[u], vm[u]);
     } else {
 #pragma unroll
-        for (uint32_t u = 0; u < kGroupsPerWave; ++u)
-            compress_group<DT, false, STORE>(cin, slot, L, n, ts, u * kWavesPerBlock + wave, k7, lane, sh);
+        for (uint32_t u = 0; u < kGroupsPerWave; ++u) {
+            const uint32_t gi = u * kWavesPerBlock + wave;
+            uint32_t hp[4], lp[4], vm;
+            load_lane<DT, false>(cin, ts + (uint64_t)gi * kGroup, lane, n, hp, lp, vm);
+            compress_group<DT, false, STORE>(slot, L, n, ts, gi, k7, lane, sh, hp, lp, vm);
+        }
     }
     __syncthreads();
 
