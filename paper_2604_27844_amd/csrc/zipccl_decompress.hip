@@ -270,22 +270,37 @@ __device__ __forceinline__ void decode_store(uint8_t* __restrict__ cout, const D
  * version, dtype, G and n must match the call, the table must be a window, and the zero-point
  * list the header promises must fit into the readable bytes.
  */
-template <int DT>
-__device__ __forceinline__ bool check_header(const uint8_t* __restrict__ slot, const SlotLayout& L, uint64_t n,
-                                             uint64_t slot_off, uint64_t comp_capacity, uint32_t& e0, uint32_t& n_esc)
+struct HeaderWords { uint32_t h[12]; };
+
+/* All twelve words are fetched before any is looked at (one round of scalar loads, no chain of
+ * dependent ones); a kernel can request them early and look at them later. */
+__device__ __forceinline__ HeaderWords load_header(const uint8_t* __restrict__ slot)
 {
     const uint32_t* hw = reinterpret_cast<const uint32_t*>(slot);
-    const uint64_t n_hdr = (uint64_t)hw[4] | ((uint64_t)hw[5] << 32);
-    const uint64_t ne = (uint64_t)hw[6] | ((uint64_t)hw[7] << 32);
-    const uint64_t cbytes = (uint64_t)hw[8] | ((uint64_t)hw[9] << 32);
-    const uint32_t dec_lo = hw[10], dec_hi = hw[11];
+    HeaderWords r;
+#pragma unroll
+    for (int i = 0; i < 12; ++i) r.h[i] = hw[i];
+    return r;
+}
+
+template <int DT>
+__device__ __forceinline__ bool check_header(const HeaderWords& hdr, const SlotLayout& L, uint64_t n,
+                                             uint64_t slot_off, uint64_t comp_capacity, uint32_t& e0, uint32_t& n_esc)
+{
+    const uint32_t* h = hdr.h;
+    const uint64_t n_hdr = (uint64_t)h[4] | ((uint64_t)h[5] << 32);
+    const uint64_t ne = (uint64_t)h[6] | ((uint64_t)h[7] << 32);
+    const uint64_t cbytes = (uint64_t)h[8] | ((uint64_t)h[9] << 32);
+    const uint32_t dec_lo = h[10], dec_hi = h[11];
     e0 = (dec_lo >> 8) & 0xFFu;
     n_esc = (uint32_t)ne;
-    bool ok = hw[0] == kMagic && hw[1] == kVersion && hw[2] == (uint32_t)DT && hw[3] == kGroup;
-    ok = ok && n_hdr == n && ne <= n && cbytes == L.esc + pad128(ne);
-    ok = ok && slot_off + cbytes <= comp_capacity;
-    ok = ok && e0 >= 1u && e0 <= 249u && (dec_lo >> 8) == (e0 | ((e0 + 1u) << 8) | ((e0 + 2u) << 16)) &&
-         dec_hi == ((e0 + 3u) | ((e0 + 4u) << 8) | ((e0 + 5u) << 16) | ((e0 + 6u) << 24));
+    uint32_t wrong = (h[0] ^ kMagic) | (h[1] ^ kVersion) | (h[2] ^ (uint32_t)DT) | (h[3] ^ kGroup);
+    wrong |= (uint32_t)(n_hdr != n) | (uint32_t)(ne > n) | (uint32_t)(cbytes != L.esc + pad128(ne));
+    wrong |= (uint32_t)(slot_off + cbytes > comp_capacity);
+    wrong |= (uint32_t)(e0 < 1u) | (uint32_t)(e0 > 249u);
+    wrong |= (dec_lo >> 8) ^ (e0 | ((e0 + 1u) << 8) | ((e0 + 2u) << 16));
+    wrong |= dec_hi ^ ((e0 + 3u) | ((e0 + 4u) << 8) | ((e0 + 5u) << 16) | ((e0 + 6u) << 24));
+    const bool ok = wrong == 0u;
     return ok;
 }
 
@@ -296,7 +311,6 @@ void k_decompress(const DecompressArgs a)
     constexpr uint32_t ES = DT == ZIPCCL_BF16 ? 2u : 4u;
     __shared__ DecTables s_tab;
     __shared__ __attribute__((aligned(16))) uint8_t s_esc[kWavesPerBlock][kGroupsPerWave][kEscRegion];
-    build_tables(s_tab);
 
     /* grid = (tiles of the largest chunk, chunks) */
     const uint32_t c = blockIdx.y;
@@ -306,34 +320,51 @@ void k_decompress(const DecompressArgs a)
     const uint8_t* __restrict__ slot = a.comp + a.tab.slot_off[c];
     uint8_t* __restrict__ cout = a.out + a.tab.elem_off[c] * ES;
     const SlotLayout L = slot_layout(n, DT);
+    const bool fast = (ts + kTile <= n) && ((reinterpret_cast<uintptr_t>(cout) & 15u) == 0);
+    const uint32_t lane = lane_id();
+    const uint32_t wave = threadIdx.x >> 6;   /* left in a vector register: measured faster here than scalar addressing */
+    const uint64_t ng = (n + kGroup - 1) / kGroup;
+
+    /* What does not depend on the header or on IDX goes out first (the static part is readable: the host
+       checked it): SM, planes and low words of the wave's four groups, and the groups' index entries.
+       The table build and the header check run while these loads are in flight. */
+    const HeaderWords hdr = load_header(slot);
+    DecIn in[kGroupsPerWave];
+    uint32_t next[kGroupsPerWave];
+    if (fast) {
+#pragma unroll
+        for (uint32_t u = 0; u < kGroupsPerWave; ++u) {
+            const uint64_t gstart = ts + (uint64_t)(u * kWavesPerBlock + wave) * kGroup;
+            decode_load<DT, true>(slot, L, n, gstart, lane, in[u]);
+            const uint64_t g = gstart / kGroup;
+            const uint32_t* __restrict__ idx = reinterpret_cast<const uint32_t*>(slot + L.idx);
+            in[u].base = idx[g];
+            next[u] = idx[g + 1 < ng ? g + 1 : g];
+        }
+    }
+    build_tables(s_tab);
 
     uint32_t e0, n_esc;
-    const bool ok = check_header<DT>(slot, L, n, a.tab.slot_off[c], a.comp_capacity, e0, n_esc);
+    const bool ok = check_header<DT>(hdr, L, n, a.tab.slot_off[c], a.comp_capacity, e0, n_esc);
     __syncthreads();
     if (!ok) {
         if (threadIdx.x == 0 && a.status) atomicOr(a.status, (uint32_t)ZIPCCL_ERR_CORRUPT);
         return;
     }
 
-    const bool fast = (ts + kTile <= n) && ((reinterpret_cast<uintptr_t>(cout) & 15u) == 0);
-    const uint32_t lane = lane_id();
-    const uint32_t wave = threadIdx.x >> 6;   /* left in a vector register: measured faster here than scalar addressing */
     uint32_t bad = 0;
     if (fast) {
-        /* phases over the wave's four groups, so that each phase's loads are all in flight together
-           and no vector load depends on another vector load */
-        DecIn in[kGroupsPerWave];
+        /* phases over the wave's four groups, so that each phase's loads are all in flight together */
         DecEsc es[kGroupsPerWave];
-        uint32_t next[kGroupsPerWave];
         u32x4 lv[kGroupsPerWave];
 #pragma unroll
-        for (uint32_t u = 0; u < kGroupsPerWave; ++u)
-            decode_index(slot, L, n, n_esc, ts + (uint64_t)(u * kWavesPerBlock + wave) * kGroup, in[u], next[u]);
+        for (uint32_t u = 0; u < kGroupsPerWave; ++u) {
+            const uint64_t g = (ts + (uint64_t)(u * kWavesPerBlock + wave) * kGroup) / kGroup;
+            if (g + 1 >= ng) next[u] = n_esc;
+            check_index(in[u], next[u], n_esc);
+        }
 #pragma unroll
         for (uint32_t u = 0; u < kGroupsPerWave; ++u) decode_fetch_list(slot, L, in[u], next[u], lane, lv[u]);
-#pragma unroll
-        for (uint32_t u = 0; u < kGroupsPerWave; ++u)
-            decode_load<DT, true>(slot, L, n, ts + (uint64_t)(u * kWavesPerBlock + wave) * kGroup, lane, in[u]);
 #pragma unroll
         for (uint32_t u = 0; u < kGroupsPerWave; ++u) decode_park_list(s_esc[wave][u], lane, lv[u]);
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -350,18 +381,18 @@ void k_decompress(const DecompressArgs a)
         for (uint32_t u = 0; u < kGroupsPerWave; ++u) {
             const uint64_t gstart = ts + (uint64_t)(u * kWavesPerBlock + wave) * kGroup;
             if (gstart < n) {
-                DecIn in;
-                uint32_t next;
+                DecIn r;
+                uint32_t nx;
                 u32x4 lv;
-                decode_index(slot, L, n, n_esc, gstart, in, next);
-                decode_fetch_list(slot, L, in, next, lane, lv);
-                decode_load<DT, false>(slot, L, n, gstart, lane, in);
+                decode_index(slot, L, n, n_esc, gstart, r, nx);
+                decode_fetch_list(slot, L, r, nx, lane, lv);
+                decode_load<DT, false>(slot, L, n, gstart, lane, r);
                 decode_park_list(s_esc[wave][u], lane, lv);
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                 __builtin_amdgcn_wave_barrier();
                 __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-                const DecEsc es = decode_locate(in, s_esc[wave][u]);
-                decode_store<DT, false>(cout, in, es, gstart, e0, lane, s_tab);
+                const DecEsc es = decode_locate(r, s_esc[wave][u]);
+                decode_store<DT, false>(cout, r, es, gstart, e0, lane, s_tab);
                 bad |= es.bad;
             }
         }
@@ -620,7 +651,7 @@ __global__ __launch_bounds__(kThreads, !FAST ? 4 : DT == ZIPCCL_BF16 ? 8 : 6) vo
         const uint32_t p = r + threadIdx.x;
         const uint64_t slot_off = (uint64_t)p * a.slot_cap;
         uint32_t e0 = 0, n_esc = 0;
-        const bool ok = p < a.n_peers && check_header<DT>(a.comp + slot_off, L, n, slot_off, a.comp_capacity, e0, n_esc);
+        const bool ok = p < a.n_peers && check_header<DT>(load_header(a.comp + slot_off), L, n, slot_off, a.comp_capacity, e0, n_esc);
         const uint64_t votes = __ballot(ok);
         if (lane == 0) s_wcnt[wave] = (uint32_t)__popcll(votes);
         __syncthreads();
