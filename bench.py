@@ -21,7 +21,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0            # MI355X HBM3E, published peak
-KERNELS = {"compress": "zipccl_compress = k_compress + k_tile_scan + k_place (one call, three launches)",
+KERNELS = {"compress": "zipccl_compress = k_compress + k_place (one call, two launches; chunks of more than 4096 tiles add k_tile_scan)",
            "decompress": "zipccl_decompress = k_decompress"}
 PAPER_CONTEXT = ("paper (64x RTX A6000, 200 Gb/s): communication time -1.35x, end-to-end training 1.18x; "
                  "it prints no codec GB/s, so vs_baseline is null")
