@@ -302,21 +302,22 @@ __global__ __launch_bounds__(kThreads) void k_compress(const CompressArgs a)
 }
 
 /* Move nw aligned words: word i of dst = bytes [4i + sh8, 4i + sh8 + 4) of the aligned word array s32.
- * `width` lanes (this one is number `lane`) share the job, four words per lane and step, with all
+ * `width` lanes (this one is number `lane`) share the job, W words per lane and step, with all
  * loads of a step issued before its stores.  Reads reach at most 7 bytes past the last source byte. */
+template <uint32_t W>
 __device__ __forceinline__ void move_words(uint32_t* __restrict__ d32, const uint32_t* __restrict__ s32,
                                            uint32_t nw, uint32_t sh8, uint32_t lane, uint32_t width)
 {
-    for (uint32_t i0 = 0; i0 < nw; i0 += 4u * width) {
-        uint32_t lo[4], hi[4];
+    for (uint32_t i0 = 0; i0 < nw; i0 += W * width) {
+        uint32_t lo[W], hi[W];
 #pragma unroll
-        for (uint32_t k = 0; k < 4; ++k) {
+        for (uint32_t k = 0; k < W; ++k) {
             const uint32_t i = i0 + k * width + lane;
             lo[k] = hi[k] = 0;
             if (i < nw) { lo[k] = s32[i]; hi[k] = s32[i + 1]; }
         }
 #pragma unroll
-        for (uint32_t k = 0; k < 4; ++k) {
+        for (uint32_t k = 0; k < W; ++k) {
             const uint32_t i = i0 + k * width + lane;
             if (i < nw) d32[i] = __builtin_amdgcn_alignbyte(hi[k], lo[k], sh8);
         }
@@ -406,7 +407,7 @@ __global__ __launch_bounds__(kThreads) void k_place(const CompressArgs a)
         if (sub < head) hb = src[sub];
         if (sub < cnt - done) tb = src[done + sub];
         if (cnt <= kPlaceBig) {
-            move_words(d32, s32, nw, sh8, sub, kSub);
+            move_words<4>(d32, s32, nw, sh8, sub, kSub);
         } else if (sub == 0) {
             const uint32_t k = atomicAdd(&s_nbig, 1u);
             s_big[k] = tw;
@@ -425,8 +426,9 @@ __global__ __launch_bounds__(kThreads) void k_place(const CompressArgs a)
     const uint32_t nbig = s_nbig;
     for (uint32_t b = 0; b < nbig; ++b) {
         const uint32_t k = s_big[b];
-        move_words(reinterpret_cast<uint32_t*>(s_dst[k]), reinterpret_cast<const uint32_t*>(s_src[k]), s_nw[k],
-                   s_sh[k], threadIdx.x, kThreads);
+        /* 8 words per lane: a whole tile (at most 2048 words) in one step */
+        move_words<8>(reinterpret_cast<uint32_t*>(s_dst[k]), reinterpret_cast<const uint32_t*>(s_src[k]), s_nw[k],
+                      s_sh[k], threadIdx.x, kThreads);
     }
 }
 
