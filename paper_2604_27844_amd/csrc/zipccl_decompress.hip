@@ -742,7 +742,9 @@ int launch_decompress_reduce(int dt, int out_dt, const ReduceArgs& a, void* stre
     }
     if (rest || a.n == 0) {     /* n == 0: one workgroup that only checks the headers */
         b.first_elem = full * per;
-        const dim3 grid((uint32_t)(rest == 0 ? 1 : (rest + per - 1) / per));
+        if (full) b.gpw = 1;    /* under a tile is left: one group per wave, so that it is not one workgroup's crawl */
+        const uint64_t per_rest = (uint64_t)kGroup * kWavesPerBlock * b.gpw;
+        const dim3 grid((uint32_t)(rest == 0 ? 1 : (rest + per_rest - 1) / per_rest));
         ZIPCCL_REDUCE(false, grid);
     }
 #undef ZIPCCL_REDUCE
