@@ -84,6 +84,7 @@ struct DecEsc {
     uint32_t m;              /* bit j = value j is a zero-point */
     uint32_t sh;             /* byte offset of the lane's first zero-point inside d0 */
     uint32_t d0, d1, d2;     /* three aligned words covering the lane's 8 list bytes */
+    uint32_t wA, wB;         /* two-quad lanes (fp32): the list bytes of the first and of the second quad */
     uint32_t bad;            /* nonzero: planes and IDX disagree about the group */
 };
 
@@ -123,10 +124,30 @@ __device__ __forceinline__ void decode_fetch_list(const uint8_t* __restrict__ sl
 /* Phase 1b: the lane's SM bytes, plane bytes and (fp32) low words. */
 /* WORDS: b0..b2 receive the aligned 32-bit word holding the lane's plane byte (see plane_bytes_of_words)
  * instead of the byte itself. */
-template <int DT, bool FAST, bool WORDS = false>
+template <int DT, bool FAST, bool WORDS = false, bool QUAD = false>
 __device__ __forceinline__ void decode_load(const uint8_t* __restrict__ slot, const SlotLayout& L, uint64_t n,
                                             uint64_t gstart, uint32_t lane, DecIn& r)
 {
+    if (QUAD) {
+        /* fp32, whole groups: the lane's 8 values are two quads, [4 lane, 4 lane + 4) of the group's first
+           and of its second half, so that its 32 output bytes are two contiguous 16-byte stores per wave row.
+           The lane fetches one plane byte per plane, the one it shares with its neighbour: even lanes that
+           of the first half, odd lanes that of the second (quad_plane_bytes sorts the nibbles out). */
+        const uint8_t* __restrict__ sm = slot + L.sm + gstart;
+        r.sm0 = ld_stream<uint32_t>(sm + lane * 4u);
+        r.sm1 = ld_stream<uint32_t>((sm + kGroup / 2) + lane * 4u);
+        const uint8_t* pl = slot + L.p0 + (gstart >> 3);
+        const uint32_t pi = (lane >> 1) + 32u * (lane & 1u);
+        r.b0 = ld_stream<uint8_t>(pl + pi);
+        r.b1 = ld_stream<uint8_t>((pl + L.plane_bytes) + pi);
+        r.b2 = ld_stream<uint8_t>((pl + 2 * L.plane_bytes) + pi);
+        const uint8_t* __restrict__ lo = slot + L.lo + 2 * gstart;
+        const u32x2 la = ld_stream<u32x2>(lo + lane * 8u);
+        const u32x2 lb = ld_stream<u32x2>((lo + kGroup) + lane * 8u);
+        r.lo[0] = la.x; r.lo[1] = la.y; r.lo[2] = lb.x; r.lo[3] = lb.y;
+        r.vmask = 0xFFu;
+        return;
+    }
     /* gstart is wave-uniform: uniform 64-bit base + 32-bit lane offset */
     const uint64_t e = gstart + lane * kLaneElems;
     r.sm0 = r.sm1 = r.b0 = r.b1 = r.b2 = 0;
@@ -167,6 +188,19 @@ __device__ __forceinline__ void plane_bytes_of_words(DecIn& r, uint32_t lane)
     r.b2 = __builtin_amdgcn_ubfe(r.b2, sh, 8u);
 }
 
+/* After decode_load<.., QUAD = true>: from the plane bytes shared by a pair of lanes to each lane's own
+ * byte (bits 0..3 = its first quad, bits 4..7 = its second), the three planes at once. */
+__device__ __forceinline__ void quad_plane_bytes(DecIn& r, uint32_t lane)
+{
+    const uint32_t p3 = (r.b0 & 0xFFu) | ((r.b1 & 0xFFu) << 8) | ((r.b2 & 0xFFu) << 16);
+    const uint32_t q3 = __builtin_amdgcn_update_dpp(0u, p3, 0xB1, 0xF, 0xF, false);   /* quad_perm [1,0,3,2] */
+    const uint32_t b3 = (lane & 1u) ? (((q3 >> 4) & 0x0F0F0Fu) | (p3 & 0xF0F0F0u))
+                                    : ((p3 & 0x0F0F0Fu) | ((q3 & 0x0F0F0Fu) << 4));
+    r.b0 = b3 & 0xFFu;
+    r.b1 = (b3 >> 8) & 0xFFu;
+    r.b2 = b3 >> 16;
+}
+
 /* Phase 1c: park the slice in the wave's LDS region so that lanes can pick their bytes by position. */
 __device__ __forceinline__ void decode_park_list(uint8_t* lds, uint32_t lane, const u32x4& v)
 {
@@ -193,8 +227,30 @@ __device__ __forceinline__ DecEsc decode_locate(const DecIn& in, const uint8_t* 
     return r;
 }
 
+/* Phase 2 for two-quad lanes: element order is all first quads by lane, then all second quads, so the
+ * lane's zero-points sit in two places of the slice; one scan carries both counts. */
+__device__ __forceinline__ DecEsc decode_locate_quad(const DecIn& in, const uint8_t* lds)
+{
+    DecEsc r;
+    r.m = (in.b0 | in.b1 | in.b2) ^ 0xFFu;
+    const uint32_t cA = __popc(r.m & 15u), cB = __popc(r.m >> 4);
+    const uint32_t inc = wave_incl_scan(cA | (cB << 16));
+    const uint32_t tot = __builtin_amdgcn_readlane(inc, 63);
+    const uint32_t totA = tot & 0xFFFFu;
+    r.bad = in.idx_bad | ((totA + (tot >> 16)) ^ in.count);
+    const uint32_t pA = min((in.base & 15u) + (inc & 0xFFFFu) - cA, kGroup + 15u);
+    const uint32_t pB = min((in.base & 15u) + totA + (inc >> 16) - cB, kGroup + 15u);
+    const uint32_t* wa = reinterpret_cast<const uint32_t*>(lds + (pA & ~3u));
+    const uint32_t* wb = reinterpret_cast<const uint32_t*>(lds + (pB & ~3u));
+    r.wA = __builtin_amdgcn_alignbyte(wa[1], wa[0], pA & 3u);
+    r.wB = __builtin_amdgcn_alignbyte(wb[1], wb[0], pB & 3u);
+    r.d0 = r.d1 = r.d2 = r.sh = 0;
+    return r;
+}
+
 /* Rebuild the bytes of the high 16-bit words of the lane's 8 values (section 4, third paragraph):
  * lA / hA = low / high bytes of values 0..3, lB / hB of values 4..7. */
+template <bool QUAD = false>
 __device__ __forceinline__ void decode_bytes(const DecIn& in, const DecEsc& es, uint32_t e0, const DecTables& tab,
                                              uint32_t& lA, uint32_t& hA, uint32_t& lB, uint32_t& hB)
 {
@@ -203,7 +259,11 @@ __device__ __forceinline__ void decode_bytes(const DecIn& in, const DecEsc& es, 
     const uint2 t0 = tab.spread[0][in.b0], t1 = tab.spread[1][in.b1], t2 = tab.spread[2][in.b2];
     uint32_t eA = (t0.x | t1.x | t2.x) + k4;
     uint32_t eB = (t0.y | t1.y | t2.y) + k4;
-    {   /* zero-point exponents dropped in place: the lane's list bytes are the 8-byte window l8:h8 */
+    if (QUAD) {   /* each quad's zero-point exponents from its own window */
+        const uint2 xa = tab.expand4[es.m & 15u], xb = tab.expand4[es.m >> 4];
+        eA = bfi(xa.y, perm(0u, es.wA, xa.x), eA);
+        eB = bfi(xb.y, perm(0u, es.wB, xb.x), eB);
+    } else {   /* zero-point exponents dropped in place: the lane's list bytes are the 8-byte window l8:h8 */
         const uint32_t l8 = __builtin_amdgcn_alignbyte(es.d1, es.d0, es.sh);
         const uint32_t h8 = __builtin_amdgcn_alignbyte(es.d2, es.d1, es.sh);
         const u32x4 x = tab.expand[es.m];
@@ -216,11 +276,12 @@ __device__ __forceinline__ void decode_bytes(const DecIn& in, const DecEsc& es, 
 }
 
 /* The same as four words holding the 8 high 16-bit words in element order. */
+template <bool QUAD = false>
 __device__ __forceinline__ void decode_values(const DecIn& in, const DecEsc& es, uint32_t e0,
                                               const DecTables& tab, uint32_t hp[4])
 {
     uint32_t lA, hA, lB, hB;
-    decode_bytes(in, es, e0, tab, lA, hA, lB, hB);
+    decode_bytes<QUAD>(in, es, e0, tab, lA, hA, lB, hB);
     hp[0] = perm(hA, lA, 0x05010400u);
     hp[1] = perm(hA, lA, 0x07030602u);
     hp[2] = perm(hB, lB, 0x05010400u);
@@ -234,20 +295,21 @@ __device__ __forceinline__ void decode_store(uint8_t* __restrict__ cout, const D
 {
     const uint64_t e = gstart + lane * kLaneElems;
     uint32_t hp[4];
-    decode_values(in, es, e0, tab, hp);
+    decode_values<DT == ZIPCCL_FP32 && FAST>(in, es, e0, tab, hp);
     if (FAST) {
         if (DT == ZIPCCL_BF16) {
             st_stream<u32x4>((cout + gstart * 2) + lane * 16u, u32x4{hp[0], hp[1], hp[2], hp[3]});
         } else {
+            /* two quads per lane (decode_load<.., QUAD>): values 0..3 belong to the group's first half,
+               4..7 to its second; each store is 16 contiguous bytes per lane */
             uint32_t x[8];
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 x[2 * k] = perm(hp[k], in.lo[k], 0x05040100u);
                 x[2 * k + 1] = perm(hp[k], in.lo[k], 0x07060302u);
             }
-            /* 32 contiguous bytes per lane: plain stores (streaming ones are slow on this pattern) */
-            *reinterpret_cast<u32x4*>((cout + gstart * 4) + lane * 32u) = u32x4{x[0], x[1], x[2], x[3]};
-            *reinterpret_cast<u32x4*>((cout + gstart * 4 + 16) + lane * 32u) = u32x4{x[4], x[5], x[6], x[7]};
+            st_stream<u32x4>((cout + gstart * 4) + lane * 16u, u32x4{x[0], x[1], x[2], x[3]});
+            st_stream<u32x4>((cout + gstart * 4 + 2 * kGroup) + lane * 16u, u32x4{x[4], x[5], x[6], x[7]});
         }
     } else {
 #pragma unroll
@@ -335,7 +397,7 @@ void k_decompress(const DecompressArgs a)
 #pragma unroll
         for (uint32_t u = 0; u < kGroupsPerWave; ++u) {
             const uint64_t gstart = ts + (uint64_t)(u * kWavesPerBlock + wave) * kGroup;
-            decode_load<DT, true>(slot, L, n, gstart, lane, in[u]);
+            decode_load<DT, true, false, DT == ZIPCCL_FP32>(slot, L, n, gstart, lane, in[u]);
             const uint64_t g = gstart / kGroup;
             const uint32_t* __restrict__ idx = reinterpret_cast<const uint32_t*>(slot + L.idx);
             in[u].base = idx[g];
@@ -371,7 +433,14 @@ void k_decompress(const DecompressArgs a)
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 #pragma unroll
-        for (uint32_t u = 0; u < kGroupsPerWave; ++u) es[u] = decode_locate(in[u], s_esc[wave][u]);
+        for (uint32_t u = 0; u < kGroupsPerWave; ++u) {
+            if (DT == ZIPCCL_FP32) {
+                quad_plane_bytes(in[u], lane);
+                es[u] = decode_locate_quad(in[u], s_esc[wave][u]);
+            } else {
+                es[u] = decode_locate(in[u], s_esc[wave][u]);
+            }
+        }
 #pragma unroll
         for (uint32_t u = 0; u < kGroupsPerWave; ++u) {
             decode_store<DT, true>(cout, in[u], es[u], ts + (uint64_t)(u * kWavesPerBlock + wave) * kGroup, e0, lane, s_tab);
