@@ -31,24 +31,37 @@ namespace {
  * lp[k] the low words (fp32 only).  vmask bit j = value j exists (e + j < n).
  * Values that do not exist read as 0.
  */
+/* FAST, bf16: `skew` says that the chunk starts at an odd element of the tensor, i.e. its bytes are 2 but
+ * not 4-byte aligned; the lane's 16 bytes then come as halfword + three dwords + halfword. */
 template <int DT, bool FAST>
 __device__ __forceinline__ void load_lane(const uint8_t* __restrict__ cin, uint64_t gbase, uint32_t lane, uint64_t n,
-                                          uint32_t hp[4], uint32_t lp[4], uint32_t& vmask)
+                                          uint32_t hp[4], uint32_t lp[4], uint32_t& vmask, bool skew = false)
 {
     /* gbase (first value of the group) is wave-uniform: uniform 64-bit base + 32-bit lane offset */
     const uint64_t e = gbase + lane * kLaneElems;
     if (FAST) {
         vmask = 0xFFu;
         if (DT == ZIPCCL_BF16) {
-            const u32x4 v = ld_stream<u32x4>((cin + gbase * 2) + lane * 16u);
-            hp[0] = v.x; hp[1] = v.y; hp[2] = v.z; hp[3] = v.w;
+            const uint8_t* __restrict__ p = (cin + gbase * 2) + lane * 16u;
+            if (!skew) {
+                const u32x4 v = ld_stream_a4(p);
+                hp[0] = v.x; hp[1] = v.y; hp[2] = v.z; hp[3] = v.w;
+            } else {
+                const uint32_t h0 = ld_stream<uint16_t>(p);
+                const u32x3 d = __builtin_nontemporal_load(reinterpret_cast<const u32x3_a4*>(p + 2));
+                const uint32_t h7 = ld_stream<uint16_t>(p + 14);
+                hp[0] = h0 | (d.x << 16);
+                hp[1] = __builtin_amdgcn_alignbyte(d.y, d.x, 2u);
+                hp[2] = __builtin_amdgcn_alignbyte(d.z, d.y, 2u);
+                hp[3] = (d.z >> 16) | (h7 << 16);
+            }
             lp[0] = lp[1] = lp[2] = lp[3] = 0;
         } else {
             /* fp32, whole groups: the lane's 8 values are two quads, [4 lane, 4 lane + 4) of the group's first
                half and of its second half, so that each load is 16 contiguous bytes per lane (32 contiguous
                bytes per lane cost ~7 % of the bandwidth, measured).  Values 0..3 = first quad, 4..7 = second. */
-            const u32x4 a = ld_stream<u32x4>((cin + gbase * 4) + lane * 16u);
-            const u32x4 b = ld_stream<u32x4>((cin + gbase * 4 + 2 * kGroup) + lane * 16u);
+            const u32x4 a = ld_stream_a4((cin + gbase * 4) + lane * 16u);
+            const u32x4 b = ld_stream_a4((cin + gbase * 4 + 2 * kGroup) + lane * 16u);
             const uint32_t x[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
@@ -273,7 +286,10 @@ __global__ __launch_bounds__(kThreads) void k_compress(const CompressArgs a)
     const uint8_t* __restrict__ cin = a.in + a.tab.elem_off[c] * ES;
     uint8_t* __restrict__ slot = a.out + a.tab.slot_off[c];
     const SlotLayout L = slot_layout(n, DT);
-    const bool fast = (ts + kTile <= n) && ((reinterpret_cast<uintptr_t>(cin) & 15u) == 0);
+    /* whole tiles take the vector path; a chunk of the tensor starts at some element of it, so its bytes are
+       dword-aligned or (bf16, odd element) skewed by one halfword */
+    const bool fast = ts + kTile <= n;
+    const bool skew = (reinterpret_cast<uintptr_t>(cin) & 2u) != 0;
     const uint32_t lane = lane_id();
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   /* keep wave-derived math scalar */
     /* the table is a kernel argument, or (estimated on the device) two words in device memory */
@@ -288,7 +304,7 @@ __global__ __launch_bounds__(kThreads) void k_compress(const CompressArgs a)
         uint32_t hp[kGroupsPerWave][4], lp[kGroupsPerWave][4], vm[kGroupsPerWave];
 #pragma unroll
         for (uint32_t u = 0; u < kGroupsPerWave; ++u)
-            load_lane<DT, true>(cin, ts + (uint64_t)(u * kWavesPerBlock + wave) * kGroup, lane, n, hp[u], lp[u], vm[u]);
+            load_lane<DT, true>(cin, ts + (uint64_t)(u * kWavesPerBlock + wave) * kGroup, lane, n, hp[u], lp[u], vm[u], skew);
 #pragma unroll
         for (uint32_t u = 0; u < kGroupsPerWave; ++u)
             compress_group<DT, true, STORE>(slot, L, n, ts, u * kWavesPerBlock + wave, k7, lane, sh, hp[u], lp[u], vm[u]);

@@ -291,14 +291,27 @@ __device__ __forceinline__ void decode_values(const DecIn& in, const DecEsc& es,
 /* Rebuild the 8 values and store them. */
 template <int DT, bool FAST>
 __device__ __forceinline__ void decode_store(uint8_t* __restrict__ cout, const DecIn& in, const DecEsc& es,
-                                             uint64_t gstart, uint32_t e0, uint32_t lane, const DecTables& tab)
+                                             uint64_t gstart, uint32_t e0, uint32_t lane, const DecTables& tab,
+                                             bool skew = false)
 {
     const uint64_t e = gstart + lane * kLaneElems;
     uint32_t hp[4];
     decode_values<DT == ZIPCCL_FP32 && FAST>(in, es, e0, tab, hp);
     if (FAST) {
         if (DT == ZIPCCL_BF16) {
-            st_stream<u32x4>((cout + gstart * 2) + lane * 16u, u32x4{hp[0], hp[1], hp[2], hp[3]});
+            uint8_t* __restrict__ p = (cout + gstart * 2) + lane * 16u;
+            if (!skew) {
+                st_stream_a4(p, u32x4{hp[0], hp[1], hp[2], hp[3]});
+            } else {
+                /* the chunk starts at an odd element of the tensor (bytes 2 but not 4-byte aligned):
+                   halfword + three dwords + halfword */
+                st_stream<uint16_t>(p, (uint16_t)hp[0]);
+                __builtin_nontemporal_store(u32x3{__builtin_amdgcn_alignbyte(hp[1], hp[0], 2u),
+                                                  __builtin_amdgcn_alignbyte(hp[2], hp[1], 2u),
+                                                  __builtin_amdgcn_alignbyte(hp[3], hp[2], 2u)},
+                                            reinterpret_cast<u32x3_a4*>(p + 2));
+                st_stream<uint16_t>(p + 14, (uint16_t)(hp[3] >> 16));
+            }
         } else {
             /* two quads per lane (decode_load<.., QUAD>): values 0..3 belong to the group's first half,
                4..7 to its second; each store is 16 contiguous bytes per lane */
@@ -308,8 +321,8 @@ __device__ __forceinline__ void decode_store(uint8_t* __restrict__ cout, const D
                 x[2 * k] = perm(hp[k], in.lo[k], 0x05040100u);
                 x[2 * k + 1] = perm(hp[k], in.lo[k], 0x07060302u);
             }
-            st_stream<u32x4>((cout + gstart * 4) + lane * 16u, u32x4{x[0], x[1], x[2], x[3]});
-            st_stream<u32x4>((cout + gstart * 4 + 2 * kGroup) + lane * 16u, u32x4{x[4], x[5], x[6], x[7]});
+            st_stream_a4((cout + gstart * 4) + lane * 16u, u32x4{x[0], x[1], x[2], x[3]});
+            st_stream_a4((cout + gstart * 4 + 2 * kGroup) + lane * 16u, u32x4{x[4], x[5], x[6], x[7]});
         }
     } else {
 #pragma unroll
@@ -382,9 +395,12 @@ void k_decompress(const DecompressArgs a)
     const uint8_t* __restrict__ slot = a.comp + a.tab.slot_off[c];
     uint8_t* __restrict__ cout = a.out + a.tab.elem_off[c] * ES;
     const SlotLayout L = slot_layout(n, DT);
-    const bool fast = (ts + kTile <= n) && ((reinterpret_cast<uintptr_t>(cout) & 15u) == 0);
+    /* whole tiles take the vector path; a chunk of the tensor starts at some element of it, so its bytes are
+       dword-aligned or (bf16, odd element) skewed by one halfword */
+    const bool fast = ts + kTile <= n;
+    const bool skew = (reinterpret_cast<uintptr_t>(cout) & 2u) != 0;
     const uint32_t lane = lane_id();
-    const uint32_t wave = threadIdx.x >> 6;   /* left in a vector register: measured faster here than scalar addressing */
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   /* scalar: group addresses and index entries stay out of the vector registers */
     const uint64_t ng = (n + kGroup - 1) / kGroup;
 
     /* What does not depend on the header or on IDX goes out first (the static part is readable: the host
@@ -443,7 +459,8 @@ void k_decompress(const DecompressArgs a)
         }
 #pragma unroll
         for (uint32_t u = 0; u < kGroupsPerWave; ++u) {
-            decode_store<DT, true>(cout, in[u], es[u], ts + (uint64_t)(u * kWavesPerBlock + wave) * kGroup, e0, lane, s_tab);
+            decode_store<DT, true>(cout, in[u], es[u], ts + (uint64_t)(u * kWavesPerBlock + wave) * kGroup, e0, lane, s_tab,
+                                   DT == ZIPCCL_BF16 && skew);
             bad |= es[u].bad;
         }
     } else {
@@ -636,15 +653,15 @@ __device__ __forceinline__ void reduce_stages(const ReduceArgs& a, const SlotLay
             if (FAST) {
                 if (ODT == ZIPCCL_FP32) {
                     /* 32 contiguous bytes per lane: plain stores (streaming ones are slow on this pattern) */
-                    *reinterpret_cast<u32x4*>(og + lane * 32u) = u32x4{__float_as_uint(acc[0]), __float_as_uint(acc[1]),
+                    *reinterpret_cast<u32x4_a4*>(og + lane * 32u) = u32x4{__float_as_uint(acc[0]), __float_as_uint(acc[1]),
                                                                        __float_as_uint(acc[2]), __float_as_uint(acc[3])};
-                    *reinterpret_cast<u32x4*>((og + 16) + lane * 32u) = u32x4{__float_as_uint(acc[4]), __float_as_uint(acc[5]),
+                    *reinterpret_cast<u32x4_a4*>((og + 16) + lane * 32u) = u32x4{__float_as_uint(acc[4]), __float_as_uint(acc[5]),
                                                                               __float_as_uint(acc[6]), __float_as_uint(acc[7])};
                 } else {
                     uint32_t o[4];
 #pragma unroll
                     for (int k = 0; k < 4; ++k) o[k] = f32_to_bf16_bits(acc[2 * k]) | (f32_to_bf16_bits(acc[2 * k + 1]) << 16);
-                    st_stream<u32x4>(og + lane * 16u, u32x4{o[0], o[1], o[2], o[3]});
+                    st_stream_a4(og + lane * 16u, u32x4{o[0], o[1], o[2], o[3]});
                 }
             } else {
 #pragma unroll
@@ -694,7 +711,7 @@ __device__ __forceinline__ void reduce_stages(const ReduceArgs& a, const SlotLay
 /*
  * a.gpw = groups per wave: the larger, the fewer workgroups pay for the header checks and the table
  * build; 1 for small shards so that there are enough workgroups to fill the chip.  Dynamic LDS: one
- * 32-bit word per peer.  FAST: every group of the launch is complete and the output 16-byte aligned.
+ * 32-bit word per peer.  FAST: every group of the launch is complete and the output dword-aligned.
  */
 template <int DT, int ODT, bool FAST>
 __global__ __launch_bounds__(kThreads, !FAST ? 4 : DT == ZIPCCL_BF16 ? 8 : 6) void k_decompress_reduce(const ReduceArgs a)
@@ -787,10 +804,10 @@ int launch_decompress_reduce(int dt, int out_dt, const ReduceArgs& a, void* stre
     ReduceArgs b = a;
     b.gpw = a.n >= (uint64_t)kTile * 2048u ? kGroupsPerWave : 1u;
     const uint64_t per = (uint64_t)kGroup * kWavesPerBlock * b.gpw;
-    /* whole tiles with an aligned output go to the kernel without bounds checks, the rest (at most one
-       tile, or everything when the output is not 16-byte aligned) to the general one */
+    /* whole tiles with a dword-aligned output go to the kernel without bounds checks, the rest (at most one
+       tile, or everything when the output is only 2-byte aligned) to the general one */
     const size_t lds_bytes = sizeof(uint32_t) * a.n_peers;
-    const bool aligned = (reinterpret_cast<uintptr_t>(a.out) & 15u) == 0;
+    const bool aligned = (reinterpret_cast<uintptr_t>(a.out) & 3u) == 0;
     const uint64_t full = aligned ? a.n / per : 0;
     const uint64_t rest = a.n - full * per;
 #define ZIPCCL_REDUCE(FAST, GRID)                                                                                      \

@@ -15,11 +15,19 @@ typedef unsigned short us2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+/* 16 bytes at an address that is only known to be 4-byte aligned: a chunk of the caller's tensor may start
+ * at any element (the hardware takes multi-dword accesses at dword alignment; the type tells the compiler) */
+typedef u32x4 u32x4_a4 __attribute__((aligned(4)));
+typedef uint32_t u32x3 __attribute__((ext_vector_type(3)));
+typedef u32x3 u32x3_a4 __attribute__((aligned(4)));
+
 /* streaming accesses: every tensor byte is touched once, so keep it out of the way of the caches */
 template <typename T>
 __device__ __forceinline__ T ld_stream(const void* p) { return __builtin_nontemporal_load(static_cast<const T*>(p)); }
 template <typename T>
 __device__ __forceinline__ void st_stream(void* p, T v) { __builtin_nontemporal_store(v, static_cast<T*>(p)); }
+__device__ __forceinline__ u32x4 ld_stream_a4(const void* p) { return __builtin_nontemporal_load(static_cast<const u32x4_a4*>(p)); }
+__device__ __forceinline__ void st_stream_a4(void* p, u32x4 v) { __builtin_nontemporal_store(v, static_cast<u32x4_a4*>(p)); }
 
 __device__ __forceinline__ uint32_t pk_sub_u16(uint32_t a, uint32_t b)
 {

@@ -67,6 +67,21 @@ def test_ragged_chunks_with_empty_and_unaligned_starts(dtype, compress_path):
     check_parity(data, dtype, 0.5, len(ce), ce, label="ragged")
 
 
+@pytest.mark.parametrize("dtype", [z.BF16, z.FP32], ids=["bf16", "fp32"])
+def test_chunk_starts_of_every_alignment_with_whole_tiles(dtype, compress_path):
+    # chunk starts (in bf16 bytes) at 0, 4, 49168, 81936, 81944 and 114714: multiples of 16, of 8, of 4 and
+    # of 2 only, each followed by whole tiles (the vector path takes any dword-aligned start, the
+    # element-wise one the rest)
+    ce = np.array([2, 24582, 16384, 4, 16385, 24576], dtype=np.uint64)
+    n = int(ce.sum())
+    rng = np.random.default_rng(8)
+    f = rng.standard_normal(n, dtype=np.float32) * np.float32(0.5)
+    f[rng.integers(0, n, 3000)] *= np.float32(1e6)          # zero-points everywhere
+    data = W.f32_to_bf16_words(f) if dtype == z.BF16 else f.view(np.uint32).copy()
+    _say(f"[alignments] dtype={dtype} n={n} path={compress_path}")
+    check_parity(data, dtype, 0.5, len(ce), ce, label="alignments")
+
+
 def test_more_chunks_than_one_launch_holds(compress_path):
     rng = np.random.default_rng(8)
     ce = rng.integers(0, 3000, 300).astype(np.uint64)
