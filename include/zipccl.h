@@ -116,7 +116,7 @@ size_t zipccl_compress_min_workspace_size(size_t n_elems, zipccl_dtype_t dt, uin
 /*
  * Compress (section 4, second paragraph; kernel steps of section 4.2).
  *   d_in            device, n_elems values of dtype dt, aligned to the element size
- *                   (16-byte aligned chunk starts take the vector-load path)
+ *                   (whole tiles of 8192 values take the vector path wherever the chunk starts)
  *   table           host, from zipccl_build_table
  *   d_out           device, 128-byte aligned, out_capacity >= zipccl_max_compressed_size(...)
  *   d_chunk_bytes   device, n_chunks u64, may be NULL: bytes to transmit for each chunk

@@ -3,7 +3,8 @@
  *
  * compress   : paper section 4 (split, 3-bit code, zero-points) with the kernel steps of
  *              section 4.2 re-designed for wave64: one wave handles a group of 512 values,
- *              8 consecutive values per lane (one 16-byte load for bf16), a workgroup of
+ *              8 values per lane (consecutive: one 16-byte load for bf16; whole fp32 groups: two
+ *              quads, one from each half of the group, one 16-byte load each), a workgroup of
  *              4 waves handles a tile of 16 groups.  Per lane the work is SWAR on packed
  *              words: v_perm_b32 gathers the sign/mantissa and exponent bytes, packed 16-bit
  *              sub/min produce the codes, v_dot4_u32_u8 transposes code bits into plane bytes.
@@ -14,8 +15,9 @@
  *              with a block-level atomic add inside the kernel, is a kernel boundary here.
  *              k_compress<kModeStash> writes everything whose place is known (SM, LO, planes,
  *              tile-local index) and parks the zero-point exponents of its tile in a stash;
- *              k_tile_scan turns the per-tile counts into per-chunk prefixes; k_place moves
- *              each tile's exponents to their final place and finishes index and header.
+ *              the per-tile counts become per-chunk prefixes inside k_place (chunks of up to
+ *              kPlaceScanTiles tiles) or in k_tile_scan; k_place moves each tile's exponents
+ *              to their final place and finishes index and header.
  *              (Waiting in-kernel for the predecessors' counts costs a tile ~10 us of lateness
  *              of the slowest of them, measured; the stash costs ~5 % extra traffic.)
  * Everything here is integer work.

@@ -2,9 +2,10 @@
  * Decompress side of libzipccl.so for gfx950 (CDNA4, wave64): k_decompress (paper section 4, third
  * paragraph) and k_decompress_reduce (decode + local FP32 reduction of the zipped Reduce-Scatter,
  * sections 3.3 and 5.2).  No workgroup depends on another.  Work decomposition as on the compress side:
- * a wave owns a group of 512 values at a time, 8 consecutive values per lane; decoding is SWAR on packed
- * bytes (table-driven bit spread, v_perm_b32 / v_bfi_b32 recombination) with a DPP wave scan to
- * locate each lane's zero-point exponents.
+ * a wave owns a group of 512 values at a time, 8 values per lane (consecutive ones; for whole fp32 groups
+ * two quads, one from each half of the group, so that every tensor access is 16 contiguous bytes per
+ * lane); decoding is SWAR on packed bytes (table-driven bit spread, v_perm_b32 / v_bfi_b32
+ * recombination) with a DPP wave scan to locate each lane's zero-point exponents.
  */
 #include "zipccl_device.h"
 
