@@ -161,3 +161,51 @@ def test_reduce_into_an_output_that_is_only_element_aligned_and_empty_input():
     z.zipccl_decompress_reduce(empty, d_out, 0, z.BF16, 2, z.FP32, d_st)
     torch.cuda.synchronize()
     assert int(d_st.item()) == 0 and not d_out.cpu().numpy().any()
+
+
+def test_estimate_compress_reduce_chain_replays_inside_a_hip_graph():
+    """Table estimate -> compress with the device table -> fused reduce only launch kernels (no allocation,
+    memset or synchronisation), so the chain can be captured; every replay, on fresh input contents and with
+    the program's own eager work in between, must equal the oracle's chain."""
+    from oracle import sigma as osg
+    P, n = 4, 5 * 8192 + 300                                  # P peer slices = P equal chunks of one tensor
+    d_in = torch.zeros(P * n, dtype=torch.int16, device=DEV)
+    cap = z.zipccl_max_compressed_size(P * n, z.BF16, P)
+    d_comp = torch.empty(cap, dtype=torch.uint8, device=DEV)
+    d_ws = torch.empty(z.zipccl_compress_workspace_size(P * n, z.BF16, P), dtype=torch.uint8, device=DEV)
+    d_ews = torch.empty(z.zipccl_estimate_workspace_size(), dtype=torch.uint8, device=DEV)
+    d_tab = torch.zeros(8, dtype=torch.uint8, device=DEV)
+    d_sum = torch.zeros(n, dtype=torch.int32, device=DEV)
+    d_st = torch.zeros(1, dtype=torch.int32, device=DEV)
+
+    def chain():
+        z.zipccl_estimate_table(d_in, P * n, z.BF16, d_tab, None, d_ews)
+        z.zipccl_compress_device_table(d_in, P * n, z.BF16, P, None, d_tab, d_comp, None, d_ws)
+        z.zipccl_decompress_reduce(d_comp, d_sum, n, z.BF16, P, z.FP32, d_st)
+
+    rng = np.random.default_rng(11)
+    first = W.f32_to_bf16_words(rng.standard_normal(P * n, dtype=np.float32) * np.float32(0.3))
+    d_in.copy_(torch.from_numpy(first.view(np.int16)))
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                              # warm-up outside the capture
+        chain()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        chain()
+    for rep in range(3):
+        data = W.f32_to_bf16_words(rng.standard_normal(P * n, dtype=np.float32) * np.float32(0.01 * 7 ** rep))
+        d_in.copy_(torch.from_numpy(data.view(np.int16)))      # eager work between replays
+        d_comp.fill_(0xA5)
+        d_sum.fill_(0x3C3C3C3C)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        dec, _ = osg.estimate_table(data, z.BF16)
+        assert list(d_tab.cpu().numpy()) == list(dec), rep
+        ref, ref_cb, off = oracle.compress(data, z.BF16, dec, P)
+        want = oracle.decompress_reduce(ref, n, z.BF16, P, z.FP32)
+        assert int(d_st.item()) == 0
+        assert np.array_equal(d_sum.cpu().numpy().view(np.uint32), want), rep
