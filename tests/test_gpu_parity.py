@@ -42,7 +42,7 @@ def test_workload_parity_small(name, scale, compress_path):
 
 
 EDGE_N = [0, 1, 7, 8, 9, 63, 64, 127, 128, 129, 511, 512, 513, 1023, 4095, 4096, 4097, 8191, 8192, 8193,
-          16384, 16389, 40000]
+          16383, 16384, 16385, 16389, 32767, 32768, 32769, 40000]
 
 
 @pytest.mark.parametrize("dtype", [z.BF16, z.FP32], ids=["bf16", "fp32"])
