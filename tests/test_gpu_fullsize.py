@@ -41,3 +41,49 @@ def test_fullsize_parity(name):
         assert np.array_equal(got[s:e], ref[s:e]), f"chunk {c} differs"
     ratio = w.nbytes / float(ref_cb.sum())
     print(f"[full] {w.name} ratio {ratio:.4f}", flush=True)
+
+
+@pytest.mark.parametrize("dtype,n,sigma", [(z.BF16, 2 ** 32 - 1, 0.02), (z.FP32, 2 ** 31 + 4097, 0.5)],
+                         ids=["bf16_max_chunk", "fp32_sections_past_4GiB"])
+def test_one_chunk_of_the_largest_sizes(dtype, n, sigma):
+    """A single chunk of ZIPCCL_MAX_CHUNK_ELEMS bf16 values (524288 tiles, 2^23 IDX entries, > 2^27 zero-points)
+    and an fp32 chunk whose sections start past 4 GiB inside the slot: 64-bit offsets everywhere.  The input
+    repeats a random block (generating 2^32 samples would take minutes); both compress paths."""
+    rng = np.random.default_rng(123 + dtype)
+    if dtype == z.BF16:
+        blk = W.f32_to_bf16_words(rng.standard_normal(2 ** 26, dtype=np.float32) * np.float32(sigma))
+        blk[::1000] = 0x7F80
+    else:
+        blk = (rng.standard_normal(2 ** 25, dtype=np.float32) * np.float32(sigma)).view(np.uint32).copy()
+        blk[::777] = 0x7F800000
+    data = np.tile(blk, n // blk.size + 1)[:n].copy()
+    data[-5:] = [0x0000, 0x8000, 0x7FC1, 0x3F80, 0xFF80] if dtype == z.BF16 else [0, 1 << 31, 0x7FC00001, 0x3F800000, 0xFF800000]
+    print(f"[huge] dtype={dtype} n={n}: oracle compress", flush=True)
+    ref, ref_cb, off = oracle.compress(data, dtype, oracle.build_table(sigma), 1, None)
+    cb = int(ref_cb[0])
+    d_in = to_device_words(data)
+    cap = z.zipccl_max_compressed_size(n, dtype, 1)
+    assert cap == int(off[-1])
+    d_out = torch.empty(cap, dtype=torch.uint8, device=DEV)
+    d_cb = torch.zeros(1, dtype=torch.int64, device=DEV)
+    d_ws = torch.empty(z.zipccl_compress_workspace_size(n, dtype, 1), dtype=torch.uint8, device=DEV)
+    d_back = torch.empty_like(d_in)
+    d_st = torch.zeros(1, dtype=torch.int32, device=DEV)
+    try:
+        for path in (0, 1):
+            print(f"[huge] GPU compress path {path}", flush=True)
+            z.zipccl_debug_compress_path(path)
+            d_out.fill_(0xA5)
+            z.zipccl_compress(d_in, n, dtype, 1, None, z.zipccl_build_table(sigma, dtype), d_out, d_cb, d_ws)
+            torch.cuda.synchronize()
+            assert int(d_cb.item()) == cb
+            for a in range(0, cb, 1 << 30):
+                b = min(cb, a + (1 << 30))
+                assert np.array_equal(d_out[a:b].cpu().numpy(), ref[a:b]), f"compressed bytes differ in [{a}, {b})"
+            d_back.fill_(0)
+            z.zipccl_decompress(d_out, d_back, n, dtype, 1, None, d_st)
+            torch.cuda.synchronize()
+            assert int(d_st.item()) == 0
+            assert torch.equal(d_back, d_in), "GPU round trip differs"
+    finally:
+        z.zipccl_debug_compress_path(0)
