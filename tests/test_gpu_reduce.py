@@ -209,3 +209,39 @@ def test_estimate_compress_reduce_chain_replays_inside_a_hip_graph():
         want = oracle.decompress_reduce(ref, n, z.BF16, P, z.FP32)
         assert int(d_st.item()) == 0
         assert np.array_equal(d_sum.cpu().numpy().view(np.uint32), want), rep
+
+
+def test_reduce_of_the_largest_peer_count_with_rejected_slots_in_every_round():
+    """1024 slots (the limit): headers are checked 256 at a time, the accepted ones listed in slot order;
+    a rejected slot in each of those rounds (and two side by side) must only drop out of the sum."""
+    rng = np.random.default_rng(12)
+    P, n = 1024, 700
+    peers = _peers(rng, P, n, z.BF16, [0.02, 0.3])
+    buf = _receive_buffer(peers, z.BF16, [0.02, 0.3])
+    cap1 = z.zipccl_max_compressed_size(n, z.BF16, 1)
+    want_all = oracle.decompress_reduce(buf.cpu().numpy(), n, z.BF16, P, z.FP32)
+    d_out = torch.full((n,), 0x3C3C3C3C, dtype=torch.int32, device=DEV)
+    d_st = torch.zeros(1, dtype=torch.int32, device=DEV)
+    z.zipccl_decompress_reduce(buf, d_out, n, z.BF16, P, z.FP32, d_st)
+    torch.cuda.synchronize()
+    assert int(d_st.item()) == 0
+    assert np.array_equal(d_out.cpu().numpy().view(np.uint32), want_all)
+    victims = [0, 255, 256, 257, 600, 1023]
+    bad = buf.clone()
+    for v in victims:
+        bad[v * cap1 + 2] = 0x00                              # magic of that slot
+    rest = [peers[p] for p in range(P) if p not in victims]
+    sig = [[0.02, 0.3][p % 2] for p in range(P) if p not in victims]
+    # the remaining slices, each with the table it had, as the oracle sees them
+    cbuf = torch.full((cap1 * len(rest),), 0xA5, dtype=torch.uint8, device=DEV)
+    ws = torch.empty(z.zipccl_compress_workspace_size(n, z.BF16, 1), dtype=torch.uint8, device=DEV)
+    for k, x in enumerate(rest):
+        z.zipccl_compress(torch.from_numpy(x.view(np.int16)).to(DEV), n, z.BF16, 1, None,
+                          z.zipccl_build_table(sig[k], z.BF16), cbuf[k * cap1:(k + 1) * cap1], None, ws)
+        torch.cuda.synchronize()
+    want = oracle.decompress_reduce(cbuf.cpu().numpy(), n, z.BF16, len(rest), z.FP32)
+    d_st.zero_()
+    z.zipccl_decompress_reduce(bad, d_out, n, z.BF16, P, z.FP32, d_st)
+    torch.cuda.synchronize()
+    assert int(d_st.item()) == 4
+    assert np.array_equal(d_out.cpu().numpy().view(np.uint32), want)
