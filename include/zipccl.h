@@ -181,7 +181,8 @@ zipccl_status_t zipccl_decompress(const void* d_comp, size_t comp_capacity,
  * received for its shard, back to back at the a-priori offsets of an equal split (slot p at
  * p * zipccl_max_compressed_size(n_elems, dt, 1, NULL)), n_elems values each; every slot may carry
  * its own table.  out[i] = ((x_0[i] + x_1[i]) + x_2[i]) + ... in FP32, peers in slot order, starting
- * from x_0[i] itself (bf16 inputs are widened exactly), so the result is reproducible bit for bit.
+ * from x_0[i] itself (bf16 inputs are widened exactly; a NaN input gives a quiet NaN even when it is
+ * the only slot), so the result is reproducible bit for bit.
  *   d_out    device, n_elems values of out_dt: ZIPCCL_FP32 = the sums, ZIPCCL_BF16 = the sums
  *            rounded to nearest even (NaN made quiet); aligned to its element size
  *   d_status as in zipccl_decompress; a corrupt slot is left out of the sum
