@@ -126,9 +126,20 @@ def run_reduce(w, peers, steps):
         evs[k][1].record(stream)
     torch.cuda.synchronize()
     ms = float(np.mean([e[0].elapsed_time(e[1]) for e in evs]))
+    # the same sums rounded to bf16 (what a gradient shard kept in bf16 would receive)
+    d_sum16 = torch.empty(n, dtype=torch.int16, device=dev)
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(steps)]
+    for k in range(steps):
+        evs[k][0].record(stream)
+        z.zipccl_decompress_reduce(d_comp, d_sum16, n, w.dtype, peers, z.BF16, d_st, stream=stream)
+        evs[k][1].record(stream)
+    torch.cuda.synchronize()
+    ms16 = float(np.mean([e[0].elapsed_time(e[1]) for e in evs]))
+    assert torch.equal(d_sum16.view(torch.bfloat16), d_sum.to(torch.bfloat16)), "bf16 output is not the rounded FP32 sum"
     comp_bytes = int(d_cb.sum().item())
     algo = comp_bytes + 4 * n
-    return {"peers": peers, "n_per_peer": n, "ms": round(ms, 4),
+    return {"peers": peers, "n_per_peer": n, "ms": round(ms, 4), "ms_bf16_out": round(ms16, 4),
+            "hbm_frac_bf16_out": round((comp_bytes + 2 * n) / (ms16 * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
             "uncompressed_in_GBps": round(w.nbytes / (ms * 1e-3) / 1e9, 1),
             "algorithmic_bytes": algo, "hbm_GBps": round(algo / (ms * 1e-3) / 1e9, 1),
             "hbm_frac": round(algo / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
