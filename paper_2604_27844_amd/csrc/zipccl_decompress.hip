@@ -653,11 +653,28 @@ __device__ __forceinline__ void reduce_stages(const ReduceArgs& a, const SlotLay
             uint8_t* __restrict__ og = a.out + (uint64_t)r.cur_g * kGroup * OES;
             if (FAST) {
                 if (ODT == ZIPCCL_FP32) {
-                    /* 32 contiguous bytes per lane: plain stores (streaming ones are slow on this pattern) */
-                    *reinterpret_cast<u32x4_a4*>(og + lane * 32u) = u32x4{__float_as_uint(acc[0]), __float_as_uint(acc[1]),
-                                                                       __float_as_uint(acc[2]), __float_as_uint(acc[3])};
-                    *reinterpret_cast<u32x4_a4*>((og + 16) + lane * 32u) = u32x4{__float_as_uint(acc[4]), __float_as_uint(acc[5]),
-                                                                              __float_as_uint(acc[6]), __float_as_uint(acc[7])};
+                    /* The lane's 8 sums are 32 contiguous bytes, a pattern that stores slowly.  Once per
+                       group they go through the wave's LDS region (free between decodes), half a group at
+                       a time, and come back as 16 contiguous bytes per lane: two streaming stores of 1 KiB. */
+                    const u32x4 lo4 = u32x4{__float_as_uint(acc[0]), __float_as_uint(acc[1]),
+                                            __float_as_uint(acc[2]), __float_as_uint(acc[3])};
+                    const u32x4 hi4 = u32x4{__float_as_uint(acc[4]), __float_as_uint(acc[5]),
+                                            __float_as_uint(acc[6]), __float_as_uint(acc[7])};
+                    u32x4 row[2];
+#pragma unroll
+                    for (uint32_t h = 0; h < 2; ++h) {
+                        if ((lane >> 5) == h) {
+                            *reinterpret_cast<u32x4*>(lds + (lane & 31u) * 32u) = lo4;
+                            *reinterpret_cast<u32x4*>(lds + (lane & 31u) * 32u + 16u) = hi4;
+                        }
+                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                        __builtin_amdgcn_wave_barrier();
+                        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                        row[h] = *reinterpret_cast<const u32x4*>(lds + lane * 16u);
+                        __builtin_amdgcn_wave_barrier();
+                    }
+                    st_stream_a4(og + lane * 16u, row[0]);
+                    st_stream_a4((og + 2 * kGroup) + lane * 16u, row[1]);
                 } else {
                     uint32_t o[4];
 #pragma unroll
@@ -720,7 +737,9 @@ __global__ __launch_bounds__(kThreads, !FAST ? 4 : DT == ZIPCCL_BF16 ? 8 : 6) vo
     extern __shared__ __attribute__((aligned(16))) uint8_t s_dyn[];
     uint32_t* s_peer = reinterpret_cast<uint32_t*>(s_dyn);     /* the accepted slots, in slot order */
     __shared__ DecTables s_tab;
-    __shared__ __attribute__((aligned(16))) uint8_t s_esc[kWavesPerBlock][kEscRegion];
+    /* per wave: the zero-point slice of the group being decoded, or half a group of FP32 sums on their way out */
+    constexpr uint32_t kRegion = kEscRegion > 1024u ? kEscRegion : 1024u;
+    __shared__ __attribute__((aligned(16))) uint8_t s_esc[kWavesPerBlock][kRegion];
     __shared__ uint32_t s_wcnt[kWavesPerBlock];
     build_tables(s_tab);
 
