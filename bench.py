@@ -127,7 +127,8 @@ def run_reduce(w, peers, steps):
         z.zipccl_decompress_reduce(d_comp, d_sum, n, w.dtype, peers, z.FP32, d_st, stream=stream)
         evs[k][1].record(stream)
     torch.cuda.synchronize()
-    ms = float(np.median([e[0].elapsed_time(e[1]) for e in evs]))
+    ts = [e[0].elapsed_time(e[1]) for e in evs]
+    ms, ms_min = float(np.median(ts)), float(min(ts))
     # the same sums rounded to bf16 (what a gradient shard kept in bf16 would receive)
     d_sum16 = torch.empty(n, dtype=torch.int16, device=dev)
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(steps)]
@@ -136,11 +137,14 @@ def run_reduce(w, peers, steps):
         z.zipccl_decompress_reduce(d_comp, d_sum16, n, w.dtype, peers, z.BF16, d_st, stream=stream)
         evs[k][1].record(stream)
     torch.cuda.synchronize()
-    ms16 = float(np.median([e[0].elapsed_time(e[1]) for e in evs]))
+    ts = [e[0].elapsed_time(e[1]) for e in evs]
+    ms16, ms16_min = float(np.median(ts)), float(min(ts))
     assert torch.equal(d_sum16.view(torch.bfloat16), d_sum.to(torch.bfloat16)), "bf16 output is not the rounded FP32 sum"
     comp_bytes = int(d_cb.sum().item())
     algo = comp_bytes + 4 * n
-    return {"peers": peers, "n_per_peer": n, "ms": round(ms, 4), "ms_bf16_out": round(ms16, 4), "timing": "median of the timed calls",
+    return {"peers": peers, "n_per_peer": n, "ms": round(ms, 4), "ms_min": round(ms_min, 4), "ms_bf16_out": round(ms16, 4),
+            "ms_bf16_out_min": round(ms16_min, 4),
+            "timing": "calls back to back: median and fastest; the core clock drops under sustained load and this kernel follows it",
             "hbm_frac_bf16_out": round((comp_bytes + 2 * n) / (ms16 * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
             "uncompressed_in_GBps": round(w.nbytes / (ms * 1e-3) / 1e9, 1),
             "algorithmic_bytes": algo, "hbm_GBps": round(algo / (ms * 1e-3) / 1e9, 1),
