@@ -117,11 +117,13 @@ def run_reduce(w, peers, steps):
     peers' contributions to one shard."""
     import torch
     import paper_2604_27844_amd.binding as z
-    if w.dtype != z.BF16 or w.n_elems % peers:
+    if w.n_elems % peers:
         return None
     dev = torch.device("cuda:0")
     n = w.n_elems // peers
-    d_in = torch.from_numpy(w.data.view(np.int16)).to(dev)
+    bf16 = w.dtype == z.BF16
+    d_in = torch.from_numpy(w.data.view(np.int16 if bf16 else np.int32)).to(dev)
+    as_f32 = (lambda t: t.view(torch.bfloat16).float()) if bf16 else (lambda t: t.view(torch.float32))
     table = z.zipccl_build_table(w.sigma, w.dtype)
     cap = z.zipccl_max_compressed_size(w.n_elems, w.dtype, peers)
     d_comp = torch.empty(cap, dtype=torch.uint8, device=dev)
@@ -134,9 +136,9 @@ def run_reduce(w, peers, steps):
     z.zipccl_decompress_reduce(d_comp, d_sum, n, w.dtype, peers, z.FP32, d_st, stream=stream)
     torch.cuda.synchronize()
     assert int(d_st.item()) == 0
-    ref = d_in[:n].view(torch.bfloat16).float()
+    ref = as_f32(d_in[:n]).clone()
     for p in range(1, peers):
-        ref = ref + d_in[p * n:(p + 1) * n].view(torch.bfloat16).float()
+        ref = ref + as_f32(d_in[p * n:(p + 1) * n])
     assert torch.equal(ref.view(torch.int32), d_sum.view(torch.int32)), "fused reduce differs from peer-ordered FP32 sum"
     del ref
     d_sum16 = torch.empty(n, dtype=torch.int16, device=dev)
