@@ -301,12 +301,9 @@ int zo_decompress(const void* comp, uint64_t comp_capacity, void* out, uint64_t 
     return ZO_OK;
 }
 
-/* fp32 -> bf16, round to nearest even; NaN keeps its sign and top payload bits and is made quiet. */
-static uint16_t f32_to_bf16_rne(float f)
+/* fp32 bits (not a NaN: the caller has replaced those) -> bf16, round to nearest even */
+static uint16_t f32_bits_to_bf16_rne(uint32_t u)
 {
-    uint32_t u;
-    memcpy(&u, &f, 4);
-    if ((u & 0x7F800000u) == 0x7F800000u && (u & 0x007FFFFFu)) return (uint16_t)((u >> 16) | 0x0040u);
     u += 0x7FFFu + ((u >> 16) & 1u);
     return (uint16_t)(u >> 16);
 }
@@ -314,10 +311,15 @@ static uint16_t f32_to_bf16_rne(float f)
 /*
  * Section 3.3 / 5.2: local reduction after a zipped All-to-All.  comp holds n_peers slots of n
  * elements each, back to back at their a-priori offsets (what a rank's receive buffer looks
- * like); out[i] = ((x_0[i] + x_1[i]) + x_2[i]) + ... in FP32, peers in order, starting from
- * x_0[i] itself.  bf16 inputs are widened exactly.  out_dtype ZO_FP32 writes floats, ZO_BF16
- * writes the FP32 sum rounded to nearest even.  scratch holds one decoded slice (n elements
- * of the input dtype).
+ * like).  The paper says "in FP32" and nothing more; the definition taken here:
+ *   acc = -0.0f;  for p = 0 .. n_peers-1 (slot order):  acc = acc + x_p[i]   (FP32, round to nearest even)
+ * -0 is the identity of FP32 addition for everything that is not a NaN (-0 + x = x, signed zeros
+ * included), so out[i] = ((x_0[i] + x_1[i]) + x_2[i]) + ... and a single peer is widened exactly.
+ * IEEE 754 leaves open which payload and sign a NaN result carries (the NaN that Inf - Inf produces
+ * differs in sign between x86 and CDNA), so a sum that is a NaN is stored as the one quiet NaN
+ * 0x7FC00000: the result is then the same bits on every machine.
+ * bf16 inputs are widened exactly.  out_dtype ZO_FP32 writes the sums, ZO_BF16 the sums rounded to
+ * nearest even (the NaN becomes 0x7FC0).  scratch holds one decoded slice (n elements of the input dtype).
  */
 int zo_decompress_reduce(const void* comp, uint64_t comp_capacity, void* out, uint64_t n, int dtype,
                          uint32_t n_peers, int out_dtype, void* scratch, float* acc)
@@ -341,12 +343,16 @@ int zo_decompress_reduce(const void* comp, uint64_t comp_capacity, void* out, ui
             else bits = ((const uint32_t*)scratch)[i];
             float x;
             memcpy(&x, &bits, 4);
-            acc[i] = p == 0 ? x : acc[i] + x;
+            if (p == 0) acc[i] = -0.0f;
+            acc[i] = acc[i] + x;
         }
     }
     for (uint64_t i = 0; i < n; ++i) {
-        if (out_dtype == ZO_FP32) ((float*)out)[i] = acc[i];
-        else ((uint16_t*)out)[i] = f32_to_bf16_rne(acc[i]);
+        uint32_t bits;
+        memcpy(&bits, &acc[i], 4);
+        if (isnan(acc[i])) bits = 0x7FC00000u;
+        if (out_dtype == ZO_FP32) ((uint32_t*)out)[i] = bits;
+        else ((uint16_t*)out)[i] = f32_bits_to_bf16_rne(bits);
     }
     return ZO_OK;
 }

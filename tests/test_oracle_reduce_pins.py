@@ -20,10 +20,33 @@ def _bf16(vals):
 
 
 def test_single_peer_is_exact_widening_including_signed_zero():
+    """Every bf16 pattern that is not a NaN comes back widened bit for bit (-0 stays -0, subnormals and
+    infinities survive: -0 is the identity of the FP32 addition); every NaN comes back as 0x7FC00000."""
     x = np.arange(65536, dtype=np.uint16)
-    x = x[((x >> 7) & 0xFF) != 0xFF]                      # finite values only
     got = oracle.decompress_reduce(_pack([x], BF16), x.size, BF16, 1)
-    assert np.array_equal(got, x.astype(np.uint32) << 16)   # -0 stays -0, subnormals survive
+    nan = (((x >> 7) & 0xFF) == 0xFF) & ((x & 0x7F) != 0)
+    assert nan.sum() == 254
+    assert np.array_equal(got[~nan], x[~nan].astype(np.uint32) << 16)
+    assert np.all(got[nan] == 0x7FC00000)
+    got16 = oracle.decompress_reduce(_pack([x], BF16), x.size, BF16, 1, BF16)
+    assert np.array_equal(got16[~nan], x[~nan]) and np.all(got16[nan] == 0x7FC0)
+
+
+def test_nan_sums_are_the_canonical_quiet_nan_whatever_produced_them():
+    """Hand values.  A signalling NaN (0x7F800001) alone, a negative quiet NaN with payload, Inf - Inf, and a
+    NaN met after finite terms all give 0x7FC00000 (bf16 output: 0x7FC0); signed zeros follow IEEE 754:
+    (-0) + (-0) = -0, (+0) + (-0) = +0."""
+    inf, ninf = 0x7F800000, 0xFF800000
+    cases = [([0x7F800001], 0x7FC00000), ([0xFFC12345], 0x7FC00000), ([inf, ninf], 0x7FC00000),
+             ([0x3F800000, 0x40000000, 0xFFFFFFFF], 0x7FC00000), ([0x7FC00001, 0x3F800000], 0x7FC00000),
+             ([inf, inf], inf), ([0x80000000, 0x80000000], 0x80000000), ([0x00000000, 0x80000000], 0x00000000),
+             ([0x80000000], 0x80000000), ([0x00000001, 0x00000001], 0x00000002)]
+    for words, want in cases:
+        peers = [np.array([w], dtype=np.uint32) for w in words]
+        got = oracle.decompress_reduce(_pack(peers, FP32), 1, FP32, len(peers))
+        assert got[0] == want, (words, hex(int(got[0])))
+        got16 = oracle.decompress_reduce(_pack(peers, FP32), 1, FP32, len(peers), BF16)
+        assert got16[0] == want >> 16, (words, hex(int(got16[0])))      # each sum is a bf16 value or rounds to zero
 
 
 def test_small_integers_sum_exactly():
