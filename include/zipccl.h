@@ -180,11 +180,13 @@ zipccl_status_t zipccl_decompress(const void* d_comp, size_t comp_capacity,
  * fixes FP32 for the local reduction of BF16 traffic).  d_comp holds the n_peers slots a rank has
  * received for its shard, back to back at the a-priori offsets of an equal split (slot p at
  * p * zipccl_max_compressed_size(n_elems, dt, 1, NULL)), n_elems values each; every slot may carry
- * its own table.  out[i] = ((x_0[i] + x_1[i]) + x_2[i]) + ... in FP32, peers in slot order, starting
- * from x_0[i] itself (bf16 inputs are widened exactly; a NaN input gives a quiet NaN even when it is
- * the only slot), so the result is reproducible bit for bit.
+ * its own table.  acc = -0.0f, then acc = acc + x_p[i] for every slot p in slot order, in FP32 with round to
+ * nearest even: -0 is the identity of that addition for everything that is not a NaN, so
+ * out[i] = ((x_0[i] + x_1[i]) + x_2[i]) + ... and a single slot is widened exactly (signed zeros, subnormals
+ * and infinities included).  A sum that is a NaN is stored as the quiet NaN 0x7FC00000 whatever produced it
+ * (IEEE 754 leaves payload and sign of a NaN result open), so the result is reproducible bit for bit.
  *   d_out    device, n_elems values of out_dt: ZIPCCL_FP32 = the sums, ZIPCCL_BF16 = the sums
- *            rounded to nearest even (NaN made quiet); aligned to its element size
+ *            rounded to nearest even (the NaN becomes 0x7FC0); aligned to its element size
  *   d_status as in zipccl_decompress; a corrupt slot is left out of the sum
  * comp_capacity must cover the static part of every slot; 1 <= n_peers <= 1024.
  * Asynchronous on `stream`.

@@ -487,12 +487,17 @@ void k_decompress(const DecompressArgs a)
     if (bad && a.status) atomicOr(a.status, (uint32_t)ZIPCCL_ERR_CORRUPT);
 }
 
-/* fp32 bits -> bf16 bits, round to nearest even; NaN keeps sign and top payload bits and is made quiet */
-__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
+/* The bits a sum is stored as: a NaN sum becomes the one quiet NaN 0x7FC00000 (which payload and sign a NaN
+ * result carries is left to the implementation by IEEE 754; this makes the output the same bits everywhere). */
+__device__ __forceinline__ uint32_t sum_bits(float f)
 {
-    const uint32_t u = __float_as_uint(f);
-    const bool nan = (u & 0x7F800000u) == 0x7F800000u && (u & 0x007FFFFFu) != 0u;
-    return nan ? ((u >> 16) | 0x0040u) : ((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+    return f != f ? 0x7FC00000u : __float_as_uint(f);
+}
+
+/* fp32 bits (from sum_bits: no NaN other than 0x7FC00000, which this maps to 0x7FC0) -> bf16 bits, round to nearest even */
+__device__ __forceinline__ uint32_t f32_bits_to_bf16_bits(uint32_t u)
+{
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
 }
 
 /* A 32-bit load through the constant address space: for a wave-uniform address the compiler issues it
@@ -531,7 +536,8 @@ struct StageBuf {
  * the loads of stage k + 1 are in flight and the index entries of stage k + 2 have been requested.
  * Every stage issues the same number of loads, so that a wait for the older ones never has to drain
  * the younger ones; past the last stage the look-ahead repeats the last stage's requests.
- * The sum starts at -0.0f, which every first value x turns into x itself.
+ * The sum starts at -0.0f, the identity of FP32 addition for everything that is not a NaN, and one
+ * addition per accepted slot follows; a NaN sum is stored as 0x7FC00000 (sum_bits).
  */
 template <int DT, int ODT, bool FAST>
 __device__ __forceinline__ void reduce_stages(const ReduceArgs& a, const SlotLayout& L, uint64_t gs0, uint32_t n_groups,
@@ -665,10 +671,8 @@ __device__ __forceinline__ void reduce_stages(const ReduceArgs& a, const SlotLay
                     /* The lane's 8 sums are 32 contiguous bytes, a pattern that stores slowly.  Once per
                        group they go through the wave's LDS region (free between decodes), half a group at
                        a time, and come back as 16 contiguous bytes per lane: two streaming stores of 1 KiB. */
-                    const u32x4 lo4 = u32x4{__float_as_uint(acc[0]), __float_as_uint(acc[1]),
-                                            __float_as_uint(acc[2]), __float_as_uint(acc[3])};
-                    const u32x4 hi4 = u32x4{__float_as_uint(acc[4]), __float_as_uint(acc[5]),
-                                            __float_as_uint(acc[6]), __float_as_uint(acc[7])};
+                    const u32x4 lo4 = u32x4{sum_bits(acc[0]), sum_bits(acc[1]), sum_bits(acc[2]), sum_bits(acc[3])};
+                    const u32x4 hi4 = u32x4{sum_bits(acc[4]), sum_bits(acc[5]), sum_bits(acc[6]), sum_bits(acc[7])};
                     u32x4 row[2];
 #pragma unroll
                     for (uint32_t h = 0; h < 2; ++h) {
@@ -687,7 +691,8 @@ __device__ __forceinline__ void reduce_stages(const ReduceArgs& a, const SlotLay
                 } else {
                     uint32_t o[4];
 #pragma unroll
-                    for (int k = 0; k < 4; ++k) o[k] = f32_to_bf16_bits(acc[2 * k]) | (f32_to_bf16_bits(acc[2 * k + 1]) << 16);
+                    for (int k = 0; k < 4; ++k)
+                        o[k] = f32_bits_to_bf16_bits(sum_bits(acc[2 * k])) | (f32_bits_to_bf16_bits(sum_bits(acc[2 * k + 1])) << 16);
                     st_stream_a4(og + lane * 16u, u32x4{o[0], o[1], o[2], o[3]});
                 }
             } else {
@@ -695,8 +700,8 @@ __device__ __forceinline__ void reduce_stages(const ReduceArgs& a, const SlotLay
                 for (int j = 0; j < 8; ++j) {
                     if ((r.in.vmask >> j) & 1u) {
                         const uint64_t i = lane * kLaneElems + j;
-                        if (ODT == ZIPCCL_FP32) *reinterpret_cast<float*>(og + i * 4) = acc[j];
-                        else *reinterpret_cast<uint16_t*>(og + i * 2) = (uint16_t)f32_to_bf16_bits(acc[j]);
+                        if (ODT == ZIPCCL_FP32) *reinterpret_cast<uint32_t*>(og + i * 4) = sum_bits(acc[j]);
+                        else *reinterpret_cast<uint16_t*>(og + i * 2) = (uint16_t)f32_bits_to_bf16_bits(sum_bits(acc[j]));
                     }
                 }
             }
