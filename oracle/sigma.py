@@ -30,3 +30,38 @@ def estimate_table(words, dtype):
     if not (s > 0.0) or not np.isfinite(s):
         return np.array([0, 1, 2, 3, 4, 5, 6, 7], dtype=np.uint8), s
     return zo.build_table(s), s
+
+
+# Phi^-1(3/4): the median of |w| for w ~ N(0, sigma^2) is sigma times this
+PHI_INV_3_4 = 0.6744897501960817
+
+
+def robust_sigma(words, dtype):
+    """A sigma for Eq.5 that a few large entries cannot move (the tensors the paper feeds to section 4.1 are
+    zero-mean Gaussians; activations with outlier channels or a parameter shard that also holds LayerNorm
+    gains are not, and one part in twenty of such entries multiplies the sample standard deviation by ten).
+
+    For w ~ N(0, sigma^2) half of the |w| lie below sigma * Phi^-1(3/4), so
+        sigma = median(|w|) / Phi^-1(3/4).
+    The median is taken over the magnitudes of the high 16-bit words (the bf16 value itself; an fp32 value
+    truncated to its bf16 prefix, which is the part the exponent code works on), as integers: rank
+    floor((K - 1) / 2) of the K magnitudes that are neither zero nor Inf/NaN (a zero is not a sample of the
+    Gaussian and is a zero-point under every window).  That makes the estimate a count, exact and the same in
+    any order of summation.  K = 0 gives NaN."""
+    w = np.ascontiguousarray(words).reshape(-1)
+    hi = w if dtype == zo.BF16 else (w >> np.uint32(16))
+    mag = (hi & 0x7FFF).astype(np.uint16)
+    mag = mag[(mag != 0) & (mag < 0x7F80)]
+    if mag.size == 0:
+        return float("nan")
+    med = np.sort(mag)[(mag.size - 1) // 2]
+    value = (np.array([med], dtype=np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)[0]
+    return float(value / PHI_INV_3_4)
+
+
+def robust_table(words, dtype):
+    """Table for robust_sigma (Eq.5 / Eq.2); no usable magnitude at all falls back to the lowest window."""
+    s = robust_sigma(words, dtype)
+    if not (s > 0.0) or not np.isfinite(s):
+        return np.array([0, 1, 2, 3, 4, 5, 6, 7], dtype=np.uint8), s
+    return zo.build_table(s), s

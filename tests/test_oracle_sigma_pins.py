@@ -48,3 +48,93 @@ def test_table_from_estimate_and_fallbacks():
                 np.array([0x3F80, 0x7F80, 0x3F80], dtype=np.uint16), np.array([0x7FC0, 0, 0], dtype=np.uint16)):
         dec, s = osg.estimate_table(bad, BF16)
         assert list(dec) == [0, 1, 2, 3, 4, 5, 6, 7]
+
+
+# ---- robust sigma: median of the magnitudes / Phi^-1(3/4) ----
+
+def _f32w(a):
+    return np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+
+
+def test_robust_constant_is_the_normal_quartile():
+    from scipy.special import ndtri, erf
+    assert osg.PHI_INV_3_4 == pytest.approx(float(ndtri(0.75)), rel=1e-15)
+    assert float(erf(osg.PHI_INV_3_4 / math.sqrt(2.0))) == pytest.approx(0.5, abs=1e-15)   # P(|w| < c sigma) = 1/2
+
+
+def test_robust_hand_values_and_rank():
+    c = osg.PHI_INV_3_4
+    # lower median: rank (K - 1) // 2 of the sorted magnitudes; sign is ignored; every value here is a bf16 value
+    assert osg.robust_sigma(_f32w([3.0, -1.0, 2.0, 4.0]), FP32) == 2.0 / c
+    assert osg.robust_sigma(_f32w([3.0, -1.0, 2.0, 4.0, 8.0]), FP32) == 3.0 / c
+    assert osg.robust_sigma(_f32w([-5.0]), FP32) == 5.0 / c
+    assert osg.robust_sigma(W.f32_to_bf16_words(np.array([3.0, -1.0, 2.0, 4.0], dtype=np.float32)), BF16) == 2.0 / c
+    # zeros, infinities and NaN are left out: [0, -0, 1, 2, 3, inf, nan] -> median of [1, 2, 3]
+    x = np.array([0x0000, 0x8000, 0x3F80, 0x4000, 0x4040, 0x7F80, 0xFFC1], dtype=np.uint16)
+    assert osg.robust_sigma(x, BF16) == 2.0 / c
+    # an fp32 value counts with its bf16 prefix (truncated, not rounded): 1.99999 -> 1.9921875
+    assert osg.robust_sigma(_f32w([1.99999]), FP32) == 1.9921875 / c
+    # subnormals take part
+    assert osg.robust_sigma(np.array([0x0001, 0x0002, 0x0003], dtype=np.uint16), BF16) == 2 * 2.0 ** -133 / c
+    for nothing in (np.zeros(0, np.uint16), np.zeros(9, np.uint16), np.array([0x7F80, 0xFF80, 0x7FC0], np.uint16)):
+        assert math.isnan(osg.robust_sigma(nothing, BF16))
+        assert list(osg.robust_table(nothing, BF16)[0]) == [0, 1, 2, 3, 4, 5, 6, 7]
+
+
+def test_robust_median_agrees_with_numpy_median_for_odd_counts():
+    rng = np.random.default_rng(5)
+    for n in (1, 3, 101, 4097):
+        w = W.f32_to_bf16_words(rng.standard_normal(n, dtype=np.float32) * np.float32(0.3))
+        w = w[(w & 0x7FFF) != 0]
+        if w.size % 2 == 0:
+            w = w[1:]
+        mags = ((w & 0x7FFF).astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+        assert osg.robust_sigma(w, BF16) == float(np.median(mags)) / osg.PHI_INV_3_4
+
+
+def test_robust_on_clean_gaussians_is_sigma_within_sampling_error_and_scales_exactly():
+    rng = np.random.default_rng(6)
+    n = 1 << 18
+    f = rng.standard_normal(n, dtype=np.float32)
+    s1 = osg.robust_sigma(f.view(np.uint32), FP32)
+    # asymptotic sd of the median-based sigma: 1 / (2 f(q) sqrt(n)) / q with f the half-normal density at the
+    # quartile q, = 1.166 / sqrt(n); plus up to 2^-7 of truncation to the bf16 prefix
+    assert -2.0 ** -7 - 5 * 1.166 / math.sqrt(n) < s1 - 1.0 < 5 * 1.166 / math.sqrt(n)
+    for k in (-20, -3, 7):
+        assert osg.robust_sigma((f * np.float32(2.0 ** k)).view(np.uint32), FP32) == s1 * 2.0 ** k     # bit for bit
+    b = W.f32_to_bf16_words(f * np.float32(0.02))
+    assert abs(osg.robust_sigma(b, BF16) / 0.02 - 1.0) < 2.0 ** -8 + 5 * 1.166 / math.sqrt(n)
+
+
+def test_robust_ignores_what_poisons_the_sample_standard_deviation():
+    """The two workloads on which the sample standard deviation picks a worse window: the estimate must stay
+    within 10 % of the bulk sigma and choose the window of the nominal sigma."""
+    from scipy.special import ndtri
+    c5 = W.make("c5", 1 / 64)
+    s = osg.robust_sigma(c5.data, c5.dtype)
+    # closed form for the mixture: 5 % of the magnitudes sit near 1, so the median of all is the
+    # 0.5 / 0.95 quantile of the bulk's magnitudes
+    expect = 0.02 * float(ndtri(0.5 + 0.25 / 0.95)) / osg.PHI_INV_3_4
+    assert s == pytest.approx(expect, rel=0.01) and abs(s / 0.02 - 1) < 0.10
+    assert osg.estimate_sigma(c5.data, c5.dtype) > 0.2                      # ten times the bulk sigma
+    assert list(osg.robust_table(c5.data, c5.dtype)[0]) == list(oracle.build_table(0.02))
+    c2 = W.make("c2", 1 / 8)
+    s = osg.robust_sigma(c2.data, c2.dtype)
+    assert abs(s - 1.0) < 0.10 and osg.estimate_sigma(c2.data, c2.dtype) > 2.0
+    assert list(osg.robust_table(c2.data, c2.dtype)[0]) == list(oracle.build_table(1.0))
+    c5f = W.make("c5_fp32", 1 / 32)
+    assert list(osg.robust_table(c5f.data, c5f.dtype)[0]) == list(oracle.build_table(0.02))
+    # ratio with the estimated table within 1 % of the ratio with the nominal one
+    for w in (c5, c2, c5f):
+        nominal = oracle.compress(w.data, w.dtype, oracle.build_table(w.sigma), w.n_chunks, w.chunk_elems)[1].sum()
+        robust = oracle.compress(w.data, w.dtype, osg.robust_table(w.data, w.dtype)[0], w.n_chunks, w.chunk_elems)[1].sum()
+        assert abs(float(robust) / float(nominal) - 1.0) < 0.01
+
+
+def test_robust_table_on_every_workload_is_the_nominal_one_or_better():
+    for name, scale in (("c1", 1.0), ("c3", 1 / 32), ("c4", 1 / 64)):
+        w = W.make(name, scale)
+        dec, s = osg.robust_table(w.data, w.dtype)
+        nominal = oracle.compress(w.data, w.dtype, oracle.build_table(w.sigma), w.n_chunks, w.chunk_elems)[1].sum()
+        robust = oracle.compress(w.data, w.dtype, dec, w.n_chunks, w.chunk_elems)[1].sum()
+        assert float(robust) <= float(nominal) * 1.01, (name, s, list(dec))
