@@ -2,11 +2,13 @@
 """Benchmark of the ZipCCL codec hot path on one MI355X.
 
 A step = one compress + one decompress of the whole workload (all peer chunks), inputs
-resident in HBM.  Prints ONE JSON line: round-trip throughput in uncompressed GB/s, the
-per-direction rates and compression ratio, the HBM roofline of the dominant kernel measured
-live with events on the launch stream, and the CPU oracle timed on the host cores.
+resident in HBM.  Prints ONE JSON line: round-trip throughput in uncompressed GB/s for the
+headline workload (c5, the largest), the per-direction rates and compression ratio, the HBM
+roofline of the dominant kernel measured live with events on the launch stream, the CPU oracle
+timed on the host cores, the legs built next to the codec (fused reduce, sigma estimates), and the
+same codec figures for every other workload (`other_workloads`).
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c5] [--all]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c5] [--no-others] [--no-cpu]
 """
 import argparse
 import json
@@ -25,6 +27,8 @@ KERNELS = {"compress": "zipccl_compress = k_compress + k_place (one call, two la
            "decompress": "zipccl_decompress = k_decompress"}
 PAPER_CONTEXT = ("paper (64x RTX A6000, 200 Gb/s): communication time -1.35x, end-to-end training 1.18x; "
                  "it prints no codec GB/s, so vs_baseline is null")
+OTHERS = ("c3", "c4", "c5", "c5_fp32", "c2", "c1")
+CACHE_RESIDENT = ("c1", "c2")      # 2 MiB and 32 MiB: they fit the 256 MB last-level cache and are launch-bound
 
 
 def log(msg):
@@ -51,9 +55,14 @@ def warm_up(step, warmup):
     return done
 
 
+def frac(nbytes, ms):
+    return round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)
+
+
 def run_gpu(w, steps, warmup):
     import torch
     import paper_2604_27844_amd.binding as z
+    from paper_2604_27844_amd.yardstick import zipccl_yardstick_copy
 
     dev = torch.device("cuda:0")
     signed = np.int16 if w.dtype == z.BF16 else np.int32
@@ -103,12 +112,12 @@ def run_gpu(w, steps, warmup):
     cevs = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(5)]
     for k in range(5):
         cevs[k][0].record(stream)
-        z.zipccl_debug_copy(d_back, d_in, half, stream=stream)
+        zipccl_yardstick_copy(d_back, d_in, half, stream=stream)
         cevs[k][1].record(stream)
     torch.cuda.synchronize()
     copy_ms = float(np.median([e[0].elapsed_time(e[1]) for e in cevs]))
     return dict(wall_s=wall, tc_ms=tc, td_ms=td, comp_bytes=comp_bytes, copy_GBps=2 * half / (copy_ms * 1e-3) / 1e9,
-                d_out=d_out, d_cb=d_cb, table=table, warm=warm)
+                d_in=d_in, d_out=d_out, d_cb=d_cb, d_ws=d_ws, table=table, warm=warm)
 
 
 def run_reduce(w, peers, steps):
@@ -166,37 +175,57 @@ def run_reduce(w, peers, steps):
     return {"peers": peers, "n_per_peer": n, "ms": round(ms, 4), "ms_min": round(ms_min, 4), "ms_bf16_out": round(ms16, 4),
             "ms_bf16_out_min": round(ms16_min, 4),
             "timing": "calls back to back after 80 ms of the same load: median and fastest",
-            "hbm_frac_bf16_out": round((comp_bytes + 2 * n) / (ms16 * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+            "hbm_frac_bf16_out": frac(comp_bytes + 2 * n, ms16),
             "uncompressed_in_GBps": round(w.nbytes / (ms * 1e-3) / 1e9, 1),
             "algorithmic_bytes": algo, "hbm_GBps": round(algo / (ms * 1e-3) / 1e9, 1),
-            "hbm_frac": round(algo / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+            "hbm_frac": frac(algo, ms),
             "checked": "bit-equal to the peer-ordered FP32 sum of the inputs"}
 
 
-def run_estimate(w, steps):
-    """sigma / table from the data on the device (zipccl_estimate_table): one read of the tensor."""
+def run_estimate(w, r, steps):
+    """sigma / table from the data on the device, one read of the tensor each: the sample standard deviation
+    (zipccl_estimate_table, what section 4.1 names) and the median-based sigma (zipccl_estimate_table_robust);
+    and the compression ratio each table gives on this workload next to the nominal-sigma table's.
+    steps = 0: no timing."""
     import torch
     import paper_2604_27844_amd.binding as z
     dev = torch.device("cuda:0")
-    d_in = torch.from_numpy(w.data.view(np.int16 if w.dtype == z.BF16 else np.int32)).to(dev)
+    d_in, d_out, d_cb, d_ws = r["d_in"], r["d_out"], r["d_cb"], r["d_ws"]
     d_tab = torch.zeros(8, dtype=torch.uint8, device=dev)
     d_sig = torch.zeros(1, dtype=torch.float64, device=dev)
-    d_ws = torch.empty(z.zipccl_estimate_workspace_size(), dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream()
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(steps)]
-    warm_up(lambda: z.zipccl_estimate_table(d_in, w.n_elems, w.dtype, d_tab, d_sig, d_ws, stream=stream), 1)
-    for k in range(steps):
-        evs[k][0].record(stream)
-        z.zipccl_estimate_table(d_in, w.n_elems, w.dtype, d_tab, d_sig, d_ws, stream=stream)
-        evs[k][1].record(stream)
-    torch.cuda.synchronize()
-    ms = float(np.mean([e[0].elapsed_time(e[1]) for e in evs]))
-    return {"ms": round(ms, 4), "sigma": float(d_sig.item()), "dec1": int(d_tab[1].item()),
-            "hbm_GBps": round(w.nbytes / (ms * 1e-3) / 1e9, 1),
-            "hbm_frac": round(w.nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
+    out = {"ratio_with_nominal_sigma_table": round(w.nbytes / r["comp_bytes"], 5), "nominal_sigma": w.sigma,
+           "nominal_dec1": int(r["table"].dec[1])}
+    legs = (("sample_std", z.zipccl_estimate_table, z.zipccl_estimate_workspace_size()),
+            ("robust_median", z.zipccl_estimate_table_robust, z.zipccl_estimate_robust_workspace_size()))
+    for name, fn, ws_bytes in legs:
+        d_ews = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+        call = lambda: fn(d_in, w.n_elems, w.dtype, d_tab, d_sig, d_ews, stream=stream)
+        leg = {}
+        if steps:
+            evs = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(steps)]
+            warm_up(call, 1)
+            for k in range(steps):
+                evs[k][0].record(stream)
+                call()
+                evs[k][1].record(stream)
+            torch.cuda.synchronize()
+            ts = [e[0].elapsed_time(e[1]) for e in evs]
+            ms = float(np.median(ts))
+            leg.update({"ms": round(ms, 4), "ms_min": round(float(min(ts)), 4),
+                        "hbm_GBps": round(w.nbytes / (ms * 1e-3) / 1e9, 1), "hbm_frac": frac(w.nbytes, ms)})
+        else:
+            call()
+        z.zipccl_compress_device_table(d_in, w.n_elems, w.dtype, w.n_chunks, w.chunk_elems, d_tab, d_out, d_cb, d_ws,
+                                       stream=stream)
+        torch.cuda.synchronize()
+        leg.update({"sigma": float(d_sig.item()), "dec1": int(d_tab[1].item()),
+                    "ratio_with_estimated_table": round(w.nbytes / int(d_cb.sum().item()), 5)})
+        out[name] = leg
+    return out
 
 
-def run_oracle(w, gpu_out=None, gpu_cb=None):
+def run_oracle(w, gpu_out=None, gpu_cb=None, parallel=True):
     """The oracle as it stands: single thread over the whole workload, then one chunk per host thread."""
     import oracle
     dec = oracle.build_table(w.sigma)
@@ -212,26 +241,47 @@ def run_oracle(w, gpu_out=None, gpu_cb=None):
         for c in range(0, w.n_chunks, max(1, w.n_chunks // 8)):    # sampled slots, byte for byte
             s, e = int(off[c]), int(off[c]) + int(ref_cb[c])
             same = same and bool(np.array_equal(gpu_out[s:e], ref[s:e]))
-    # chunk-parallel: every peer slice is independent
-    cores = len(os.sched_getaffinity(0))
-    ce = w.chunk_elems if w.chunk_elems is not None else np.full(w.n_chunks, w.n_elems // w.n_chunks, dtype=np.uint64)
-    starts = np.concatenate([[0], np.cumsum(ce)]).astype(np.int64)
-
-    def one(c):
-        x = w.data[starts[c]:starts[c + 1]]
-        o, cb, _ = oracle.compress(x, w.dtype, dec)
-        oracle.decompress(o, x.size, w.dtype)
-
-    threads = min(cores, w.n_chunks)
-    t3 = time.perf_counter()
-    with ThreadPoolExecutor(threads) as ex:
-        list(ex.map(one, range(w.n_chunks)))
-    t4 = time.perf_counter()
     gb = w.nbytes / 1e9
-    return dict(single=dict(compress_GBps=gb / (t1 - t0), decompress_GBps=gb / (t2 - t1),
-                            roundtrip_GBps=gb / (t2 - t0)),
-                parallel=dict(roundtrip_GBps=gb / (t4 - t3), threads=threads),
-                ratio=w.nbytes / float(ref_cb.sum()), matches_gpu=same, host_cores=cores)
+    cores = len(os.sched_getaffinity(0))
+    res = dict(single=dict(compress_GBps=gb / (t1 - t0), decompress_GBps=gb / (t2 - t1), roundtrip_GBps=gb / (t2 - t0)),
+               ratio=w.nbytes / float(ref_cb.sum()), matches_gpu=same, host_cores=cores)
+    if parallel:
+        # chunk-parallel: every peer slice is independent
+        ce = w.chunk_elems if w.chunk_elems is not None else np.full(w.n_chunks, w.n_elems // w.n_chunks, dtype=np.uint64)
+        starts = np.concatenate([[0], np.cumsum(ce)]).astype(np.int64)
+
+        def one(c):
+            x = w.data[starts[c]:starts[c + 1]]
+            o, cb, _ = oracle.compress(x, w.dtype, dec)
+            oracle.decompress(o, x.size, w.dtype)
+
+        threads = min(cores, w.n_chunks)
+        t3 = time.perf_counter()
+        with ThreadPoolExecutor(threads) as ex:
+            list(ex.map(one, range(w.n_chunks)))
+        t4 = time.perf_counter()
+        res["parallel"] = dict(roundtrip_GBps=gb / (t4 - t3), threads=threads)
+    return res
+
+
+def codec_entry(w, r, with_oracle):
+    """The per-workload figures of `other_workloads`: both directions, median and fastest call, against that
+    workload's own algorithmic bytes."""
+    tc, td = float(np.median(r["tc_ms"])), float(np.median(r["td_ms"]))
+    ab = w.nbytes + r["comp_bytes"]
+    e = {"MiB": round(w.nbytes / 2**20, 1), "n_chunks": w.n_chunks, "ragged": w.chunk_elems is not None,
+         "dtype": "u16" if w.dtype == 0 else "u32",
+         "compress_ms": round(tc, 4), "compress_ms_min": round(float(r["tc_ms"].min()), 4),
+         "decompress_ms": round(td, 4), "decompress_ms_min": round(float(r["td_ms"].min()), 4),
+         "compress_GBps": round(w.nbytes / 1e9 / (tc * 1e-3), 2), "decompress_GBps": round(w.nbytes / 1e9 / (td * 1e-3), 2),
+         "algorithmic_bytes_per_call": ab, "compress_frac": frac(ab, tc), "decompress_frac": frac(ab, td),
+         "copy_kernel_frac": round(r["copy_GBps"] / HBM_PEAK_GBPS, 4),
+         "compression_ratio": round(w.nbytes / r["comp_bytes"], 5)}
+    if with_oracle:
+        o = run_oracle(w, r["d_out"].cpu().numpy(), r["d_cb"].cpu().numpy().astype(np.uint64), parallel=False)
+        e.update({"gpu_bytes_match_oracle": o["matches_gpu"], "oracle_ratio": round(o["ratio"], 5),
+                  "oracle_1thread_roundtrip_GBps": round(o["single"]["roundtrip_GBps"], 4)})
+    return e
 
 
 def main():
@@ -243,8 +293,9 @@ def main():
     ap.add_argument("--settle-ms", type=float, default=SETTLE_S * 1e3, help="minimum duration of every warm-up (counter runs: 0)")
     ap.add_argument("--workload", default="c5", help="c1|c2|c3|c4|c5|c5_fp32 (default: c5, the largest)")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (parity/debug only)")
-    ap.add_argument("--all", action="store_true", help="also time the other >=256 MB workloads (extra object)")
-    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--no-others", action="store_true", help="only the headline workload (profiling runs)")
+    ap.add_argument("--all", action="store_true", help="accepted for compatibility: every workload is timed by default")
+    ap.add_argument("--no-cpu", action="store_true", help="skip every oracle leg")
     ap.add_argument("--chunks", type=int, default=0, help="override the workload's chunk count with an equal split")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -265,6 +316,7 @@ def main():
     r = run_gpu(w, args.steps, args.warmup)
     gb = w.nbytes / 1e9
     tc, td = float(r["tc_ms"].mean()), float(r["td_ms"].mean())
+    tc_med, td_med = float(np.median(r["tc_ms"])), float(np.median(r["td_ms"]))
     ms_per_step = r["wall_s"] * 1e3 / args.steps
     algo_bytes = w.nbytes + r["comp_bytes"]       # each direction reads one side and writes the other
     dominant = "compress" if tc >= td else "decompress"
@@ -283,15 +335,21 @@ def main():
         "dtype": "u16" if w.dtype == 0 else "u32", "data": "synthetic",
         "config": {"workload": w.name, "n_elems": w.n_elems, "elem_bytes": es, "n_chunks": w.n_chunks,
                    "ragged": w.chunk_elems is not None, "table_sigma": w.sigma, "group": 512, "scale": args.scale},
-        "compress_GBps": round(gb / (tc * 1e-3), 2), "decompress_GBps": round(gb / (td * 1e-3), 2),
-        "compress_ms": round(tc, 4), "decompress_ms": round(td, 4),
+        "compress_GBps": round(gb / (tc_med * 1e-3), 2), "decompress_GBps": round(gb / (td_med * 1e-3), 2),
+        "compress_ms": round(tc_med, 4), "decompress_ms": round(td_med, 4),
+        "compress_ms_mean": round(tc, 4), "decompress_ms_mean": round(td, 4),
         "compress_ms_min": round(float(r["tc_ms"].min()), 4), "decompress_ms_min": round(float(r["td_ms"].min()), 4),
+        "timing": "event-timed calls on the launch stream; *_ms = median of the timed steps, *_ms_mean their mean, *_ms_min the fastest",
         "compression_ratio": round(w.nbytes / r["comp_bytes"], 5),
         "roofline": {"bound": "hbm", "kernel": KERNELS[dominant], "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                     "achieved_from": "algorithmic bytes per call / mean event-timed duration of the slower call",
+                     "traffic": traffic,
+                     "traffic_source": "profiles/hbm_traffic.json (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an earlier run "
+                                       "of this command, summarised in profiles/; not measured in this run)",
                      "algorithmic_bytes_per_launch": algo_bytes,
-                     "compress_frac": round(algo_bytes / (tc * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
-                     "decompress_frac": round(algo_bytes / (td * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                     "compress_frac": frac(algo_bytes, tc), "decompress_frac": frac(algo_bytes, td),
+                     "compress_frac_median": frac(algo_bytes, tc_med), "decompress_frac_median": frac(algo_bytes, td_med),
                      "copy_kernel_GBps": round(r["copy_GBps"], 1)},
         "paper_context": PAPER_CONTEXT,
     }
@@ -310,32 +368,34 @@ def main():
                                              "how": "one peer chunk per host thread"},
                                "host_cores": o["host_cores"], "ratio": round(o["ratio"], 5),
                                "gpu_bytes_match_oracle": o["matches_gpu"]}
+    log("sigma estimates")
+    out["estimate_table"] = run_estimate(w, r, max(3, args.steps // 2))
     del r
     torch.cuda.empty_cache()
+    log("fused reduce")
     red = run_reduce(w, 8, max(3, args.steps))
     if red:
         out["decompress_reduce"] = red
-    out["estimate_table"] = run_estimate(w, max(3, args.steps // 2))
 
-    if args.all:
+    if not args.no_others:
         extra = {}
-        for name in ("c3", "c4", "c5", "c5_fp32", "c2", "c1"):
+        for name in OTHERS:
             if name == args.workload:
                 continue
-            log(f"extra workload {name}")
+            log(f"workload {name}")
             w2 = workloads.make(name, args.scale)
             r2 = run_gpu(w2, args.steps, args.warmup)
-            tc2, td2 = float(r2["tc_ms"].mean()), float(r2["td_ms"].mean())
-            ab = w2.nbytes + r2["comp_bytes"]
-            extra[w2.name] = {"MiB": round(w2.nbytes / 2**20, 1),
-                              "compress_GBps": round(w2.nbytes / 1e9 / (tc2 * 1e-3), 2),
-                              "decompress_GBps": round(w2.nbytes / 1e9 / (td2 * 1e-3), 2),
-                              "compress_hbm_frac": round(ab / (tc2 * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
-                              "decompress_hbm_frac": round(ab / (td2 * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
-                              "compression_ratio": round(w2.nbytes / r2["comp_bytes"], 5)}
+            e = codec_entry(w2, r2, not args.no_cpu)
+            if name in CACHE_RESIDENT:
+                e["cache_resident"] = True          # launch-bound: outside the >= 256 MB target
+            e["estimate_table"] = run_estimate(w2, r2, 0)
+            extra[w2.name] = e
             del r2, w2
             torch.cuda.empty_cache()
         out["other_workloads"] = extra
+        big = [v for v in extra.values() if not v.get("cache_resident")]
+        out["min_frac_over_256MB_workloads"] = min([out["roofline"]["compress_frac_median"], out["roofline"]["decompress_frac_median"]] +
+                                                  [x for v in big for x in (v["compress_frac"], v["decompress_frac"])])
 
     print(json.dumps(out), flush=True)
 

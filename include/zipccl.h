@@ -106,7 +106,8 @@ zipccl_status_t zipccl_chunk_static_bytes(size_t n_elems, zipccl_dtype_t dt, uin
 /* Bytes of device scratch for zipccl_compress.  With zipccl_compress_workspace_size bytes
  * (about one byte per element) compress reads the input once: zero-point exponents are parked
  * in the scratch until the per-chunk prefix of section 4.2.3 is known.  With less, but at least
- * zipccl_compress_min_workspace_size bytes (8 bytes per 8192 elements), it reads the input twice.
+ * zipccl_compress_min_workspace_size bytes (8 bytes per 8192 elements), it reads the input twice
+ * (count, prefix, emit): workspace_bytes alone selects the form, call by call, and both write the same bytes.
  * Both return 0 on invalid arguments. */
 size_t zipccl_compress_workspace_size(size_t n_elems, zipccl_dtype_t dt, uint32_t n_chunks,
                                       const uint64_t* chunk_elems);
@@ -150,6 +151,24 @@ size_t zipccl_estimate_workspace_size(void);
 zipccl_status_t zipccl_estimate_table(const void* d_in, size_t n_elems, zipccl_dtype_t dt,
                                       zipccl_table_t* d_table, double* d_sigma,
                                       void* d_workspace, size_t workspace_bytes, void* stream);
+/*
+ * The same with a sigma that a few large entries cannot move.  Section 4.1 derives the window for a
+ * zero-mean Gaussian; activations with outlier channels, or a parameter shard that also holds LayerNorm
+ * gains, inflate the sample standard deviation many times over and push the window off the bulk of the
+ * values.  For w ~ N(0, sigma^2) the median of |w| is sigma * Phi^-1(3/4), so
+ *     sigma = median(|w|) / 0.6744897501960817,
+ * the median taken over the 15-bit magnitudes of the values' high 16-bit words (the bf16 value; the bf16
+ * prefix of an fp32 value), as integers: rank floor((K - 1) / 2) of the K magnitudes that are neither zero
+ * nor Inf/NaN.  K = 0 selects the lowest window (sigma NaN).  The window then follows from Eq.5 / Eq.2 as in
+ * zipccl_build_table.  One pass over the tensor; the result is exact (a count) whatever the order of work.
+ *   d_workspace  device, 8-byte aligned, >= zipccl_estimate_robust_workspace_size() bytes (256 KiB);
+ *                contents are overwritten
+ * n_elems must be below 2^40.  Other arguments as for zipccl_estimate_table.
+ */
+size_t zipccl_estimate_robust_workspace_size(void);
+zipccl_status_t zipccl_estimate_table_robust(const void* d_in, size_t n_elems, zipccl_dtype_t dt,
+                                             zipccl_table_t* d_table, double* d_sigma,
+                                             void* d_workspace, size_t workspace_bytes, void* stream);
 zipccl_status_t zipccl_compress_device_table(const void* d_in, size_t n_elems, zipccl_dtype_t dt,
                                              uint32_t n_chunks, const uint64_t* chunk_elems,
                                              const zipccl_table_t* d_table,
@@ -214,23 +233,6 @@ zipccl_status_t zipccl_fit_link_model(const double* d_bytes, const double* t_sec
                                       double* alpha, double* beta);
 
 const char* zipccl_status_string(zipccl_status_t s);
-
-/*
- * Diagnostic switch, process-wide: path = 0 (default) lets zipccl_compress use the single-pass
- * form when the workspace allows it, path = 1 forces the form that reads the input twice.
- * Both produce identical bytes.  The environment variable ZIPCCL_COMPRESS_PATH=3pass sets the
- * initial value to 1.  Returns the previous value; any other argument only queries.
- */
-int zipccl_debug_compress_path(int path);
-
-/*
- * Measurement yardstick: a plain device-to-device copy kernel (16 bytes per lane, one load and
- * one store per thread, the fastest plain form measured).  d_dst / d_src device, 16-byte
- * aligned, bytes a multiple of 16; asynchronous on `stream`.  The benchmark reports its rate
- * as the practical ceiling next to the HBM peak, and counter runs use it to scale
- * FETCH_SIZE / WRITE_SIZE readings.
- */
-zipccl_status_t zipccl_debug_copy(void* d_dst, const void* d_src, size_t bytes, void* stream);
 
 #ifdef __cplusplus
 }

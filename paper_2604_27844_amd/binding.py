@@ -39,7 +39,7 @@ def _load():
     path = lib_path()
     if not os.path.exists(path):
         # tests, smoke() and bench.py load what is built and build only if nothing is there
-        build_lib.build()
+        build_lib.build(lib=path)
     if not os.path.exists(path):
         raise ImportError(f"{path} is missing: run __graft_entry__.build() (hipcc, gfx950) first")
     lib = ctypes.CDLL(path)
@@ -67,10 +67,10 @@ def _load():
     lib.zipccl_estimate_table.argtypes = [vp, sz, i32, vp, vp, vp, sz, vp]
     lib.zipccl_decompress.restype = i32
     lib.zipccl_decompress.argtypes = [vp, sz, vp, sz, i32, u32, vp, vp, vp]
-    lib.zipccl_debug_copy.restype = i32
-    lib.zipccl_debug_copy.argtypes = [vp, vp, sz, vp]
-    lib.zipccl_debug_compress_path.restype = i32
-    lib.zipccl_debug_compress_path.argtypes = [i32]
+    lib.zipccl_estimate_robust_workspace_size.restype = sz
+    lib.zipccl_estimate_robust_workspace_size.argtypes = []
+    lib.zipccl_estimate_table_robust.restype = i32
+    lib.zipccl_estimate_table_robust.argtypes = [vp, sz, i32, vp, vp, vp, sz, vp]
     lib.zipccl_decompress_reduce.restype = i32
     lib.zipccl_decompress_reduce.argtypes = [vp, sz, vp, sz, i32, u32, i32, vp, vp]
     dp = ctypes.POINTER(ctypes.c_double)
@@ -89,7 +89,7 @@ EXPORTS = ("zipccl_build_table", "zipccl_max_compressed_size", "zipccl_chunk_slo
            "zipccl_compress_workspace_size", "zipccl_compress_min_workspace_size", "zipccl_compress", "zipccl_decompress", "zipccl_decompress_reduce", "zipccl_status_string",
            "zipccl_switch_prefers_zipped", "zipccl_fit_link_model",
            "zipccl_estimate_workspace_size", "zipccl_estimate_table", "zipccl_compress_device_table",
-           "zipccl_debug_compress_path", "zipccl_debug_copy")
+           "zipccl_estimate_robust_workspace_size", "zipccl_estimate_table_robust")
 
 
 def _host_u64(chunk_elems):
@@ -117,16 +117,6 @@ def _stream(stream):
 
 def zipccl_status_string(code):
     return _lib.zipccl_status_string(int(code)).decode()
-
-
-def zipccl_debug_compress_path(path=-1):
-    return int(_lib.zipccl_debug_compress_path(int(path)))
-
-
-def zipccl_debug_copy(d_dst, d_src, nbytes, stream=None):
-    rc = _lib.zipccl_debug_copy(_dptr(d_dst), _dptr(d_src), int(nbytes), _stream(stream))
-    if rc:
-        raise ZipcclError(rc, "zipccl_debug_copy")
 
 
 def zipccl_build_table(sigma, dt=BF16):
@@ -223,11 +213,24 @@ def zipccl_estimate_table(d_in, n_elems, dt, d_table, d_sigma, d_workspace, stre
         raise ZipcclError(rc, "zipccl_estimate_table")
 
 
+def zipccl_estimate_robust_workspace_size():
+    return int(_lib.zipccl_estimate_robust_workspace_size())
+
+
+def zipccl_estimate_table_robust(d_in, n_elems, dt, d_table, d_sigma, d_workspace, stream=None):
+    """As zipccl_estimate_table, with sigma = median of the magnitudes / Phi^-1(3/4)."""
+    wsb = d_workspace.numel() * d_workspace.element_size()
+    rc = _lib.zipccl_estimate_table_robust(_dptr(d_in), int(n_elems), dt, _dptr(d_table), _dptr(d_sigma),
+                                           _dptr(d_workspace), wsb, _stream(stream))
+    if rc:
+        raise ZipcclError(rc, "zipccl_estimate_table_robust")
+
+
 def zipccl_compress_device_table(d_in, n_elems, dt, n_chunks, chunk_elems, d_table, d_out, d_chunk_bytes,
-                                 d_workspace, stream=None):
+                                 d_workspace, stream=None, workspace_bytes=None):
     _keep, p = _host_u64(chunk_elems)
     cap = d_out.numel() * d_out.element_size()
-    wsb = d_workspace.numel() * d_workspace.element_size()
+    wsb = d_workspace.numel() * d_workspace.element_size() if workspace_bytes is None else int(workspace_bytes)
     rc = _lib.zipccl_compress_device_table(_dptr(d_in), int(n_elems), dt, int(n_chunks), p, _dptr(d_table),
                                            _dptr(d_out), cap, _dptr(d_chunk_bytes), _dptr(d_workspace), wsb,
                                            _stream(stream))

@@ -1,17 +1,47 @@
 /*
- * Auxiliary kernels of libzipccl.so: the sigma estimate / table choice on the device (paper section 4.1)
- * and the plain-copy yardstick used by the benchmark.
+ * Auxiliary kernels of libzipccl.so: the sigma estimates / table choice on the device (paper section 4.1).
  */
 #include "zipccl_device.h"
 
 namespace zipccl {
 namespace {
 
+/* The table for a given sigma by Eq.5 / Eq.2 (erf in FP64), exactly as the host builder does; a sigma that is
+ * not positive and finite selects the lowest window.  One thread. */
+__device__ void table_from_sigma(double sigma, uint8_t* table, double* sigma_out)
+{
+    uint32_t e0 = 1;
+    if (sigma > 0.0 && sigma < __longlong_as_double(0x7FF0000000000000ll)) {
+        const double x_opt = log2(sigma) + 0.5 * log2(14.0 * log(2.0) / 16383.0);     /* Eq.5 */
+        const int lo = (int)floor(x_opt), hi = (int)ceil(x_opt);
+        const double s2 = sigma * sqrt(2.0);
+        const double p_lo = erf(ldexp(1.0, lo + 7) / s2) - erf(ldexp(1.0, lo) / s2);    /* Eq.2 */
+        const double p_hi = erf(ldexp(1.0, hi + 7) / s2) - erf(ldexp(1.0, hi) / s2);
+        int e = (p_hi > p_lo ? hi : lo) + 127;
+        e = e < 1 ? 1 : (e > 248 ? 248 : e);
+        e0 = (uint32_t)e;
+    }
+    table[0] = 0;
+    for (uint32_t k = 1; k <= 7; ++k) table[k] = (uint8_t)(e0 + k - 1);
+    if (sigma_out) *sigma_out = sigma;
+}
+
+/* Value of element i as a double (bf16 widened exactly). */
+template <int DT>
+__device__ __forceinline__ double value_at(const uint8_t* in, uint64_t i)
+{
+    uint32_t bits;
+    if (DT == ZIPCCL_BF16) bits = (uint32_t)(*reinterpret_cast<const uint16_t*>(in + i * 2)) << 16;
+    else bits = *reinterpret_cast<const uint32_t*>(in + i * 4);
+    return (double)__uint_as_float(bits);
+}
+
 /*
  * sigma of a tensor as the paper takes it (section 4.1: torch.std = unbiased sample standard
- * deviation), in FP64: every workgroup writes its partial sum x and sum x^2; k_estimate_finish adds the
- * partials in a fixed order, forms sigma, and picks the window with Eq.5 / Eq.2 (erf in FP64),
- * exactly as the host builder does.  A sigma that is not positive and finite selects the lowest window.
+ * deviation), in FP64.  Sums are taken of d = x - pivot, the pivot being the tensor's first value (0 if that
+ * is not finite): sum d^2 - (sum d)^2 / N then cancels only as far as the pivot is from the mean, not as far
+ * as the mean is from zero.  Every workgroup writes its partial sums; k_estimate_finish adds the partials in a
+ * fixed order, forms sigma, and picks the window (table_from_sigma).
  */
 template <int DT>
 __global__ __launch_bounds__(kThreads) void k_moments(const MomentArgs a)
@@ -20,6 +50,8 @@ __global__ __launch_bounds__(kThreads) void k_moments(const MomentArgs a)
     constexpr uint32_t PER16 = 16u / ES;               /* values per 16-byte load */
     __shared__ double s_sum[kWavesPerBlock], s_sq[kWavesPerBlock];
     double sum = 0.0, sq = 0.0;
+    double pivot = a.n ? value_at<DT>(a.in, 0) : 0.0;
+    if (!(fabs(pivot) < __longlong_as_double(0x7FF0000000000000ll))) pivot = 0.0;
     const bool aligned = (reinterpret_cast<uintptr_t>(a.in) & 15u) == 0;
     const uint64_t n16 = aligned ? a.n / PER16 : 0;    /* 16-byte pieces handled with vector loads */
     for (uint64_t i = (uint64_t)blockIdx.x * kThreads + threadIdx.x; i < n16; i += (uint64_t)gridDim.x * kThreads) {
@@ -28,21 +60,18 @@ __global__ __launch_bounds__(kThreads) void k_moments(const MomentArgs a)
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             if (DT == ZIPCCL_BF16) {
-                const double x0 = (double)__uint_as_float(w[k] << 16), x1 = (double)__uint_as_float(w[k] & 0xFFFF0000u);
+                const double x0 = (double)__uint_as_float(w[k] << 16) - pivot, x1 = (double)__uint_as_float(w[k] & 0xFFFF0000u) - pivot;
                 sum += x0; sq += x0 * x0;
                 sum += x1; sq += x1 * x1;
             } else {
-                const double x = (double)__uint_as_float(w[k]);
+                const double x = (double)__uint_as_float(w[k]) - pivot;
                 sum += x; sq += x * x;
             }
         }
     }
     /* the tail (and everything, for a misaligned tensor) element by element */
     for (uint64_t i = n16 * PER16 + (uint64_t)blockIdx.x * kThreads + threadIdx.x; i < a.n; i += (uint64_t)gridDim.x * kThreads) {
-        uint32_t bits;
-        if (DT == ZIPCCL_BF16) bits = (uint32_t)(*reinterpret_cast<const uint16_t*>(a.in + i * 2)) << 16;
-        else bits = *reinterpret_cast<const uint32_t*>(a.in + i * 4);
-        const double x = (double)__uint_as_float(bits);
+        const double x = value_at<DT>(a.in, i) - pivot;
         sum += x; sq += x * x;
     }
     /* fixed-order reduction: lanes by butterfly, waves in order */
@@ -78,31 +107,114 @@ __global__ __launch_bounds__(kThreads) void k_estimate_finish(const MomentArgs a
     const double N = (double)a.n;
     double sigma = __longlong_as_double(0x7FF8000000000000ll);          /* NaN for fewer than two values */
     if (a.n >= 2) {
-        const double mean = s_sum[0] / N;
-        const double var = (s_sq[0] - N * mean * mean) / (N - 1.0);
+        const double var = (s_sq[0] - s_sum[0] * s_sum[0] / N) / (N - 1.0);      /* sums of x - pivot */
         sigma = sqrt(var > 0.0 ? var : (var == var ? 0.0 : var));
     }
-    uint32_t e0 = 1;
-    if (sigma > 0.0 && sigma < __longlong_as_double(0x7FF0000000000000ll)) {
-        const double x_opt = log2(sigma) + 0.5 * log2(14.0 * log(2.0) / 16383.0);     /* Eq.5 */
-        const int lo = (int)floor(x_opt), hi = (int)ceil(x_opt);
-        const double s2 = sigma * sqrt(2.0);
-        const double p_lo = erf(ldexp(1.0, lo + 7) / s2) - erf(ldexp(1.0, lo) / s2);    /* Eq.2 */
-        const double p_hi = erf(ldexp(1.0, hi + 7) / s2) - erf(ldexp(1.0, hi) / s2);
-        int e = (p_hi > p_lo ? hi : lo) + 127;
-        e = e < 1 ? 1 : (e > 248 ? 248 : e);
-        e0 = (uint32_t)e;
-    }
-    a.table[0] = 0;
-    for (uint32_t k = 1; k <= 7; ++k) a.table[k] = (uint8_t)(e0 + k - 1);
-    if (a.sigma) *a.sigma = sigma;
+    table_from_sigma(sigma, a.table, a.sigma);
 }
 
-/* Yardstick: plain copy, 16 bytes per lane, one load and one store per thread. */
-__global__ __launch_bounds__(kThreads) void k_copy(const u32x4* __restrict__ src, u32x4* __restrict__ dst, uint64_t n16)
+/*
+ * Robust sigma (for Eq.5 / Eq.2 when the tensor is not the zero-mean Gaussian of section 4.1: outlier
+ * channels, LayerNorm gains among matrix weights): the median of |w| over Phi^-1(3/4).  The median is taken
+ * over the 15-bit magnitudes of the values' high 16-bit words, so it is a count: k_magnitude_hist builds the
+ * histogram of all 32768 magnitudes (one workgroup per compute unit, the whole histogram in its LDS, one
+ * LDS atomic per value; nonzero bins are added to the 64-bit histogram in the workspace, which k_clear_hist
+ * zeroed), k_robust_finish finds the bin of rank (K - 1) / 2 among the K magnitudes that are neither zero nor
+ * Inf/NaN.  Integer work until the final division: the result does not depend on any order.
+ */
+constexpr uint32_t kMagBins = 32768;
+constexpr uint32_t kHistThreads = 1024;
+
+__global__ __launch_bounds__(kHistThreads) void k_clear_hist(unsigned long long* hist)
 {
-    const uint64_t i = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (i < n16) dst[i] = src[i];
+    hist[blockIdx.x * kHistThreads + threadIdx.x] = 0ull;
+}
+
+template <int DT>
+__global__ __launch_bounds__(kHistThreads) void k_magnitude_hist(const HistArgs a)
+{
+    constexpr uint32_t ES = DT == ZIPCCL_BF16 ? 2u : 4u;
+    constexpr uint32_t PER16 = 16u / ES;
+    __shared__ uint32_t s_hist[kMagBins];                  /* 128 KiB */
+    for (uint32_t i = threadIdx.x; i < kMagBins; i += kHistThreads) s_hist[i] = 0u;
+    __syncthreads();
+    const bool aligned = (reinterpret_cast<uintptr_t>(a.in) & 15u) == 0;
+    const uint64_t n16 = aligned ? a.n / PER16 : 0;
+    const uint64_t stride = (uint64_t)gridDim.x * kHistThreads;
+    auto count = [&](const u32x4& v) {
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            if (DT == ZIPCCL_BF16) atomicAdd(&s_hist[w[k] & 0x7FFFu], 1u);
+            atomicAdd(&s_hist[(w[k] >> 16) & 0x7FFFu], 1u);
+        }
+    };
+    uint64_t i = (uint64_t)blockIdx.x * kHistThreads + threadIdx.x;
+    for (; i + 3 * stride < n16; i += 4 * stride) {           /* four loads in flight per thread */
+        u32x4 v[4];
+#pragma unroll
+        for (uint32_t k = 0; k < 4; ++k) v[k] = ld_stream<u32x4>(a.in + (i + k * stride) * 16);
+#pragma unroll
+        for (uint32_t k = 0; k < 4; ++k) count(v[k]);
+    }
+    for (; i < n16; i += stride) count(ld_stream<u32x4>(a.in + i * 16));
+    /* the tail (and everything, for a misaligned tensor) element by element */
+    for (uint64_t e = n16 * PER16 + (uint64_t)blockIdx.x * kHistThreads + threadIdx.x; e < a.n; e += stride) {
+        const uint32_t hi = DT == ZIPCCL_BF16 ? *reinterpret_cast<const uint16_t*>(a.in + e * 2)
+                                              : *reinterpret_cast<const uint32_t*>(a.in + e * 4) >> 16;
+        atomicAdd(&s_hist[hi & 0x7FFFu], 1u);
+    }
+    __syncthreads();
+    for (uint32_t b = threadIdx.x; b < kMagBins; b += kHistThreads) {
+        const uint32_t c = s_hist[b];
+        if (c) atomicAdd(&a.hist[b], (unsigned long long)c);
+    }
+}
+
+__global__ __launch_bounds__(kHistThreads) void k_robust_finish(const HistArgs a)
+{
+    constexpr uint32_t kPer = kMagBins / kHistThreads;       /* 32 consecutive bins per thread */
+    constexpr uint32_t kFirstNonFinite = 0x7F80u;            /* magnitudes from here on are Inf / NaN */
+    __shared__ unsigned long long s_wave[kHistThreads / 64];
+    const uint32_t b0 = threadIdx.x * kPer;
+    unsigned long long mine = 0;
+    for (uint32_t k = 0; k < kPer; ++k) {
+        const uint32_t b = b0 + k;
+        if (b != 0u && b < kFirstNonFinite) mine += a.hist[b];
+    }
+    /* exclusive prefix over the threads: butterfly-free serial form, 16 waves */
+    unsigned long long inc = mine;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const unsigned long long up = __shfl_up(inc, d, 64);
+        if ((threadIdx.x & 63u) >= (uint32_t)d) inc += up;
+    }
+    if ((threadIdx.x & 63u) == 63u) s_wave[threadIdx.x >> 6] = inc;
+    __syncthreads();
+    unsigned long long before = 0, total = 0;
+    for (uint32_t w = 0; w < kHistThreads / 64; ++w) {
+        const unsigned long long c = s_wave[w];
+        before += w < (threadIdx.x >> 6) ? c : 0ull;
+        total += c;
+    }
+    const unsigned long long excl = before + inc - mine;
+    if (total == 0ull) {
+        if (threadIdx.x == 0) table_from_sigma(__longlong_as_double(0x7FF8000000000000ll), a.table, a.sigma);
+        return;
+    }
+    const unsigned long long rank = (total - 1ull) / 2ull;
+    if (rank < excl || rank >= excl + mine) return;          /* exactly one thread holds the rank */
+    unsigned long long run = excl;
+    for (uint32_t k = 0; k < kPer; ++k) {
+        const uint32_t b = b0 + k;
+        if (b == 0u || b >= kFirstNonFinite) continue;
+        run += a.hist[b];
+        if (rank < run) {
+            const double med = (double)__uint_as_float(b << 16);
+            table_from_sigma(med / 0.6744897501960817, a.table, a.sigma);     /* Phi^-1(3/4) */
+            return;
+        }
+    }
 }
 
 } // namespace
@@ -118,15 +230,16 @@ int launch_estimate(int dt, const MomentArgs& a, void* stream)
 }
 
 
-int launch_copy(void* d_dst, const void* d_src, uint64_t bytes, void* stream)
+int launch_estimate_robust(int dt, const HistArgs& a, void* stream)
 {
-    const uint64_t n16 = bytes / 16;
-    if (n16 == 0) return (int)hipSuccess;
-    const uint64_t blocks = (n16 + kThreads - 1) / kThreads;
-    hipLaunchKernelGGL(k_copy, dim3((uint32_t)blocks), dim3(kThreads), 0, (hipStream_t)stream,
-                       static_cast<const u32x4*>(d_src), static_cast<u32x4*>(d_dst), n16);
+    hipStream_t s = (hipStream_t)stream;
+    hipLaunchKernelGGL(k_clear_hist, dim3(kMagBins / kHistThreads), dim3(kHistThreads), 0, s, a.hist);
+    if (hipGetLastError() != hipSuccess) return 1;
+    if (dt == ZIPCCL_BF16) hipLaunchKernelGGL((k_magnitude_hist<ZIPCCL_BF16>), dim3(a.n_blocks), dim3(kHistThreads), 0, s, a);
+    else hipLaunchKernelGGL((k_magnitude_hist<ZIPCCL_FP32>), dim3(a.n_blocks), dim3(kHistThreads), 0, s, a);
+    if (hipGetLastError() != hipSuccess) return 1;
+    hipLaunchKernelGGL(k_robust_finish, dim3(1), dim3(kHistThreads), 0, s, a);
     return (int)hipGetLastError();
 }
-
 
 } // namespace zipccl

@@ -3,10 +3,8 @@
  * arithmetic for the chunked layout (section 4.2.1) and argument checking + launch logic
  * of compress / decompress.  No device memory is allocated here.
  */
-#include <atomic>
 #include <cmath>
 #include <cstdint>
-#include <cstdlib>
 #include <algorithm>
 #include <cstring>
 #include <vector>
@@ -59,7 +57,7 @@ bool table_ok(const zipccl_table_t* t)
 
 /* Fill the by-value chunk table of one launch covering chunks [c0, c0 + nb). */
 uint32_t fill_tab(ChunkTab& tab, const std::vector<uint64_t>& ce, const std::vector<uint64_t>& slot_off,
-                  uint32_t c0, uint32_t nb, int dt)
+                  uint32_t c0, uint32_t nb)
 {
     tab.n_chunks = nb;
     uint64_t eoff = 0;
@@ -76,7 +74,6 @@ uint32_t fill_tab(ChunkTab& tab, const std::vector<uint64_t>& ce, const std::vec
         tab.elem_off[i] = eoff;
         tab.slot_off[i] = slot_off[c0 + nb] - slot_off[c0];
     }
-    (void)dt;
     return tiles;
 }
 
@@ -103,16 +100,6 @@ WorkspacePlan plan_workspace(const std::vector<uint64_t>& ce, uint64_t n_elems)
     w.min_bytes = w.stash_off;
     w.full_bytes = w.stash_off + ((n_elems + kStashSlack + 15) & ~15ull);
     return w;
-}
-
-/* 0 = single pass with a stash, 1 = two passes over the input; see zipccl_debug_compress_path */
-std::atomic<int>& compress_path()
-{
-    static std::atomic<int> path([] {
-        const char* e = std::getenv("ZIPCCL_COMPRESS_PATH");
-        return (e && std::strcmp(e, "3pass") == 0) ? 1 : 0;
-    }());
-    return path;
 }
 
 } // namespace
@@ -221,7 +208,7 @@ zipccl_status_t compress_impl(const void* d_in, size_t n_elems, zipccl_dtype_t d
     if (wp.tiles > 0x7FFFFFFFull) return ZIPCCL_ERR_INVALID_ARG;
     if (wp.min_bytes > workspace_bytes) return ZIPCCL_ERR_BUFFER_TOO_SMALL;
     /* without room for the stash the input is read twice instead */
-    const bool stash = compress_path().load() == 0 && wp.full_bytes <= workspace_bytes;
+    const bool stash = wp.full_bytes <= workspace_bytes;
 
     CompressArgs a;
     std::memset(&a, 0, sizeof a);
@@ -236,7 +223,7 @@ zipccl_status_t compress_impl(const void* d_in, size_t n_elems, zipccl_dtype_t d
     uint8_t* const ws = static_cast<uint8_t*>(d_workspace);
     for (uint32_t c0 = 0; c0 < n_chunks; c0 += kMaxBatch) {
         const uint32_t nb = (n_chunks - c0) < kMaxBatch ? (n_chunks - c0) : kMaxBatch;
-        const uint32_t nt = fill_tab(a.tab, ce, slot_off, c0, nb, dt);
+        const uint32_t nt = fill_tab(a.tab, ce, slot_off, c0, nb);
         a.in = static_cast<const uint8_t*>(d_in) + elem_base * es;
         a.out = static_cast<uint8_t*>(d_out) + slot_off[c0];
         a.chunk_bytes = d_chunk_bytes ? d_chunk_bytes + c0 : nullptr;
@@ -309,6 +296,31 @@ zipccl_status_t zipccl_estimate_table(const void* d_in, size_t n_elems, zipccl_d
     return launch_estimate(dt, a, stream) == 0 ? ZIPCCL_OK : ZIPCCL_ERR_DEVICE;
 }
 
+size_t zipccl_estimate_robust_workspace_size(void) { return kHistBytes; }
+
+zipccl_status_t zipccl_estimate_table_robust(const void* d_in, size_t n_elems, zipccl_dtype_t dt,
+                                             zipccl_table_t* d_table, double* d_sigma,
+                                             void* d_workspace, size_t workspace_bytes, void* stream)
+{
+    if (!dtype_ok(dt)) return ZIPCCL_ERR_UNSUPPORTED_DTYPE;
+    if (!d_table || !d_workspace || (!d_in && n_elems)) return ZIPCCL_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(d_in) % elem_size(dt)) || (reinterpret_cast<uintptr_t>(d_table) % 8) ||
+        (reinterpret_cast<uintptr_t>(d_sigma) % 8) || (reinterpret_cast<uintptr_t>(d_workspace) % 8))
+        return ZIPCCL_ERR_INVALID_ARG;
+    /* a workgroup counts in 32 bits: at most 2^32 - 1 values each */
+    if (n_elems / kHistBlocks >= 0xFFFFFFFFull) return ZIPCCL_ERR_INVALID_ARG;
+    if (workspace_bytes < zipccl_estimate_robust_workspace_size()) return ZIPCCL_ERR_BUFFER_TOO_SMALL;
+    HistArgs a;
+    a.in = static_cast<const uint8_t*>(d_in);
+    a.n = n_elems;
+    a.hist = static_cast<unsigned long long*>(d_workspace);
+    const uint64_t want = (n_elems + 65535) / 65536;             /* about 64 values per thread at least */
+    a.n_blocks = (uint32_t)(want < 1 ? 1 : (want > kHistBlocks ? kHistBlocks : want));
+    a.table = reinterpret_cast<uint8_t*>(d_table);
+    a.sigma = d_sigma;
+    return launch_estimate_robust(dt, a, stream) == 0 ? ZIPCCL_OK : ZIPCCL_ERR_DEVICE;
+}
+
 zipccl_status_t zipccl_decompress(const void* d_comp, size_t comp_capacity,
                                   void* d_out, size_t n_elems, zipccl_dtype_t dt,
                                   uint32_t n_chunks, const uint64_t* chunk_elems,
@@ -340,7 +352,7 @@ zipccl_status_t zipccl_decompress(const void* d_comp, size_t comp_capacity,
     uint64_t elem_base = 0;
     for (uint32_t c0 = 0; c0 < n_chunks; c0 += kMaxBatch) {
         const uint32_t nb = (n_chunks - c0) < kMaxBatch ? (n_chunks - c0) : kMaxBatch;
-        fill_tab(a.tab, ce, slot_off, c0, nb, dt);
+        fill_tab(a.tab, ce, slot_off, c0, nb);
         a.comp = static_cast<const uint8_t*>(d_comp) + slot_off[c0];
         a.comp_capacity = comp_capacity - slot_off[c0];
         a.out = static_cast<uint8_t*>(d_out) + elem_base * es;
@@ -371,14 +383,6 @@ zipccl_status_t zipccl_decompress_reduce(const void* d_comp, size_t comp_capacit
     a.n = n_elems;
     a.n_peers = n_peers;
     return launch_decompress_reduce(dt, out_dt, a, stream) == 0 ? ZIPCCL_OK : ZIPCCL_ERR_DEVICE;
-}
-
-zipccl_status_t zipccl_debug_copy(void* d_dst, const void* d_src, size_t bytes, void* stream)
-{
-    if (!d_dst || !d_src || (reinterpret_cast<uintptr_t>(d_dst) % 16) || (reinterpret_cast<uintptr_t>(d_src) % 16) ||
-        (bytes % 16) || bytes / 16 / 256 > 0x7FFFFFFFull)
-        return ZIPCCL_ERR_INVALID_ARG;
-    return launch_copy(d_dst, d_src, bytes, stream) == 0 ? ZIPCCL_OK : ZIPCCL_ERR_DEVICE;
 }
 
 int zipccl_switch_prefers_zipped(const zipccl_link_model_t* m, double d_bytes, double e, double s,
@@ -416,13 +420,6 @@ zipccl_status_t zipccl_fit_link_model(const double* d_bytes, const double* t_sec
     *beta = sxy / sxx;
     *alpha = mt - *beta * md;
     return ZIPCCL_OK;
-}
-
-int zipccl_debug_compress_path(int path)
-{
-    const int prev = compress_path().load();
-    if (path == 0 || path == 1) compress_path().store(path);
-    return prev;
 }
 
 const char* zipccl_status_string(zipccl_status_t s)

@@ -81,7 +81,19 @@ constexpr uint32_t kMomentBlocks = 2048;             /* workgroups (and partial 
 struct MomentArgs {
     const uint8_t* in;
     uint64_t n;
-    double* partial;         /* 2 doubles per workgroup: sum x, sum x^2 */
+    double* partial;         /* 2 doubles per workgroup: sum d, sum d^2 with d = x - first value */
+    uint32_t n_blocks;
+    uint8_t* table;          /* device zipccl_table_t (8 bytes) */
+    double* sigma;           /* may be null */
+};
+
+constexpr uint32_t kHistBlocks = 256;                /* workgroups of the magnitude histogram: one per compute unit */
+constexpr uint32_t kHistBytes = 32768 * 8;           /* its workspace: one 64-bit count per 15-bit magnitude */
+
+struct HistArgs {
+    const uint8_t* in;
+    uint64_t n;
+    unsigned long long* hist;   /* 32768 counts, zeroed by the first kernel of the call */
     uint32_t n_blocks;
     uint8_t* table;          /* device zipccl_table_t (8 bytes) */
     double* sigma;           /* may be null */
@@ -114,8 +126,8 @@ enum CompressMode { kModeCount = 0, kModeEmit = 1, kModeStash = 2 };
 
 /* launchers implemented next to their kernels (zipccl_compress.hip, zipccl_decompress.hip, zipccl_aux.hip);
  * they return a hipError_t as int */
-int launch_copy(void* d_dst, const void* d_src, uint64_t bytes, void* stream);
 int launch_estimate(int dt, const MomentArgs& a, void* stream);
+int launch_estimate_robust(int dt, const HistArgs& a, void* stream);
 int launch_compress(int dt, int mode, const CompressArgs& a, void* stream);
 int launch_tile_scan(const CompressArgs& a, void* stream);
 int launch_place(int dt, bool scan, const CompressArgs& a, void* stream);

@@ -15,7 +15,9 @@ def to_device_words(data):
     return torch.from_numpy(np.ascontiguousarray(data).view(signed)).to(DEV)
 
 
-def gpu_compress(data, dtype, sigma, n_chunks=1, chunk_elems=None, table=None, d_in=None):
+def gpu_compress(data, dtype, sigma, n_chunks=1, chunk_elems=None, table=None, d_in=None, reread=False):
+    """reread: hand zipccl_compress only its minimum workspace, which selects the form that reads the input
+    twice (count, prefix, emit) instead of the single pass with a stash."""
     n = int(data.size)
     table = table if table is not None else z.zipccl_build_table(sigma, dtype)
     cap = z.zipccl_max_compressed_size(n, dtype, n_chunks, chunk_elems)
@@ -25,7 +27,8 @@ def gpu_compress(data, dtype, sigma, n_chunks=1, chunk_elems=None, table=None, d
     d_cb = torch.full((n_chunks,), -1, dtype=torch.int64, device=DEV)
     ws = z.zipccl_compress_workspace_size(n, dtype, n_chunks, chunk_elems)
     d_ws = torch.full((ws,), 0x5A, dtype=torch.uint8, device=DEV)
-    z.zipccl_compress(d_in, n, dtype, n_chunks, chunk_elems, table, d_out, d_cb, d_ws)
+    wsb = z.zipccl_compress_min_workspace_size(n, dtype, n_chunks, chunk_elems) if reread else None
+    z.zipccl_compress(d_in, n, dtype, n_chunks, chunk_elems, table, d_out, d_cb, d_ws, workspace_bytes=wsb)
     torch.cuda.synchronize()
     return d_out, d_cb, table
 
@@ -40,12 +43,12 @@ def gpu_decompress(d_comp, n, dtype, n_chunks=1, chunk_elems=None, comp_capacity
     return d_back.cpu().numpy().view(words), int(d_st.item())
 
 
-def check_parity(data, dtype, sigma, n_chunks=1, chunk_elems=None, label=""):
+def check_parity(data, dtype, sigma, n_chunks=1, chunk_elems=None, label="", reread=False):
     """GPU compressed bytes, chunk sizes and decoded words must equal the oracle's."""
     n = int(data.size)
     dec = oracle.build_table(sigma)
     ref, ref_cb, off = oracle.compress(data, dtype, dec, n_chunks, chunk_elems)
-    d_out, d_cb, table = gpu_compress(data, dtype, sigma, n_chunks, chunk_elems)
+    d_out, d_cb, table = gpu_compress(data, dtype, sigma, n_chunks, chunk_elems, reread=reread)
     assert list(bytes(table.dec)) == list(dec), f"{label}: table differs"
     got = d_out.cpu().numpy()
     got_cb = d_cb.cpu().numpy().astype(np.uint64)

@@ -1,10 +1,12 @@
-"""GPU parity of the device-side sigma estimate and table choice against the oracle.
+"""GPU parity of the device-side sigma estimates and table choice against the oracle.
 
 sigma is floating point (FP64 sums in a different order): tolerance 1e-10 relative, derived from
 N * 2^-53 growth of a recursive FP64 sum over <= 2^27 values with |mean| <= sigma.  The table is
 an integer decision taken from sigma in FP64 on both sides; inputs are chosen away from the
 decision boundaries (sigma = 0.82335 * 2^k) so the tolerance cannot flip it.  Compressing with
 the device table must give exactly the bytes of compressing with the oracle's table.
+The robust estimate (median of the magnitudes) is a count followed by one FP64 division by the same
+constant on both sides: its sigma must be equal bit for bit.
 """
 import math
 
@@ -32,6 +34,32 @@ def _estimate(d_in, n, dtype):
     return d_tab, list(d_tab.cpu().numpy()), float(d_sig.item())
 
 
+def _estimate_robust(d_in, n, dtype):
+    d_tab = torch.full((8,), 0xEE, dtype=torch.uint8, device=DEV)
+    d_sig = torch.zeros(1, dtype=torch.float64, device=DEV)
+    d_ws = torch.full((z.zipccl_estimate_robust_workspace_size(),), 0x77, dtype=torch.uint8, device=DEV)   # garbage in
+    z.zipccl_estimate_table_robust(d_in, n, dtype, d_tab, d_sig, d_ws)
+    torch.cuda.synchronize()
+    return d_tab, list(d_tab.cpu().numpy()), float(d_sig.item())
+
+
+def _compress_with_device_table_equals_oracle(w, d_in, d_tab, dec):
+    cap = z.zipccl_max_compressed_size(w.n_elems, w.dtype, w.n_chunks, w.chunk_elems)
+    d_out = torch.full((cap,), 0xA5, dtype=torch.uint8, device=DEV)
+    d_cb = torch.zeros(w.n_chunks, dtype=torch.int64, device=DEV)
+    d_ws = torch.empty(z.zipccl_compress_workspace_size(w.n_elems, w.dtype, w.n_chunks, w.chunk_elems),
+                       dtype=torch.uint8, device=DEV)
+    z.zipccl_compress_device_table(d_in, w.n_elems, w.dtype, w.n_chunks, w.chunk_elems, d_tab, d_out, d_cb, d_ws)
+    torch.cuda.synchronize()
+    ref, ref_cb, off = oracle.compress(w.data, w.dtype, dec, w.n_chunks, w.chunk_elems)
+    got = d_out.cpu().numpy()
+    assert np.array_equal(d_cb.cpu().numpy().astype(np.uint64), ref_cb)
+    for c in range(w.n_chunks):
+        a, b = int(off[c]), int(off[c]) + int(ref_cb[c])
+        assert np.array_equal(got[a:b], ref[a:b]), c
+    return w.nbytes / float(ref_cb.sum())
+
+
 def _away_from_boundary(s):
     frac = (math.log2(s / 0.82335)) % 1.0
     return min(frac, 1 - frac) > 1e-6
@@ -47,20 +75,7 @@ def test_estimate_matches_oracle_on_workloads(name, scale):
     d_tab, got_dec, got_s = _estimate(d_in, w.n_elems, w.dtype)
     assert got_s == pytest.approx(s, rel=1e-10)
     assert got_dec == list(dec)
-    # compress with the device table == oracle compress with the oracle's estimated table
-    cap = z.zipccl_max_compressed_size(w.n_elems, w.dtype, w.n_chunks, w.chunk_elems)
-    d_out = torch.full((cap,), 0xA5, dtype=torch.uint8, device=DEV)
-    d_cb = torch.zeros(w.n_chunks, dtype=torch.int64, device=DEV)
-    d_ws = torch.empty(z.zipccl_compress_workspace_size(w.n_elems, w.dtype, w.n_chunks, w.chunk_elems),
-                       dtype=torch.uint8, device=DEV)
-    z.zipccl_compress_device_table(d_in, w.n_elems, w.dtype, w.n_chunks, w.chunk_elems, d_tab, d_out, d_cb, d_ws)
-    torch.cuda.synchronize()
-    ref, ref_cb, off = oracle.compress(w.data, w.dtype, dec, w.n_chunks, w.chunk_elems)
-    got = d_out.cpu().numpy()
-    assert np.array_equal(d_cb.cpu().numpy().astype(np.uint64), ref_cb)
-    for c in range(w.n_chunks):
-        a, b = int(off[c]), int(off[c]) + int(ref_cb[c])
-        assert np.array_equal(got[a:b], ref[a:b]), c
+    _compress_with_device_table_equals_oracle(w, d_in, d_tab, dec)
 
 
 def test_estimate_edge_cases():
@@ -87,3 +102,71 @@ def test_estimate_edge_cases():
                 assert math.isnan(got_s), label
             else:
                 assert got_s == pytest.approx(s, rel=1e-10, abs=1e-300), label
+
+
+def test_plain_estimate_far_from_zero_mean_does_not_cancel():
+    """Sums are taken of x minus the first value, so a tensor whose mean dwarfs its spread keeps its sigma:
+    a constant that is not a power of two gives exactly 0 (lowest window), mean 1000 with sigma 0.001 in fp32
+    gives the oracle's two-pass value."""
+    const = np.full(100000, 0x3DCD, dtype=np.uint16)                      # bf16 0.1
+    dec, s = osg.estimate_table(const, z.BF16)
+    assert s == 0.0 and list(dec) == [0, 1, 2, 3, 4, 5, 6, 7]
+    _, got_dec, got_s = _estimate(to_device_words(const), const.size, z.BF16)
+    assert got_s == 0.0 and got_dec == list(dec)
+    rng = np.random.default_rng(8)
+    far = (np.float32(1000.0) + rng.standard_normal(1 << 20, dtype=np.float32) * np.float32(1e-3)).astype(np.float32)
+    dec, s = osg.estimate_table(far.view(np.uint32), z.FP32)
+    assert 0.9e-3 < s < 1.1e-3 and _away_from_boundary(s)
+    _, got_dec, got_s = _estimate(to_device_words(far.view(np.uint32)), far.size, z.FP32)
+    assert got_s == pytest.approx(s, rel=1e-9) and got_dec == list(dec)
+
+
+@pytest.mark.parametrize("name,scale", [("c1", 1.0), ("c2", 1 / 8), ("c3", 1 / 32), ("c4", 1 / 64), ("c5", 1 / 64),
+                                        ("c5_fp32", 1 / 32)])
+def test_robust_estimate_matches_oracle_on_workloads(name, scale):
+    w = W.make(name, scale)
+    print(f"[robust] {w.name} n={w.n_elems}", flush=True)
+    dec, s = osg.robust_table(w.data, w.dtype)
+    d_in = to_device_words(w.data)
+    d_tab, got_dec, got_s = _estimate_robust(d_in, w.n_elems, w.dtype)
+    assert got_s == s                                          # exact: a count and one division
+    assert got_dec == list(dec)
+    ratio = _compress_with_device_table_equals_oracle(w, d_in, d_tab, dec)
+    nominal = w.nbytes / float(oracle.compress(w.data, w.dtype, oracle.build_table(w.sigma), w.n_chunks, w.chunk_elems)[1].sum())
+    assert ratio >= nominal * 0.99, (ratio, nominal)           # the window of the nominal sigma, or as good
+
+
+def test_robust_estimate_edge_cases():
+    rng = np.random.default_rng(9)
+    allpat = np.arange(65536, dtype=np.uint16)
+    cases = {
+        "empty": np.zeros(0, dtype=np.uint16),
+        "zeros only": np.array([0x0000, 0x8000] * 50, dtype=np.uint16),
+        "inf and nan only": np.array([0x7F80, 0xFF80, 0x7FC0, 0xFFFF], dtype=np.uint16),
+        "one value": np.array([0xC0A0], dtype=np.uint16),
+        "two values": np.array([0x3F80, 0x4040], dtype=np.uint16),
+        "subnormals": np.array([0x0001, 0x0002, 0x0003, 0x8004], dtype=np.uint16),
+        "every pattern": allpat,
+        "every pattern, shuffled, odd length": rng.permutation(allpat)[:65001],
+        "tail after vector part": W.f32_to_bf16_words(rng.standard_normal(300007, dtype=np.float32) * np.float32(3.0)),
+        "mostly zeros": np.where(rng.random(200000) < 0.9, 0, W.f32_to_bf16_words(rng.standard_normal(200000, dtype=np.float32))).astype(np.uint16),
+    }
+    for label, x in cases.items():
+        print(f"[robust edge] {label} n={x.size}", flush=True)
+        dec, s = osg.robust_table(x, z.BF16)
+        d_in = to_device_words(x)
+        d_off = torch.zeros(x.size + 1, dtype=torch.int16, device=DEV)     # a view 2 bytes into an allocation
+        d_off[1:] = d_in
+        for d in (d_in, d_off[1:]):
+            _, got_dec, got_s = _estimate_robust(d, x.size, z.BF16)
+            assert got_dec == list(dec), label
+            assert (math.isnan(s) and math.isnan(got_s)) or got_s == s, (label, got_s, s)
+    f = rng.integers(0, 2 ** 32, 100003, dtype=np.uint64).astype(np.uint32)                  # fp32 bit patterns
+    dec, s = osg.robust_table(f, z.FP32)
+    _, got_dec, got_s = _estimate_robust(to_device_words(f), f.size, z.FP32)
+    assert got_dec == list(dec) and got_s == s
+    with pytest.raises(z.ZipcclError) as ei:
+        d_small = torch.zeros(1024, dtype=torch.uint8, device=DEV)
+        z.zipccl_estimate_table_robust(to_device_words(f), f.size, z.FP32, torch.zeros(8, dtype=torch.uint8, device=DEV),
+                                       None, d_small)
+    assert ei.value.code == 3

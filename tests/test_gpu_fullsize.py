@@ -69,21 +69,19 @@ def test_one_chunk_of_the_largest_sizes(dtype, n, sigma):
     d_ws = torch.empty(z.zipccl_compress_workspace_size(n, dtype, 1), dtype=torch.uint8, device=DEV)
     d_back = torch.empty_like(d_in)
     d_st = torch.zeros(1, dtype=torch.int32, device=DEV)
-    try:
-        for path in (0, 1):
-            print(f"[huge] GPU compress path {path}", flush=True)
-            z.zipccl_debug_compress_path(path)
-            d_out.fill_(0xA5)
-            z.zipccl_compress(d_in, n, dtype, 1, None, z.zipccl_build_table(sigma, dtype), d_out, d_cb, d_ws)
-            torch.cuda.synchronize()
-            assert int(d_cb.item()) == cb
-            for a in range(0, cb, 1 << 30):
-                b = min(cb, a + (1 << 30))
-                assert np.array_equal(d_out[a:b].cpu().numpy(), ref[a:b]), f"compressed bytes differ in [{a}, {b})"
-            d_back.fill_(0)
-            z.zipccl_decompress(d_out, d_back, n, dtype, 1, None, d_st)
-            torch.cuda.synchronize()
-            assert int(d_st.item()) == 0
-            assert torch.equal(d_back, d_in), "GPU round trip differs"
-    finally:
-        z.zipccl_debug_compress_path(0)
+    # full workspace: single pass with a stash; minimum workspace: the input is read twice
+    for wsb in (None, z.zipccl_compress_min_workspace_size(n, dtype, 1)):
+        print(f"[huge] GPU compress, workspace bytes {wsb}", flush=True)
+        d_out.fill_(0xA5)
+        z.zipccl_compress(d_in, n, dtype, 1, None, z.zipccl_build_table(sigma, dtype), d_out, d_cb, d_ws,
+                          workspace_bytes=wsb)
+        torch.cuda.synchronize()
+        assert int(d_cb.item()) == cb
+        for a in range(0, cb, 1 << 30):
+            b = min(cb, a + (1 << 30))
+            assert np.array_equal(d_out[a:b].cpu().numpy(), ref[a:b]), f"compressed bytes differ in [{a}, {b})"
+        d_back.fill_(0)
+        z.zipccl_decompress(d_out, d_back, n, dtype, 1, None, d_st)
+        torch.cuda.synchronize()
+        assert int(d_st.item()) == 0
+        assert torch.equal(d_back, d_in), "GPU round trip differs"

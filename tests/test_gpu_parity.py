@@ -24,11 +24,11 @@ def _say(msg):
     sys.stdout.flush()
 
 
-@pytest.fixture(params=[0, 1], ids=["stash", "reread"])
+@pytest.fixture(params=[False, True], ids=["stash", "reread"])
 def compress_path(request):
-    prev = z.zipccl_debug_compress_path(request.param)
-    yield request.param
-    z.zipccl_debug_compress_path(prev)
+    """False: full workspace (single pass with a stash); True: minimum workspace (the input is read twice).
+    The workspace size alone selects the form, call by call."""
+    return request.param
 
 
 SMALL = [("c1", 1.0), ("c2", 1 / 8), ("c3", 1 / 32), ("c4", 1 / 64), ("c5", 1 / 64), ("c5_fp32", 1 / 32)]
@@ -38,7 +38,7 @@ SMALL = [("c1", 1.0), ("c2", 1 / 8), ("c3", 1 / 32), ("c4", 1 / 64), ("c5", 1 / 
 def test_workload_parity_small(name, scale, compress_path):
     w = W.make(name, scale)
     _say(f"[parity] {w.name} n={w.n_elems} chunks={w.n_chunks} path={compress_path}")
-    check_parity(w.data, w.dtype, w.sigma, w.n_chunks, w.chunk_elems, label=w.name)
+    check_parity(w.data, w.dtype, w.sigma, w.n_chunks, w.chunk_elems, label=w.name, reread=compress_path)
 
 
 EDGE_N = [0, 1, 7, 8, 9, 63, 64, 127, 128, 129, 511, 512, 513, 1023, 4095, 4096, 4097, 8191, 8192, 8193,
@@ -52,7 +52,7 @@ def test_edge_sizes_single_chunk(dtype, compress_path):
         _say(f"[edge] dtype={dtype} n={n} path={compress_path}")
         f = rng.standard_normal(n, dtype=np.float32)
         data = W.f32_to_bf16_words(f) if dtype == z.BF16 else f.view(np.uint32).copy()
-        check_parity(data, dtype, 1.0, 1, None, label=f"n={n}")
+        check_parity(data, dtype, 1.0, 1, None, label=f"n={n}", reread=compress_path)
 
 
 @pytest.mark.parametrize("dtype", [z.BF16, z.FP32], ids=["bf16", "fp32"])
@@ -64,7 +64,7 @@ def test_ragged_chunks_with_empty_and_unaligned_starts(dtype, compress_path):
     f = rng.standard_normal(n, dtype=np.float32) * np.float32(0.5)
     data = W.f32_to_bf16_words(f) if dtype == z.BF16 else f.view(np.uint32).copy()
     _say(f"[ragged] dtype={dtype} n={n} chunks={len(ce)} path={compress_path}")
-    check_parity(data, dtype, 0.5, len(ce), ce, label="ragged")
+    check_parity(data, dtype, 0.5, len(ce), ce, label="ragged", reread=compress_path)
 
 
 @pytest.mark.parametrize("dtype", [z.BF16, z.FP32], ids=["bf16", "fp32"])
@@ -79,7 +79,7 @@ def test_chunk_starts_of_every_alignment_with_whole_tiles(dtype, compress_path):
     f[rng.integers(0, n, 3000)] *= np.float32(1e6)          # zero-points everywhere
     data = W.f32_to_bf16_words(f) if dtype == z.BF16 else f.view(np.uint32).copy()
     _say(f"[alignments] dtype={dtype} n={n} path={compress_path}")
-    check_parity(data, dtype, 0.5, len(ce), ce, label="alignments")
+    check_parity(data, dtype, 0.5, len(ce), ce, label="alignments", reread=compress_path)
 
 
 def test_more_chunks_than_one_launch_holds(compress_path):
@@ -90,14 +90,14 @@ def test_more_chunks_than_one_launch_holds(compress_path):
     n = int(ce.sum())
     data = W.f32_to_bf16_words(rng.standard_normal(n, dtype=np.float32))
     _say(f"[batches] n={n} chunks=300 path={compress_path}")
-    check_parity(data, z.BF16, 1.0, 300, ce, label="300 chunks")
+    check_parity(data, z.BF16, 1.0, 300, ce, label="300 chunks", reread=compress_path)
 
 
 def test_all_bf16_patterns_and_extreme_tables(compress_path):
     data = np.tile(np.arange(65536, dtype=np.uint16), 2)[:-5]
     for sigma in (1.0, 1e-45, 1e300, 0.02):
         _say(f"[patterns] sigma={sigma} path={compress_path}")
-        check_parity(data, z.BF16, sigma, 1, None, label=f"patterns sigma={sigma}")
+        check_parity(data, z.BF16, sigma, 1, None, label=f"patterns sigma={sigma}", reread=compress_path)
 
 
 def test_fp32_random_bit_patterns(compress_path):
@@ -105,7 +105,7 @@ def test_fp32_random_bit_patterns(compress_path):
     data = rng.integers(0, 2 ** 32, 100_003, dtype=np.uint64).astype(np.uint32)
     data[:6] = [0, 0x80000000, 0x7F800000, 0xFF800000, 0x7FC00001, 0xFFFFFFFF]
     _say(f"[fp32 bits] path={compress_path}")
-    check_parity(data, z.FP32, 1.0, 1, None, label="fp32 bits")
+    check_parity(data, z.FP32, 1.0, 1, None, label="fp32 bits", reread=compress_path)
 
 
 def test_all_zero_points_and_none(compress_path):
@@ -116,7 +116,7 @@ def test_all_zero_points_and_none(compress_path):
     half[::2] = 0x7F80                                       # alternating +Inf
     for name, d in (("all-escape", zeros), ("no-escape", ones), ("alternating", half)):
         _say(f"[{name}] path={compress_path}")
-        got, cb, off = check_parity(d, z.BF16, 1.0, 1, None, label=name)
+        got, cb, off = check_parity(d, z.BF16, 1.0, 1, None, label=name, reread=compress_path)
     # worst case fills the slot exactly: chunk_bytes == capacity
     d_out, d_cb, _ = gpu_compress(np.zeros(8192, dtype=np.uint16), z.BF16, 1.0)
     assert int(d_cb.item()) == z.zipccl_max_compressed_size(8192, z.BF16, 1)
@@ -250,7 +250,7 @@ def test_random_splits_and_contents_fuzz(compress_path):
             pos = rng.integers(0, n, spec.size)
             data[pos] = spec.astype(data.dtype) if dtype == z.BF16 else (spec << 16 | 0x1234).astype(np.uint32)
         _say(f"[fuzz {case}] dtype={dtype} chunks={list(ce)} sigma={sigma:.3g} path={compress_path}")
-        check_parity(data, dtype, sigma, k, ce, label=f"fuzz{case}")
+        check_parity(data, dtype, sigma, k, ce, label=f"fuzz{case}", reread=compress_path)
 
 
 @pytest.mark.parametrize("tiles", [2500, 4500], ids=["scan_in_place_kernel", "scan_kernel"])
@@ -263,7 +263,7 @@ def test_one_chunk_spanning_several_scan_segments(compress_path, tiles):
     data = W.f32_to_bf16_words(rng.standard_normal(int(ce.sum()), dtype=np.float32) * np.float32(0.5))
     data[5_000_000:5_020_000] = 0x7F80                      # a dense stretch of zero-points
     _say(f"[segments] n={data.size} path={compress_path}")
-    check_parity(data, z.BF16, 0.5, 2, ce, label="scan segments")
+    check_parity(data, z.BF16, 0.5, 2, ce, label="scan segments", reread=compress_path)
 
 
 def test_static_then_dynamic_transfer_as_in_the_second_all_to_all_design():
