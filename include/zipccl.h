@@ -48,6 +48,7 @@ extern "C" {
 #define ZIPCCL_GROUP 512u        /* elements per IDX entry: one wave64 x 8 values per lane */
 #define ZIPCCL_ALIGN 128u        /* alignment of every slot and section */
 #define ZIPCCL_MAX_CHUNK_ELEMS 0xFFFFFFFFull /* IDX entries are u32 */
+#define ZIPCCL_STATIC_SCRATCH_BYTES (32u << 20) /* the library's own workspace, per GPU: zipccl_compress_static */
 
 typedef enum { ZIPCCL_BF16 = 0, ZIPCCL_FP32 = 1 } zipccl_dtype_t;
 
@@ -132,6 +133,27 @@ zipccl_status_t zipccl_compress(const void* d_in, size_t n_elems, zipccl_dtype_t
                                 const zipccl_table_t* table,
                                 void* d_out, size_t out_capacity, uint64_t* d_chunk_bytes,
                                 void* d_workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * zipccl_compress for callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and the same
+ * bytes as zipccl_compress, minus the workspace: that is a fixed array of ZIPCCL_STATIC_SCRATCH_BYTES
+ * (32 MiB) inside the library's device code, one copy on every GPU the library runs on, held until the process
+ * ends.  The call makes no hipMalloc, hipFree or other allocating device call.
+ *   - Up to about 33.5 million values (zipccl_compress_workspace_size(...) <= 32 MiB) the input is read once;
+ *     above that twice (the form zipccl_compress takes with its minimum workspace).
+ *   - A call whose zipccl_compress_min_workspace_size(...) exceeds 32 MiB (more than about 4.19 million tiles
+ *     of 8192 values) returns ZIPCCL_ERR_BUFFER_TOO_SMALL and launches nothing.
+ *   - Every call on a GPU uses that GPU's one array: calls that may overlap in time on the same GPU (different
+ *     streams, different threads) race and must be ordered by the caller.  Nothing in the array needs to be
+ *     cleared between calls, and nothing of a call's result stays in it.
+ *   - The first call on each GPU looks up the array's device address (hipGetSymbolAddress); make that call
+ *     outside a stream capture.
+ */
+zipccl_status_t zipccl_compress_static(const void* d_in, size_t n_elems, zipccl_dtype_t dt,
+                                       uint32_t n_chunks, const uint64_t* chunk_elems,
+                                       const zipccl_table_t* table,
+                                       void* d_out, size_t out_capacity, uint64_t* d_chunk_bytes, void* stream);
 
 /*
  * Table from the data (section 4.1, last sentence: sigma of the tensor by torch.std, i.e. the

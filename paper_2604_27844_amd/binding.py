@@ -59,6 +59,8 @@ def _load():
     lib.zipccl_compress_min_workspace_size.argtypes = [sz, i32, u32, vp]
     lib.zipccl_compress.restype = i32
     lib.zipccl_compress.argtypes = [vp, sz, i32, u32, vp, tp, vp, sz, vp, vp, sz, vp]
+    lib.zipccl_compress_static.restype = i32
+    lib.zipccl_compress_static.argtypes = [vp, sz, i32, u32, vp, tp, vp, sz, vp, vp]
     lib.zipccl_compress_device_table.restype = i32
     lib.zipccl_compress_device_table.argtypes = [vp, sz, i32, u32, vp, vp, vp, sz, vp, vp, sz, vp]
     lib.zipccl_estimate_workspace_size.restype = sz
@@ -89,7 +91,7 @@ EXPORTS = ("zipccl_build_table", "zipccl_max_compressed_size", "zipccl_chunk_slo
            "zipccl_compress_workspace_size", "zipccl_compress_min_workspace_size", "zipccl_compress", "zipccl_decompress", "zipccl_decompress_reduce", "zipccl_status_string",
            "zipccl_switch_prefers_zipped", "zipccl_fit_link_model",
            "zipccl_estimate_workspace_size", "zipccl_estimate_table", "zipccl_compress_device_table",
-           "zipccl_estimate_robust_workspace_size", "zipccl_estimate_table_robust")
+           "zipccl_estimate_robust_workspace_size", "zipccl_estimate_table_robust", "zipccl_compress_static")
 
 
 def _host_u64(chunk_elems):
@@ -161,6 +163,17 @@ def zipccl_compress(d_in, n_elems, dt, n_chunks, chunk_elems, table, d_out, d_ch
                               _dptr(d_out), cap, _dptr(d_chunk_bytes), _dptr(d_workspace), wsb, _stream(stream))
     if rc:
         raise ZipcclError(rc, "zipccl_compress")
+
+
+def zipccl_compress_static(d_in, n_elems, dt, n_chunks, chunk_elems, table, d_out, d_chunk_bytes, stream=None,
+                           out_capacity=None):
+    """zipccl_compress with the library's own fixed workspace (no allocation, no workspace argument)."""
+    _keep, p = _host_u64(chunk_elems)
+    cap = d_out.numel() * d_out.element_size() if out_capacity is None else int(out_capacity)
+    rc = _lib.zipccl_compress_static(_dptr(d_in), int(n_elems), dt, int(n_chunks), p, ctypes.byref(table),
+                                     _dptr(d_out), cap, _dptr(d_chunk_bytes), _stream(stream))
+    if rc:
+        raise ZipcclError(rc, "zipccl_compress_static")
 
 
 def zipccl_decompress(d_comp, d_out, n_elems, dt, n_chunks=1, chunk_elems=None, d_status=None, stream=None,

@@ -22,10 +22,19 @@
  *              of the slowest of them, measured; the stash costs ~5 % extra traffic.)
  * Everything here is integer work.
  */
+#include <mutex>
+
 #include "zipccl_device.h"
 
 namespace zipccl {
 namespace {
+
+/*
+ * Workspace of zipccl_compress_static: device memory that belongs to the library, one copy per GPU, held until
+ * the process ends.  Host code never uses this name as an address: static_scratch() asks the runtime for the
+ * array's device address, once per device, and hands that out.
+ */
+static __device__ __align__(256) uint8_t scratch[ZIPCCL_STATIC_SCRATCH_BYTES];
 
 /*
  * Load the lane's 8 consecutive values starting at chunk-relative element e.
@@ -551,6 +560,28 @@ __global__ __launch_bounds__(kThreads) void k_tile_scan(const CompressArgs a)
 }
 
 } // namespace
+
+int static_scratch(void** ptr, size_t* bytes)
+{
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static void* addr[kMaxDevices];            /* device address of `scratch` on each GPU, once resolved */
+    int dev = -1;
+    const hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return (int)e;
+    if (dev < 0 || dev >= kMaxDevices) return (int)hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!addr[dev]) {
+        void* p = nullptr;
+        const hipError_t es = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));   /* for the current device */
+        if (es != hipSuccess) return (int)es;
+        if (!p) return (int)hipErrorInvalidSymbol;
+        addr[dev] = p;
+    }
+    *ptr = addr[dev];
+    *bytes = sizeof scratch;
+    return 0;
+}
 
 int launch_compress(int dt, int mode, const CompressArgs& a, void* stream)
 {

@@ -273,6 +273,23 @@ zipccl_status_t zipccl_compress_device_table(const void* d_in, size_t n_elems, z
                          d_chunk_bytes, d_workspace, workspace_bytes, stream);
 }
 
+zipccl_status_t zipccl_compress_static(const void* d_in, size_t n_elems, zipccl_dtype_t dt,
+                                       uint32_t n_chunks, const uint64_t* chunk_elems,
+                                       const zipccl_table_t* table,
+                                       void* d_out, size_t out_capacity, uint64_t* d_chunk_bytes, void* stream)
+{
+    if (!dtype_ok(dt)) return ZIPCCL_ERR_UNSUPPORTED_DTYPE;
+    /* the size limit first, so that it is reported whatever else is wrong with a call that large */
+    const size_t need = zipccl_compress_min_workspace_size(n_elems, dt, n_chunks, chunk_elems);
+    if (need == 0) return ZIPCCL_ERR_INVALID_ARG;
+    if (need > ZIPCCL_STATIC_SCRATCH_BYTES) return ZIPCCL_ERR_BUFFER_TOO_SMALL;
+    void* ws = nullptr;
+    size_t ws_bytes = 0;
+    if (static_scratch(&ws, &ws_bytes) != 0) return ZIPCCL_ERR_DEVICE;
+    return compress_impl(d_in, n_elems, dt, n_chunks, chunk_elems, table, nullptr, d_out, out_capacity,
+                         d_chunk_bytes, ws, ws_bytes, stream);
+}
+
 size_t zipccl_estimate_workspace_size(void) { return 16 * (size_t)kMomentBlocks; }
 
 zipccl_status_t zipccl_estimate_table(const void* d_in, size_t n_elems, zipccl_dtype_t dt,

@@ -2,6 +2,7 @@
 #ifndef ZIPCCL_INTERNAL_H
 #define ZIPCCL_INTERNAL_H
 
+#include <stddef.h>
 #include <stdint.h>
 #include "zipccl.h"
 
@@ -129,6 +130,8 @@ enum CompressMode { kModeCount = 0, kModeEmit = 1, kModeStash = 2 };
 int launch_estimate(int dt, const MomentArgs& a, void* stream);
 int launch_estimate_robust(int dt, const HistArgs& a, void* stream);
 int launch_compress(int dt, int mode, const CompressArgs& a, void* stream);
+/* device address and size of the library's own workspace on the current GPU (zipccl_compress_static) */
+int static_scratch(void** ptr, size_t* bytes);
 int launch_tile_scan(const CompressArgs& a, void* stream);
 int launch_place(int dt, bool scan, const CompressArgs& a, void* stream);
 int launch_decompress(int dt, const DecompressArgs& a, void* stream);
