@@ -18,7 +18,8 @@
  * slice on its own.  With pad(x) = x rounded up to 128 and a chunk of n elements:
  *
  *   HDR  128 B          "ZPCL", version u32 = 1, dtype u32, G u32, n u64, n_esc u64,
- *                       chunk_bytes u64, dec[8], zero fill
+ *                       chunk_bytes u64, dec[8] (dec[0] = 0), then bytes 48..127 reserved: written
+ *                       as zero, ignored when decoding
  *   SM   pad(n)         byte i = sign << 7 | 7 mantissa bits of the high 16-bit word
  *                       (section 4: sign and mantissa kept verbatim at a fixed stride)
  *   LO   pad(2n)        fp32 only: u16 i = low 16 bits of the word
@@ -207,7 +208,8 @@ zipccl_status_t zipccl_compress_device_table(const void* d_in, size_t n_elems, z
  *                   the kernel checks that each slot's zero-point list also fits
  *   d_out           device, n_elems values of dtype dt, aligned to the element size
  *   d_status        device u32, may be NULL: OR-ed with ZIPCCL_ERR_CORRUPT if a header does not
- *                   match (magic, version, dtype, G, n, table) or an index leaves the list;
+ *                   match (magic, version, dtype, G, n, sizes, a table that is not a window with
+ *                   dec[0] = 0) or an index leaves the list;
  *                   the caller zeroes it.  Values of a corrupt chunk are unspecified, but no
  *                   read or write leaves the caller's buffers.
  */

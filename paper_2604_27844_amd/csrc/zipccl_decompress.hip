@@ -343,8 +343,9 @@ __device__ __forceinline__ void decode_store(uint8_t* __restrict__ cout, const D
 
 /*
  * Chunk header check (all wave-uniform): the static part is readable (the host checked it), magic,
- * version, dtype, G and n must match the call, the table must be a window, and the zero-point
- * list the header promises must fit into the readable bytes.
+ * version, dtype, G and n must match the call, the table must be a window (dec[0] = 0, dec[1..7]
+ * consecutive), and the zero-point list the header promises must fit into the readable bytes.  The
+ * reserved bytes 48..127 are not looked at.
  */
 struct HeaderWords { uint32_t h[12]; };
 
@@ -374,6 +375,7 @@ __device__ __forceinline__ bool check_header(const HeaderWords& hdr, const SlotL
     wrong |= (uint32_t)(n_hdr != n) | (uint32_t)(ne > n) | (uint32_t)(cbytes != L.esc + pad128(ne));
     wrong |= (uint32_t)(slot_off + cbytes > comp_capacity);
     wrong |= (uint32_t)(e0 < 1u) | (uint32_t)(e0 > 249u);
+    wrong |= dec_lo & 0xFFu;                                   /* dec[0] is written as 0 */
     wrong |= (dec_lo >> 8) ^ (e0 | ((e0 + 1u) << 8) | ((e0 + 2u) << 16));
     wrong |= dec_hi ^ ((e0 + 3u) | ((e0 + 4u) << 8) | ((e0 + 5u) << 16) | ((e0 + 6u) << 24));
     const bool ok = wrong == 0u;

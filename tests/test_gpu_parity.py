@@ -193,11 +193,15 @@ def test_decoder_flags_corrupt_streams_without_leaving_buffers():
     back, st = gpu_decompress(good, n, w.dtype)
     assert st == 0 and np.array_equal(back, w.data)
     lay_idx = 128 + n + 3 * (n // 8)                       # n is a multiple of 1024 here
-    for pos, val in ((0, 0x00), (4, 2), (8, 1), (13, 1), (16, 1), (24, 0xFF), (41, 3)):
+    for pos, val in ((0, 0x00), (4, 2), (8, 1), (13, 1), (16, 1), (24, 0xFF), (40, 1), (41, 3), (47, 0)):
         bad = good.clone()
         bad[pos] = val
         _, st = gpu_decompress(bad, n, w.dtype)
         assert st == 4, pos
+    bad = good.clone()                                       # the reserved header bytes are ignored when decoding
+    bad[48:128] = 0xEE
+    back, st = gpu_decompress(bad, n, w.dtype)
+    assert st == 0 and np.array_equal(back, w.data)
     bad = good.clone()                                       # an index far outside the zero-point list
     bad[lay_idx + 4:lay_idx + 8] = torch.tensor([0xFF, 0xFF, 0xFF, 0x7F], dtype=torch.uint8, device=DEV)
     _, st = gpu_decompress(bad, n, w.dtype)
