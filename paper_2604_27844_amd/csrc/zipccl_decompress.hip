@@ -83,8 +83,7 @@ struct DecIn {
 /* The lane's zero-point bytes (up to 8, in element order) and where its mask says they go. */
 struct DecEsc {
     uint32_t m;              /* bit j = value j is a zero-point */
-    uint32_t sh;             /* byte offset of the lane's first zero-point inside d0 */
-    uint32_t d0, d1, d2;     /* three aligned words covering the lane's 8 list bytes */
+    uint32_t l8, h8;         /* the 8 list bytes from the lane's first zero-point on */
     uint32_t wA, wB;         /* two-quad lanes (fp32): the list bytes of the first and of the second quad */
     uint32_t bad;            /* nonzero: planes and IDX disagree about the group */
 };
@@ -222,9 +221,11 @@ __device__ __forceinline__ DecEsc decode_locate(const DecIn& in, const uint8_t* 
     /* the lane's zero-point exponents are the bytes [p, p + cnt) of the region, p <= 15 + 512 - cnt
        (clamped, so that a corrupt stream still reads inside the region) */
     const uint32_t p = min((in.base & 15u) + (inc - cnt), kGroup + 15u);
+    /* three aligned words and two byte alignments: a single 8-byte read at the byte address p is accepted by the
+       hardware but made the fused reduce, whose LDS pipe is two thirds busy, 35 % slower (measured) */
     const uint32_t* w = reinterpret_cast<const uint32_t*>(lds + (p & ~3u));
-    r.d0 = w[0]; r.d1 = w[1]; r.d2 = w[2];
-    r.sh = p & 3u;
+    r.l8 = __builtin_amdgcn_alignbyte(w[1], w[0], p & 3u);
+    r.h8 = __builtin_amdgcn_alignbyte(w[2], w[1], p & 3u);
     return r;
 }
 
@@ -245,7 +246,7 @@ __device__ __forceinline__ DecEsc decode_locate_quad(const DecIn& in, const uint
     const uint32_t* wb = reinterpret_cast<const uint32_t*>(lds + (pB & ~3u));
     r.wA = __builtin_amdgcn_alignbyte(wa[1], wa[0], pA & 3u);
     r.wB = __builtin_amdgcn_alignbyte(wb[1], wb[0], pB & 3u);
-    r.d0 = r.d1 = r.d2 = r.sh = 0;
+    r.l8 = r.h8 = 0;
     return r;
 }
 
@@ -265,11 +266,9 @@ __device__ __forceinline__ void decode_bytes(const DecIn& in, const DecEsc& es, 
         eA = bfi(xa.y, perm(0u, es.wA, xa.x), eA);
         eB = bfi(xb.y, perm(0u, es.wB, xb.x), eB);
     } else {   /* zero-point exponents dropped in place: the lane's list bytes are the 8-byte window l8:h8 */
-        const uint32_t l8 = __builtin_amdgcn_alignbyte(es.d1, es.d0, es.sh);
-        const uint32_t h8 = __builtin_amdgcn_alignbyte(es.d2, es.d1, es.sh);
         const u32x4 x = tab.expand[es.m];
-        eA = bfi(x.z, perm(h8, l8, x.x), eA);
-        eB = bfi(x.w, perm(h8, l8, x.y), eB);
+        eA = bfi(x.z, perm(es.h8, es.l8, x.x), eA);
+        eB = bfi(x.w, perm(es.h8, es.l8, x.y), eB);
     }
     /* recombine with sign and mantissa: low byte = mantissa | E bit 0 << 7, high = sign | E >> 1 */
     lA = bfi(0x7F7F7F7Fu, in.sm0, eA << 7); hA = bfi(0x80808080u, in.sm0, eA >> 1);
@@ -561,10 +560,10 @@ __device__ __forceinline__ void reduce_stages(const ReduceArgs& a, const SlotLay
     uint32_t gf = (uint32_t)(gs0 / kGroup);
     uint64_t idx_f = L.idx + 4u * (uint64_t)gf;                /* of IDX[gf] in a slot */
     uint32_t next_f = gf + 1u < ng ? 4u : 0u;                  /* from there to the following entry, if any */
+    uint64_t off_f = 0;                                        /* all slots accepted: offset of slot jf */
     auto front = [&](StageBuf& r) {
         /* some slot rejected: the j-th accepted one is not slot j */
-        const uint32_t p = all_ok ? jf : __builtin_amdgcn_readfirstlane(s_peer[jf]);
-        r.pre_off = (uint64_t)p * a.slot_cap;
+        r.pre_off = all_ok ? off_f : (uint64_t)__builtin_amdgcn_readfirstlane(s_peer[jf]) * a.slot_cap;
         const uint8_t* __restrict__ slot = a.comp + r.pre_off;
         r.pre_nesc = load_const_u32(slot + 24);
         r.pre_dec = load_const_u32(slot + 40);
@@ -575,8 +574,10 @@ __device__ __forceinline__ void reduce_stages(const ReduceArgs& a, const SlotLay
         if (adv_left != 0u) {
             --adv_left;
             ++jf;
+            off_f += a.slot_cap;
             if (jf == n_acc) {
                 jf = 0;
+                off_f = 0;
                 gf += kWavesPerBlock;
                 idx_f += 4u * kWavesPerBlock;
                 next_f = gf + 1u < ng ? 4u : 0u;
@@ -638,7 +639,9 @@ __device__ __forceinline__ void reduce_stages(const ReduceArgs& a, const SlotLay
             r.in.b2 = __builtin_amdgcn_ds_bpermute(from + 128u, w);
         }
         plane_bytes_of_words(r.in, lane);
-        decode_park_list(lds, lane, r.lv);
+        /* park the slice; the wave's region holds 64 x 16 bytes, so every lane writes what it fetched and the
+           store needs no predicate (lanes past the slice hold bytes that no lane picks) */
+        *reinterpret_cast<u32x4*>(lds + 16u * lane) = r.lv;
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -669,12 +672,22 @@ __device__ __forceinline__ void reduce_stages(const ReduceArgs& a, const SlotLay
         if (r.cur_last) {
             uint8_t* __restrict__ og = a.out + (uint64_t)r.cur_g * kGroup * OES;
             if (FAST) {
+                /* a NaN among the lane's sums is rare: one unordered compare per pair of sums finds out, and
+                   only then are the eight looked at one by one (sum_bits) */
+                const bool any_nan = (acc[0] != acc[0] || acc[1] != acc[1]) | (acc[2] != acc[2] || acc[3] != acc[3]) |
+                                     (acc[4] != acc[4] || acc[5] != acc[5]) | (acc[6] != acc[6] || acc[7] != acc[7]);
+                if (__builtin_expect(__ballot(any_nan) != 0ull, 0)) {
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) acc[j] = __uint_as_float(sum_bits(acc[j]));
+                }
                 if (ODT == ZIPCCL_FP32) {
                     /* The lane's 8 sums are 32 contiguous bytes, a pattern that stores slowly.  Once per
                        group they go through the wave's LDS region (free between decodes), half a group at
                        a time, and come back as 16 contiguous bytes per lane: two streaming stores of 1 KiB. */
-                    const u32x4 lo4 = u32x4{sum_bits(acc[0]), sum_bits(acc[1]), sum_bits(acc[2]), sum_bits(acc[3])};
-                    const u32x4 hi4 = u32x4{sum_bits(acc[4]), sum_bits(acc[5]), sum_bits(acc[6]), sum_bits(acc[7])};
+                    const u32x4 lo4 = u32x4{__float_as_uint(acc[0]), __float_as_uint(acc[1]),
+                                            __float_as_uint(acc[2]), __float_as_uint(acc[3])};
+                    const u32x4 hi4 = u32x4{__float_as_uint(acc[4]), __float_as_uint(acc[5]),
+                                            __float_as_uint(acc[6]), __float_as_uint(acc[7])};
                     u32x4 row[2];
 #pragma unroll
                     for (uint32_t h = 0; h < 2; ++h) {
@@ -694,7 +707,7 @@ __device__ __forceinline__ void reduce_stages(const ReduceArgs& a, const SlotLay
                     uint32_t o[4];
 #pragma unroll
                     for (int k = 0; k < 4; ++k)
-                        o[k] = f32_bits_to_bf16_bits(sum_bits(acc[2 * k])) | (f32_bits_to_bf16_bits(sum_bits(acc[2 * k + 1])) << 16);
+                        o[k] = f32_bits_to_bf16_bits(__float_as_uint(acc[2 * k])) | (f32_bits_to_bf16_bits(__float_as_uint(acc[2 * k + 1])) << 16);
                     st_stream_a4(og + lane * 16u, u32x4{o[0], o[1], o[2], o[3]});
                 }
             } else {
