@@ -171,50 +171,86 @@ __global__ __launch_bounds__(kHistThreads) void k_magnitude_hist(const HistArgs 
     }
 }
 
+/* Inclusive prefix sum of 64-bit values over the 64 lanes of a wave, exact, without going through LDS: the four
+ * 16-bit limbs are scanned separately with DPP (each limb sum stays below 2^22) and put together again.
+ * (64-bit shuffles are two LDS permutes each, and a chain of several hundred of them took 20 us here.) */
+__device__ __forceinline__ unsigned long long wave_incl_scan_u64(unsigned long long x)
+{
+    unsigned long long r = 0;
+#pragma unroll
+    for (uint32_t k = 0; k < 4; ++k)
+        r += (unsigned long long)wave_incl_scan((uint32_t)(x >> (16 * k)) & 0xFFFFu) << (16 * k);
+    return r;
+}
+
+/*
+ * One workgroup.  Thread t answers for the 32 consecutive bins [32 t, 32 t + 32).  The 32768 counts are read with
+ * coalesced loads (thread t holds bin 1024 r + t of every row r, all loads in flight together) and handed to their
+ * owners through LDS, 4096 bins at a time; every thread sums its 32 bins, one scan over the 1024 sums finds the
+ * thread that holds the rank, and that thread walks its bins.  Bins 0 (zero) and 0x7F80.. (Inf / NaN) do not count.
+ */
 __global__ __launch_bounds__(kHistThreads) void k_robust_finish(const HistArgs a)
 {
-    constexpr uint32_t kPer = kMagBins / kHistThreads;       /* 32 consecutive bins per thread */
+    constexpr uint32_t kPer = kMagBins / kHistThreads;       /* 32 bins per thread, and rows of the coalesced read */
+    constexpr uint32_t kWaves = kHistThreads / 64;           /* 16 */
+    constexpr uint32_t kRound = 4096;                        /* bins handed over per round: 128 owners */
     constexpr uint32_t kFirstNonFinite = 0x7F80u;            /* magnitudes from here on are Inf / NaN */
-    __shared__ unsigned long long s_wave[kHistThreads / 64];
-    const uint32_t b0 = threadIdx.x * kPer;
-    unsigned long long mine = 0;
-    for (uint32_t k = 0; k < kPer; ++k) {
-        const uint32_t b = b0 + k;
-        if (b != 0u && b < kFirstNonFinite) mine += a.hist[b];
-    }
-    /* exclusive prefix over the threads: butterfly-free serial form, 16 waves */
-    unsigned long long inc = mine;
+    __shared__ unsigned long long s_buf[kRound + kRound / kPer];     /* one pad word per owner: bank-conflict relief */
+    __shared__ unsigned long long s_wave[kWaves];
+    const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
+    unsigned long long v[kPer];
 #pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const unsigned long long up = __shfl_up(inc, d, 64);
-        if ((threadIdx.x & 63u) >= (uint32_t)d) inc += up;
+    for (uint32_t r = 0; r < kPer; ++r) {
+        const uint32_t b = r * kHistThreads + t;
+        v[r] = (b != 0u && b < kFirstNonFinite) ? a.hist[b] : 0ull;
     }
-    if ((threadIdx.x & 63u) == 63u) s_wave[threadIdx.x >> 6] = inc;
+    unsigned long long mine = 0;
+#pragma unroll
+    for (uint32_t q = 0; q < kMagBins / kRound; ++q) {       /* 8 rounds; round q = bins [4096 q, 4096 q + 4096) */
+#pragma unroll
+        for (uint32_t j = 0; j < kRound / kHistThreads; ++j) {
+            const uint32_t e = j * kHistThreads + t;         /* bin inside the round */
+            s_buf[e + e / kPer] = v[q * (kRound / kHistThreads) + j];
+        }
+        __syncthreads();
+        if (t / (kRound / kPer) == q) {
+            const uint32_t o = (t % (kRound / kPer)) * (kPer + 1);
+#pragma unroll
+            for (uint32_t k = 0; k < kPer; ++k) mine += s_buf[o + k];
+        }
+        __syncthreads();
+    }
+    const unsigned long long inc = wave_incl_scan_u64(mine);
+    if (lane == 63u) s_wave[wave] = inc;
     __syncthreads();
     unsigned long long before = 0, total = 0;
-    for (uint32_t w = 0; w < kHistThreads / 64; ++w) {
+    for (uint32_t w = 0; w < kWaves; ++w) {
         const unsigned long long c = s_wave[w];
-        before += w < (threadIdx.x >> 6) ? c : 0ull;
+        before += w < wave ? c : 0ull;
         total += c;
     }
-    const unsigned long long excl = before + inc - mine;
     if (total == 0ull) {
-        if (threadIdx.x == 0) table_from_sigma(__longlong_as_double(0x7FF8000000000000ll), a.table, a.sigma);
+        if (t == 0) table_from_sigma(__longlong_as_double(0x7FF8000000000000ll), a.table, a.sigma);
         return;
     }
-    const unsigned long long rank = (total - 1ull) / 2ull;
+    const unsigned long long rank = (total - 1ull) / 2ull, excl = before + inc - mine;
     if (rank < excl || rank >= excl + mine) return;          /* exactly one thread holds the rank */
-    unsigned long long run = excl;
+    unsigned long long c[kPer];
+#pragma unroll
     for (uint32_t k = 0; k < kPer; ++k) {
-        const uint32_t b = b0 + k;
-        if (b == 0u || b >= kFirstNonFinite) continue;
-        run += a.hist[b];
-        if (rank < run) {
-            const double med = (double)__uint_as_float(b << 16);
-            table_from_sigma(med / 0.6744897501960817, a.table, a.sigma);     /* Phi^-1(3/4) */
-            return;
-        }
+        const uint32_t b = t * kPer + k;
+        c[k] = (b != 0u && b < kFirstNonFinite) ? a.hist[b] : 0ull;
     }
+    unsigned long long run = excl;
+    uint32_t bin = 0;
+    bool found = false;
+#pragma unroll
+    for (uint32_t k = 0; k < kPer; ++k) {
+        run += c[k];
+        if (!found && rank < run) { found = true; bin = t * kPer + k; }
+    }
+    const double med = (double)__uint_as_float(bin << 16);
+    table_from_sigma(med / 0.6744897501960817, a.table, a.sigma);     /* Phi^-1(3/4) */
 }
 
 } // namespace
