@@ -222,6 +222,31 @@ def run_estimate(w, r, steps):
         leg.update({"sigma": float(d_sig.item()), "dec1": int(d_tab[1].item()),
                     "ratio_with_estimated_table": round(w.nbytes / int(d_cb.sum().item()), 5)})
         out[name] = leg
+    # one robust table per peer chunk (zipccl_estimate_chunk_tables + zipccl_compress_chunk_tables)
+    d_tabs = torch.zeros(8 * w.n_chunks, dtype=torch.uint8, device=dev)
+    d_ews = torch.empty(z.zipccl_estimate_chunk_tables_workspace_size(w.n_chunks), dtype=torch.uint8, device=dev)
+    call = lambda: z.zipccl_estimate_chunk_tables(d_in, w.n_elems, w.dtype, w.n_chunks, w.chunk_elems, d_tabs, None, d_ews,
+                                                  stream=stream)
+    leg = {}
+    if steps:
+        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(steps)]
+        warm_up(call, 1)
+        for k in range(steps):
+            evs[k][0].record(stream)
+            call()
+            evs[k][1].record(stream)
+        torch.cuda.synchronize()
+        ts = [e[0].elapsed_time(e[1]) for e in evs]
+        ms = float(np.median(ts))
+        leg.update({"ms": round(ms, 4), "ms_min": round(float(min(ts)), 4), "hbm_frac": frac(w.nbytes, ms)})
+    else:
+        call()
+    z.zipccl_compress_chunk_tables(d_in, w.n_elems, w.dtype, w.n_chunks, w.chunk_elems, d_tabs, d_out, d_cb, d_ws, stream=stream)
+    torch.cuda.synchronize()
+    dec1 = d_tabs.view(-1, 8)[:, 1].cpu().numpy()
+    leg.update({"dec1_min": int(dec1.min()), "dec1_max": int(dec1.max()),
+                "ratio_with_estimated_tables": round(w.nbytes / int(d_cb.sum().item()), 5)})
+    out["robust_median_per_chunk"] = leg
     return out
 
 

@@ -192,6 +192,28 @@ size_t zipccl_estimate_robust_workspace_size(void);
 zipccl_status_t zipccl_estimate_table_robust(const void* d_in, size_t n_elems, zipccl_dtype_t dt,
                                              zipccl_table_t* d_table, double* d_sigma,
                                              void* d_workspace, size_t workspace_bytes, void* stream);
+/*
+ * One table per peer chunk.  Section 4.1 takes sigma per layer; the chunks of one collective call may hold
+ * different layers, experts or peers' contributions whose scales differ by orders of magnitude, and every chunk
+ * header carries its own table anyway (the decoders read it per slot).  zipccl_estimate_chunk_tables is
+ * zipccl_estimate_table_robust applied to every chunk of the split on its own, in one pass over the tensor;
+ * zipccl_compress_chunk_tables is zipccl_compress with chunk c coded by d_tables[c].
+ *   d_tables     device, 8-byte aligned, n_chunks tables (written by the estimate, read by the compress)
+ *   d_sigmas     device, n_chunks doubles, may be NULL
+ *   d_workspace  of the estimate: 8-byte aligned, >= zipccl_estimate_chunk_tables_workspace_size(n_chunks)
+ *                bytes (256 KiB per chunk); contents are overwritten
+ * Chunk split and all other arguments as for zipccl_compress.
+ */
+size_t zipccl_estimate_chunk_tables_workspace_size(uint32_t n_chunks);
+zipccl_status_t zipccl_estimate_chunk_tables(const void* d_in, size_t n_elems, zipccl_dtype_t dt,
+                                             uint32_t n_chunks, const uint64_t* chunk_elems,
+                                             zipccl_table_t* d_tables, double* d_sigmas,
+                                             void* d_workspace, size_t workspace_bytes, void* stream);
+zipccl_status_t zipccl_compress_chunk_tables(const void* d_in, size_t n_elems, zipccl_dtype_t dt,
+                                             uint32_t n_chunks, const uint64_t* chunk_elems,
+                                             const zipccl_table_t* d_tables,
+                                             void* d_out, size_t out_capacity, uint64_t* d_chunk_bytes,
+                                             void* d_workspace, size_t workspace_bytes, void* stream);
 zipccl_status_t zipccl_compress_device_table(const void* d_in, size_t n_elems, zipccl_dtype_t dt,
                                              uint32_t n_chunks, const uint64_t* chunk_elems,
                                              const zipccl_table_t* d_table,

@@ -65,3 +65,21 @@ def robust_table(words, dtype):
     if not (s > 0.0) or not np.isfinite(s):
         return np.array([0, 1, 2, 3, 4, 5, 6, 7], dtype=np.uint8), s
     return zo.build_table(s), s
+
+
+def robust_chunk_tables(words, dtype, n_chunks, chunk_elems=None):
+    """One table per peer chunk: robust_table of every chunk of the split on its own (section 4.1 takes sigma per
+    layer; the chunks of a collective call may hold different layers or experts).  Returns (uint8[n_chunks, 8],
+    float64[n_chunks])."""
+    w = np.ascontiguousarray(words).reshape(-1)
+    if chunk_elems is None:
+        assert w.size % n_chunks == 0
+        chunk_elems = [w.size // n_chunks] * n_chunks
+    decs, sigmas, start = [], [], 0
+    for n in chunk_elems:
+        d, s = robust_table(w[start:start + int(n)], dtype)
+        decs.append(d)
+        sigmas.append(s)
+        start += int(n)
+    assert start == w.size
+    return np.array(decs, dtype=np.uint8).reshape(n_chunks, 8), np.array(sigmas, dtype=np.float64)

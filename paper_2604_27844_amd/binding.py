@@ -59,6 +59,12 @@ def _load():
     lib.zipccl_compress_min_workspace_size.argtypes = [sz, i32, u32, vp]
     lib.zipccl_compress.restype = i32
     lib.zipccl_compress.argtypes = [vp, sz, i32, u32, vp, tp, vp, sz, vp, vp, sz, vp]
+    lib.zipccl_estimate_chunk_tables_workspace_size.restype = sz
+    lib.zipccl_estimate_chunk_tables_workspace_size.argtypes = [u32]
+    lib.zipccl_estimate_chunk_tables.restype = i32
+    lib.zipccl_estimate_chunk_tables.argtypes = [vp, sz, i32, u32, vp, vp, vp, vp, sz, vp]
+    lib.zipccl_compress_chunk_tables.restype = i32
+    lib.zipccl_compress_chunk_tables.argtypes = [vp, sz, i32, u32, vp, vp, vp, sz, vp, vp, sz, vp]
     lib.zipccl_compress_static.restype = i32
     lib.zipccl_compress_static.argtypes = [vp, sz, i32, u32, vp, tp, vp, sz, vp, vp]
     lib.zipccl_compress_device_table.restype = i32
@@ -91,7 +97,8 @@ EXPORTS = ("zipccl_build_table", "zipccl_max_compressed_size", "zipccl_chunk_slo
            "zipccl_compress_workspace_size", "zipccl_compress_min_workspace_size", "zipccl_compress", "zipccl_decompress", "zipccl_decompress_reduce", "zipccl_status_string",
            "zipccl_switch_prefers_zipped", "zipccl_fit_link_model",
            "zipccl_estimate_workspace_size", "zipccl_estimate_table", "zipccl_compress_device_table",
-           "zipccl_estimate_robust_workspace_size", "zipccl_estimate_table_robust", "zipccl_compress_static")
+           "zipccl_estimate_robust_workspace_size", "zipccl_estimate_table_robust", "zipccl_compress_static",
+           "zipccl_estimate_chunk_tables_workspace_size", "zipccl_estimate_chunk_tables", "zipccl_compress_chunk_tables")
 
 
 def _host_u64(chunk_elems):
@@ -237,6 +244,32 @@ def zipccl_estimate_table_robust(d_in, n_elems, dt, d_table, d_sigma, d_workspac
                                            _dptr(d_workspace), wsb, _stream(stream))
     if rc:
         raise ZipcclError(rc, "zipccl_estimate_table_robust")
+
+
+def zipccl_estimate_chunk_tables_workspace_size(n_chunks):
+    return int(_lib.zipccl_estimate_chunk_tables_workspace_size(int(n_chunks)))
+
+
+def zipccl_estimate_chunk_tables(d_in, n_elems, dt, n_chunks, chunk_elems, d_tables, d_sigmas, d_workspace, stream=None):
+    """d_tables: 8 * n_chunks bytes on the GPU; d_sigmas: n_chunks float64 on the GPU or None."""
+    _keep, p = _host_u64(chunk_elems)
+    wsb = d_workspace.numel() * d_workspace.element_size()
+    rc = _lib.zipccl_estimate_chunk_tables(_dptr(d_in), int(n_elems), dt, int(n_chunks), p, _dptr(d_tables),
+                                           _dptr(d_sigmas), _dptr(d_workspace), wsb, _stream(stream))
+    if rc:
+        raise ZipcclError(rc, "zipccl_estimate_chunk_tables")
+
+
+def zipccl_compress_chunk_tables(d_in, n_elems, dt, n_chunks, chunk_elems, d_tables, d_out, d_chunk_bytes,
+                                 d_workspace, stream=None, workspace_bytes=None):
+    _keep, p = _host_u64(chunk_elems)
+    cap = d_out.numel() * d_out.element_size()
+    wsb = d_workspace.numel() * d_workspace.element_size() if workspace_bytes is None else int(workspace_bytes)
+    rc = _lib.zipccl_compress_chunk_tables(_dptr(d_in), int(n_elems), dt, int(n_chunks), p, _dptr(d_tables),
+                                           _dptr(d_out), cap, _dptr(d_chunk_bytes), _dptr(d_workspace), wsb,
+                                           _stream(stream))
+    if rc:
+        raise ZipcclError(rc, "zipccl_compress_chunk_tables")
 
 
 def zipccl_compress_device_table(d_in, n_elems, dt, n_chunks, chunk_elems, d_table, d_out, d_chunk_bytes,

@@ -117,17 +117,18 @@ __global__ __launch_bounds__(kThreads) void k_estimate_finish(const MomentArgs a
  * Robust sigma (for Eq.5 / Eq.2 when the tensor is not the zero-mean Gaussian of section 4.1: outlier
  * channels, LayerNorm gains among matrix weights): the median of |w| over Phi^-1(3/4).  The median is taken
  * over the 15-bit magnitudes of the values' high 16-bit words, so it is a count: k_magnitude_hist builds the
- * histogram of all 32768 magnitudes (one workgroup per compute unit, the whole histogram in its LDS, one
- * LDS atomic per value; nonzero bins are added to the 64-bit histogram in the workspace, which k_clear_hist
- * zeroed), k_robust_finish finds the bin of rank (K - 1) / 2 among the K magnitudes that are neither zero nor
- * Inf/NaN.  Integer work until the final division: the result does not depend on any order.
+ * histogram of all 32768 magnitudes (about one workgroup per compute unit, the whole histogram in its LDS, one
+ * LDS atomic per value; nonzero bins are added to the chunk's 64-bit histogram in the workspace, which
+ * k_clear_hist zeroed), k_robust_finish finds the bin of rank (K - 1) / 2 among the K magnitudes that are neither
+ * zero nor Inf/NaN.  Integer work until the final division: the result does not depend on any order.
+ * Both take several chunks at once (one histogram and one table per chunk); the whole tensor is one chunk.
  */
 constexpr uint32_t kMagBins = 32768;
 constexpr uint32_t kHistThreads = 1024;
 
 __global__ __launch_bounds__(kHistThreads) void k_clear_hist(unsigned long long* hist)
 {
-    hist[blockIdx.x * kHistThreads + threadIdx.x] = 0ull;
+    hist[(uint64_t)blockIdx.x * kHistThreads + threadIdx.x] = 0ull;     /* grid = 32 workgroups per chunk */
 }
 
 template <int DT>
@@ -138,8 +139,14 @@ __global__ __launch_bounds__(kHistThreads) void k_magnitude_hist(const HistArgs 
     __shared__ uint32_t s_hist[kMagBins];                  /* 128 KiB */
     for (uint32_t i = threadIdx.x; i < kMagBins; i += kHistThreads) s_hist[i] = 0u;
     __syncthreads();
-    const bool aligned = (reinterpret_cast<uintptr_t>(a.in) & 15u) == 0;
-    const uint64_t n16 = aligned ? a.n / PER16 : 0;
+    /* grid = (workgroups per chunk, chunks); a chunk starts at some element of the tensor: the values in front of
+       its first 16-byte boundary and behind its last one are taken one by one, the rest in 16-byte pieces */
+    const uint32_t c = blockIdx.y;
+    const uint8_t* __restrict__ in = a.in + a.tab.elem_off[c] * ES;
+    const uint64_t n = a.tab.elem_off[c + 1] - a.tab.elem_off[c];
+    const uint64_t head = min(n, (uint64_t)(((16u - (uint32_t)(reinterpret_cast<uintptr_t>(in) & 15u)) & 15u) / ES));
+    const uint64_t n16 = (n - head) / PER16;
+    const uint8_t* __restrict__ mid = in + head * ES;
     const uint64_t stride = (uint64_t)gridDim.x * kHistThreads;
     auto count = [&](const u32x4& v) {
         const uint32_t w[4] = {v.x, v.y, v.z, v.w};
@@ -149,25 +156,30 @@ __global__ __launch_bounds__(kHistThreads) void k_magnitude_hist(const HistArgs 
             atomicAdd(&s_hist[(w[k] >> 16) & 0x7FFFu], 1u);
         }
     };
+    auto count_one = [&](uint64_t e) {
+        const uint32_t hi = DT == ZIPCCL_BF16 ? *reinterpret_cast<const uint16_t*>(in + e * 2)
+                                              : *reinterpret_cast<const uint32_t*>(in + e * 4) >> 16;
+        atomicAdd(&s_hist[hi & 0x7FFFu], 1u);
+    };
     uint64_t i = (uint64_t)blockIdx.x * kHistThreads + threadIdx.x;
     for (; i + 3 * stride < n16; i += 4 * stride) {           /* four loads in flight per thread */
         u32x4 v[4];
 #pragma unroll
-        for (uint32_t k = 0; k < 4; ++k) v[k] = ld_stream<u32x4>(a.in + (i + k * stride) * 16);
+        for (uint32_t k = 0; k < 4; ++k) v[k] = ld_stream<u32x4>(mid + (i + k * stride) * 16);
 #pragma unroll
         for (uint32_t k = 0; k < 4; ++k) count(v[k]);
     }
-    for (; i < n16; i += stride) count(ld_stream<u32x4>(a.in + i * 16));
-    /* the tail (and everything, for a misaligned tensor) element by element */
-    for (uint64_t e = n16 * PER16 + (uint64_t)blockIdx.x * kHistThreads + threadIdx.x; e < a.n; e += stride) {
-        const uint32_t hi = DT == ZIPCCL_BF16 ? *reinterpret_cast<const uint16_t*>(a.in + e * 2)
-                                              : *reinterpret_cast<const uint32_t*>(a.in + e * 4) >> 16;
-        atomicAdd(&s_hist[hi & 0x7FFFu], 1u);
+    for (; i < n16; i += stride) count(ld_stream<u32x4>(mid + i * 16));
+    if (blockIdx.x == 0) {                                    /* fewer than 16 values in all */
+        if (threadIdx.x < head) count_one(threadIdx.x);
+        const uint64_t done = head + n16 * PER16;
+        if (done + threadIdx.x < n) count_one(done + threadIdx.x);
     }
     __syncthreads();
+    unsigned long long* __restrict__ hist = a.hist + (uint64_t)c * kMagBins;
     for (uint32_t b = threadIdx.x; b < kMagBins; b += kHistThreads) {
-        const uint32_t c = s_hist[b];
-        if (c) atomicAdd(&a.hist[b], (unsigned long long)c);
+        const uint32_t cnt = s_hist[b];
+        if (cnt) atomicAdd(&hist[b], (unsigned long long)cnt);
     }
 }
 
@@ -184,13 +196,17 @@ __device__ __forceinline__ unsigned long long wave_incl_scan_u64(unsigned long l
 }
 
 /*
- * One workgroup.  Thread t answers for the 32 consecutive bins [32 t, 32 t + 32).  The 32768 counts are read with
+ * One workgroup per chunk.  Thread t answers for the 32 consecutive bins [32 t, 32 t + 32).  The 32768 counts are read with
  * coalesced loads (thread t holds bin 1024 r + t of every row r, all loads in flight together) and handed to their
  * owners through LDS, 4096 bins at a time; every thread sums its 32 bins, one scan over the 1024 sums finds the
  * thread that holds the rank, and that thread walks its bins.  Bins 0 (zero) and 0x7F80.. (Inf / NaN) do not count.
  */
 __global__ __launch_bounds__(kHistThreads) void k_robust_finish(const HistArgs a)
 {
+    /* grid = chunks */
+    const unsigned long long* __restrict__ hist = a.hist + (uint64_t)blockIdx.x * kMagBins;
+    uint8_t* const table = a.table + 8u * blockIdx.x;
+    double* const sigma = a.sigma ? a.sigma + blockIdx.x : nullptr;
     constexpr uint32_t kPer = kMagBins / kHistThreads;       /* 32 bins per thread, and rows of the coalesced read */
     constexpr uint32_t kWaves = kHistThreads / 64;           /* 16 */
     constexpr uint32_t kRound = 4096;                        /* bins handed over per round: 128 owners */
@@ -202,7 +218,7 @@ __global__ __launch_bounds__(kHistThreads) void k_robust_finish(const HistArgs a
 #pragma unroll
     for (uint32_t r = 0; r < kPer; ++r) {
         const uint32_t b = r * kHistThreads + t;
-        v[r] = (b != 0u && b < kFirstNonFinite) ? a.hist[b] : 0ull;
+        v[r] = (b != 0u && b < kFirstNonFinite) ? hist[b] : 0ull;
     }
     unsigned long long mine = 0;
 #pragma unroll
@@ -230,7 +246,7 @@ __global__ __launch_bounds__(kHistThreads) void k_robust_finish(const HistArgs a
         total += c;
     }
     if (total == 0ull) {
-        if (t == 0) table_from_sigma(__longlong_as_double(0x7FF8000000000000ll), a.table, a.sigma);
+        if (t == 0) table_from_sigma(__longlong_as_double(0x7FF8000000000000ll), table, sigma);
         return;
     }
     const unsigned long long rank = (total - 1ull) / 2ull, excl = before + inc - mine;
@@ -239,7 +255,7 @@ __global__ __launch_bounds__(kHistThreads) void k_robust_finish(const HistArgs a
 #pragma unroll
     for (uint32_t k = 0; k < kPer; ++k) {
         const uint32_t b = t * kPer + k;
-        c[k] = (b != 0u && b < kFirstNonFinite) ? a.hist[b] : 0ull;
+        c[k] = (b != 0u && b < kFirstNonFinite) ? hist[b] : 0ull;
     }
     unsigned long long run = excl;
     uint32_t bin = 0;
@@ -250,7 +266,7 @@ __global__ __launch_bounds__(kHistThreads) void k_robust_finish(const HistArgs a
         if (!found && rank < run) { found = true; bin = t * kPer + k; }
     }
     const double med = (double)__uint_as_float(bin << 16);
-    table_from_sigma(med / 0.6744897501960817, a.table, a.sigma);     /* Phi^-1(3/4) */
+    table_from_sigma(med / 0.6744897501960817, table, sigma);     /* Phi^-1(3/4) */
 }
 
 } // namespace
@@ -266,15 +282,20 @@ int launch_estimate(int dt, const MomentArgs& a, void* stream)
 }
 
 
+int launch_clear_hist(unsigned long long* hist, uint32_t n_chunks, void* stream)
+{
+    hipLaunchKernelGGL(k_clear_hist, dim3(n_chunks * (kMagBins / kHistThreads)), dim3(kHistThreads), 0, (hipStream_t)stream, hist);
+    return (int)hipGetLastError();
+}
+
 int launch_estimate_robust(int dt, const HistArgs& a, void* stream)
 {
     hipStream_t s = (hipStream_t)stream;
-    hipLaunchKernelGGL(k_clear_hist, dim3(kMagBins / kHistThreads), dim3(kHistThreads), 0, s, a.hist);
+    const dim3 grid(a.n_blocks, a.tab.n_chunks);
+    if (dt == ZIPCCL_BF16) hipLaunchKernelGGL((k_magnitude_hist<ZIPCCL_BF16>), grid, dim3(kHistThreads), 0, s, a);
+    else hipLaunchKernelGGL((k_magnitude_hist<ZIPCCL_FP32>), grid, dim3(kHistThreads), 0, s, a);
     if (hipGetLastError() != hipSuccess) return 1;
-    if (dt == ZIPCCL_BF16) hipLaunchKernelGGL((k_magnitude_hist<ZIPCCL_BF16>), dim3(a.n_blocks), dim3(kHistThreads), 0, s, a);
-    else hipLaunchKernelGGL((k_magnitude_hist<ZIPCCL_FP32>), dim3(a.n_blocks), dim3(kHistThreads), 0, s, a);
-    if (hipGetLastError() != hipSuccess) return 1;
-    hipLaunchKernelGGL(k_robust_finish, dim3(1), dim3(kHistThreads), 0, s, a);
+    hipLaunchKernelGGL(k_robust_finish, dim3(a.tab.n_chunks), dim3(kHistThreads), 0, s, a);
     return (int)hipGetLastError();
 }
 

@@ -304,8 +304,9 @@ __global__ __launch_bounds__(kThreads) void k_compress(const CompressArgs a)
     const uint32_t lane = lane_id();
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   /* keep wave-derived math scalar */
     /* the table is a kernel argument, or (estimated on the device) two words in device memory */
-    const uint32_t dec_lo = a.d_table ? a.d_table[0] : a.dec_lo;
-    const uint32_t dec_hi = a.d_table ? a.d_table[1] : a.dec_hi;
+    const uint32_t* __restrict__ tab_c = a.d_table + c * a.table_stride;      /* one table for all chunks, or one each */
+    const uint32_t dec_lo = a.d_table ? tab_c[0] : a.dec_lo;
+    const uint32_t dec_hi = a.d_table ? tab_c[1] : a.dec_hi;
     const uint32_t e0 = a.d_table ? (dec_lo >> 8) & 0xFFu : a.e0;
     const uint32_t k7 = ((e0 - 1u) << 7) * 0x00010001u;
 
@@ -445,8 +446,9 @@ __global__ __launch_bounds__(kThreads) void k_place(const CompressArgs a)
     const uint64_t n = a.tab.elem_off[c + 1] - a.tab.elem_off[c];
     uint8_t* __restrict__ slot = a.out + a.tab.slot_off[c];
     const SlotLayout L = slot_layout(n, DT);
-    const uint32_t dec_lo = a.d_table ? a.d_table[0] : a.dec_lo;
-    const uint32_t dec_hi = a.d_table ? a.d_table[1] : a.dec_hi;
+    const uint32_t* __restrict__ tab_c = a.d_table + c * a.table_stride;
+    const uint32_t dec_lo = a.d_table ? tab_c[0] : a.dec_lo;
+    const uint32_t dec_hi = a.d_table ? tab_c[1] : a.dec_hi;
 
     const uint32_t sub = threadIdx.x % kSub;
     const uint32_t tw = threadIdx.x / kSub;             /* tile inside the workgroup */

@@ -182,7 +182,7 @@ namespace {
 /* compress with the table either on the host (checked here) or in device memory (d_table) */
 zipccl_status_t compress_impl(const void* d_in, size_t n_elems, zipccl_dtype_t dt,
                               uint32_t n_chunks, const uint64_t* chunk_elems,
-                              const zipccl_table_t* table, const zipccl_table_t* d_table,
+                              const zipccl_table_t* table, const zipccl_table_t* d_table, bool table_per_chunk,
                               void* d_out, size_t out_capacity, uint64_t* d_chunk_bytes,
                               void* d_workspace, size_t workspace_bytes, void* stream)
 {
@@ -214,6 +214,7 @@ zipccl_status_t compress_impl(const void* d_in, size_t n_elems, zipccl_dtype_t d
     std::memset(&a, 0, sizeof a);
     if (d_table) {
         a.d_table = reinterpret_cast<const uint32_t*>(d_table);
+        a.table_stride = table_per_chunk ? 2u : 0u;
     } else {
         a.e0 = table->dec[1];
         std::memcpy(&a.dec_lo, table->dec, 4);
@@ -227,6 +228,7 @@ zipccl_status_t compress_impl(const void* d_in, size_t n_elems, zipccl_dtype_t d
         a.in = static_cast<const uint8_t*>(d_in) + elem_base * es;
         a.out = static_cast<uint8_t*>(d_out) + slot_off[c0];
         a.chunk_bytes = d_chunk_bytes ? d_chunk_bytes + c0 : nullptr;
+        if (d_table && table_per_chunk) a.d_table = reinterpret_cast<const uint32_t*>(d_table) + 2 * (uint64_t)c0;
         a.tile_total = reinterpret_cast<uint32_t*>(ws + wp.total_off) + tile_base;
         a.tile_prefix = reinterpret_cast<uint32_t*>(ws + wp.prefix_off) + tile_base;
         a.stash = stash ? ws + wp.stash_off + elem_base : nullptr;
@@ -258,7 +260,7 @@ zipccl_status_t zipccl_compress(const void* d_in, size_t n_elems, zipccl_dtype_t
                                 void* d_out, size_t out_capacity, uint64_t* d_chunk_bytes,
                                 void* d_workspace, size_t workspace_bytes, void* stream)
 {
-    return compress_impl(d_in, n_elems, dt, n_chunks, chunk_elems, table, nullptr, d_out, out_capacity,
+    return compress_impl(d_in, n_elems, dt, n_chunks, chunk_elems, table, nullptr, false, d_out, out_capacity,
                          d_chunk_bytes, d_workspace, workspace_bytes, stream);
 }
 
@@ -269,7 +271,18 @@ zipccl_status_t zipccl_compress_device_table(const void* d_in, size_t n_elems, z
                                              void* d_workspace, size_t workspace_bytes, void* stream)
 {
     if (!d_table) return ZIPCCL_ERR_INVALID_ARG;
-    return compress_impl(d_in, n_elems, dt, n_chunks, chunk_elems, nullptr, d_table, d_out, out_capacity,
+    return compress_impl(d_in, n_elems, dt, n_chunks, chunk_elems, nullptr, d_table, false, d_out, out_capacity,
+                         d_chunk_bytes, d_workspace, workspace_bytes, stream);
+}
+
+zipccl_status_t zipccl_compress_chunk_tables(const void* d_in, size_t n_elems, zipccl_dtype_t dt,
+                                             uint32_t n_chunks, const uint64_t* chunk_elems,
+                                             const zipccl_table_t* d_tables,
+                                             void* d_out, size_t out_capacity, uint64_t* d_chunk_bytes,
+                                             void* d_workspace, size_t workspace_bytes, void* stream)
+{
+    if (!d_tables) return ZIPCCL_ERR_INVALID_ARG;
+    return compress_impl(d_in, n_elems, dt, n_chunks, chunk_elems, nullptr, d_tables, true, d_out, out_capacity,
                          d_chunk_bytes, d_workspace, workspace_bytes, stream);
 }
 
@@ -286,7 +299,7 @@ zipccl_status_t zipccl_compress_static(const void* d_in, size_t n_elems, zipccl_
     void* ws = nullptr;
     size_t ws_bytes = 0;
     if (static_scratch(&ws, &ws_bytes) != 0) return ZIPCCL_ERR_DEVICE;
-    return compress_impl(d_in, n_elems, dt, n_chunks, chunk_elems, table, nullptr, d_out, out_capacity,
+    return compress_impl(d_in, n_elems, dt, n_chunks, chunk_elems, table, nullptr, false, d_out, out_capacity,
                          d_chunk_bytes, ws, ws_bytes, stream);
 }
 
@@ -315,24 +328,69 @@ zipccl_status_t zipccl_estimate_table(const void* d_in, size_t n_elems, zipccl_d
 
 size_t zipccl_estimate_robust_workspace_size(void) { return kHistBytes; }
 
+size_t zipccl_estimate_chunk_tables_workspace_size(uint32_t n_chunks) { return (size_t)kHistBytes * n_chunks; }
+
+zipccl_status_t zipccl_estimate_chunk_tables(const void* d_in, size_t n_elems, zipccl_dtype_t dt,
+                                             uint32_t n_chunks, const uint64_t* chunk_elems,
+                                             zipccl_table_t* d_tables, double* d_sigmas,
+                                             void* d_workspace, size_t workspace_bytes, void* stream)
+{
+    if (!dtype_ok(dt)) return ZIPCCL_ERR_UNSUPPORTED_DTYPE;
+    std::vector<uint64_t> ce;
+    if (!resolve_split(n_elems, n_chunks, chunk_elems, ce)) return ZIPCCL_ERR_INVALID_ARG;
+    if (!d_tables || !d_workspace || (!d_in && n_elems)) return ZIPCCL_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(d_in) % elem_size(dt)) || (reinterpret_cast<uintptr_t>(d_tables) % 8) ||
+        (reinterpret_cast<uintptr_t>(d_sigmas) % 8) || (reinterpret_cast<uintptr_t>(d_workspace) % 8))
+        return ZIPCCL_ERR_INVALID_ARG;
+    if (workspace_bytes < zipccl_estimate_chunk_tables_workspace_size(n_chunks)) return ZIPCCL_ERR_BUFFER_TOO_SMALL;
+    if ((uint64_t)n_chunks * (32768 / 1024) > 0x7FFFFFFFull) return ZIPCCL_ERR_INVALID_ARG;
+    unsigned long long* const hist = static_cast<unsigned long long*>(d_workspace);
+    if (launch_clear_hist(hist, n_chunks, stream) != 0) return ZIPCCL_ERR_DEVICE;
+    const std::vector<uint64_t> no_slots(n_chunks + 1, 0);            /* slot offsets play no part here */
+    HistArgs a;
+    uint64_t elem_base = 0;
+    for (uint32_t c0 = 0; c0 < n_chunks; c0 += kMaxBatch) {
+        const uint32_t nb = (n_chunks - c0) < kMaxBatch ? (n_chunks - c0) : kMaxBatch;
+        fill_tab(a.tab, ce, no_slots, c0, nb);
+        uint64_t largest = 0;
+        for (uint32_t c = 0; c < nb; ++c) largest = std::max(largest, ce[c0 + c]);
+        /* a workgroup counts in 32 bits, and wants about 64 values per thread at least; about one workgroup per
+           compute unit in all */
+        const uint64_t want = (largest + 65535) / 65536, cap = std::max<uint64_t>(1, kHistBlocks / nb);
+        a.n_blocks = (uint32_t)std::min(std::max<uint64_t>(want, 1), cap);
+        if (largest / a.n_blocks >= 0xFFFFFFFFull) return ZIPCCL_ERR_INVALID_ARG;
+        a.in = static_cast<const uint8_t*>(d_in) + elem_base * elem_size(dt);
+        a.hist = hist + (uint64_t)c0 * 32768;
+        a.table = reinterpret_cast<uint8_t*>(d_tables + c0);
+        a.sigma = d_sigmas ? d_sigmas + c0 : nullptr;
+        if (launch_estimate_robust(dt, a, stream) != 0) return ZIPCCL_ERR_DEVICE;
+        elem_base += a.tab.elem_off[nb];
+    }
+    return ZIPCCL_OK;
+}
+
 zipccl_status_t zipccl_estimate_table_robust(const void* d_in, size_t n_elems, zipccl_dtype_t dt,
                                              zipccl_table_t* d_table, double* d_sigma,
                                              void* d_workspace, size_t workspace_bytes, void* stream)
 {
+    if (n_elems >= ((size_t)1 << 40)) return ZIPCCL_ERR_INVALID_ARG;      /* a workgroup counts in 32 bits */
+    const uint64_t whole = n_elems;                                   /* the tensor as one chunk of any length */
     if (!dtype_ok(dt)) return ZIPCCL_ERR_UNSUPPORTED_DTYPE;
     if (!d_table || !d_workspace || (!d_in && n_elems)) return ZIPCCL_ERR_INVALID_ARG;
     if ((reinterpret_cast<uintptr_t>(d_in) % elem_size(dt)) || (reinterpret_cast<uintptr_t>(d_table) % 8) ||
         (reinterpret_cast<uintptr_t>(d_sigma) % 8) || (reinterpret_cast<uintptr_t>(d_workspace) % 8))
         return ZIPCCL_ERR_INVALID_ARG;
-    /* a workgroup counts in 32 bits: at most 2^32 - 1 values each */
-    if (n_elems / kHistBlocks >= 0xFFFFFFFFull) return ZIPCCL_ERR_INVALID_ARG;
     if (workspace_bytes < zipccl_estimate_robust_workspace_size()) return ZIPCCL_ERR_BUFFER_TOO_SMALL;
+    unsigned long long* const hist = static_cast<unsigned long long*>(d_workspace);
+    if (launch_clear_hist(hist, 1, stream) != 0) return ZIPCCL_ERR_DEVICE;
     HistArgs a;
-    a.in = static_cast<const uint8_t*>(d_in);
-    a.n = n_elems;
-    a.hist = static_cast<unsigned long long*>(d_workspace);
-    const uint64_t want = (n_elems + 65535) / 65536;             /* about 64 values per thread at least */
+    std::memset(&a.tab, 0, sizeof a.tab);
+    a.tab.n_chunks = 1;
+    for (uint32_t i = 1; i <= kMaxBatch; ++i) a.tab.elem_off[i] = whole;
+    const uint64_t want = (whole + 65535) / 65536;                    /* about 64 values per thread at least */
     a.n_blocks = (uint32_t)(want < 1 ? 1 : (want > kHistBlocks ? kHistBlocks : want));
+    a.in = static_cast<const uint8_t*>(d_in);
+    a.hist = hist;
     a.table = reinterpret_cast<uint8_t*>(d_table);
     a.sigma = d_sigma;
     return launch_estimate_robust(dt, a, stream) == 0 ? ZIPCCL_OK : ZIPCCL_ERR_DEVICE;

@@ -73,6 +73,7 @@ struct CompressArgs {
     uint32_t e0;             /* dec[1] */
     uint32_t dec_lo, dec_hi; /* dec[0..3], dec[4..7] packed little-endian */
     const uint32_t* d_table; /* when not null: the table lives in device memory (two words), e0/dec_* unused */
+    uint32_t table_stride;   /* words from one chunk's table to the next: 0 = one table for all chunks, 2 = one each */
     ChunkTab tab;
 };
 
@@ -92,12 +93,12 @@ constexpr uint32_t kHistBlocks = 256;                /* workgroups of the magnit
 constexpr uint32_t kHistBytes = 32768 * 8;           /* its workspace: one 64-bit count per 15-bit magnitude */
 
 struct HistArgs {
-    const uint8_t* in;
-    uint64_t n;
-    unsigned long long* hist;   /* 32768 counts, zeroed by the first kernel of the call */
-    uint32_t n_blocks;
-    uint8_t* table;          /* device zipccl_table_t (8 bytes) */
-    double* sigma;           /* may be null */
+    const uint8_t* in;       /* first element of the launch's first chunk */
+    unsigned long long* hist;   /* 32768 counts per chunk of the launch, zeroed by the first kernel of the call */
+    uint32_t n_blocks;       /* workgroups per chunk */
+    uint8_t* table;          /* device zipccl_table_t (8 bytes) per chunk of the launch */
+    double* sigma;           /* one per chunk of the launch; may be null */
+    ChunkTab tab;            /* the launch's chunks (elem_off; the other fields are not used) */
 };
 
 struct DecompressArgs {
@@ -128,6 +129,7 @@ enum CompressMode { kModeCount = 0, kModeEmit = 1, kModeStash = 2 };
 /* launchers implemented next to their kernels (zipccl_compress.hip, zipccl_decompress.hip, zipccl_aux.hip);
  * they return a hipError_t as int */
 int launch_estimate(int dt, const MomentArgs& a, void* stream);
+int launch_clear_hist(unsigned long long* hist, uint32_t n_chunks, void* stream);
 int launch_estimate_robust(int dt, const HistArgs& a, void* stream);
 int launch_compress(int dt, int mode, const CompressArgs& a, void* stream);
 /* device address and size of the library's own workspace on the current GPU (zipccl_compress_static) */

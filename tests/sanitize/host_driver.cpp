@@ -32,7 +32,14 @@ static void check_tab(const ChunkTab& t)
 }
 
 int launch_estimate(int, const MomentArgs& a, void*) { CHECK(a.n_blocks >= 1 && a.n_blocks <= kMomentBlocks); ++g_launches; return 0; }
-int launch_estimate_robust(int, const HistArgs& a, void*) { CHECK(a.n_blocks >= 1 && a.n_blocks <= kHistBlocks); ++g_launches; return 0; }
+int launch_clear_hist(unsigned long long* hist, uint32_t n_chunks, void*) { CHECK(hist != nullptr && n_chunks >= 1); ++g_launches; return 0; }
+int launch_estimate_robust(int, const HistArgs& a, void*)
+{
+    CHECK(a.n_blocks >= 1 && a.n_blocks <= kHistBlocks && a.tab.n_chunks >= 1 && a.tab.n_chunks <= kMaxBatch);
+    for (uint32_t c = 0; c < kMaxBatch; ++c) CHECK(a.tab.elem_off[c] <= a.tab.elem_off[c + 1]);
+    ++g_launches;
+    return 0;
+}
 int launch_compress(int, int, const CompressArgs& a, void*) { check_tab(a.tab); ++g_launches; return 0; }
 int launch_tile_scan(const CompressArgs& a, void*) { check_tab(a.tab); ++g_launches; return 0; }
 int launch_place(int, bool, const CompressArgs& a, void*) { check_tab(a.tab); ++g_launches; return 0; }
@@ -117,6 +124,11 @@ int main()
     CHECK(zipccl_decompress_reduce(out, big, in, 5000, ZIPCCL_BF16, 1024, ZIPCCL_BF16, nullptr, nullptr) == ZIPCCL_OK);
     CHECK(zipccl_estimate_table(in, 100000, ZIPCCL_BF16, (zipccl_table_t*)out, nullptr, ws, big, nullptr) == ZIPCCL_OK);
     CHECK(zipccl_estimate_table_robust(in, 100000, ZIPCCL_BF16, (zipccl_table_t*)out, nullptr, ws, big, nullptr) == ZIPCCL_OK);
+    CHECK(zipccl_estimate_chunk_tables(in, n, ZIPCCL_FP32, C, ce.data(), (zipccl_table_t*)out, nullptr, ws, big, nullptr) == ZIPCCL_OK);
+    CHECK(zipccl_estimate_chunk_tables(in, n, ZIPCCL_FP32, C, ce.data(), (zipccl_table_t*)out, nullptr, ws, 1000, nullptr) == ZIPCCL_ERR_BUFFER_TOO_SMALL);
+    CHECK(zipccl_estimate_chunk_tables(in, n + 1, ZIPCCL_FP32, C, ce.data(), (zipccl_table_t*)out, nullptr, ws, big, nullptr) == ZIPCCL_ERR_INVALID_ARG);
+    CHECK(zipccl_compress_chunk_tables(in, n, ZIPCCL_FP32, C, ce.data(), (const zipccl_table_t*)out, out, big, nullptr, ws, big, nullptr) == ZIPCCL_OK);
+    CHECK(zipccl_compress_chunk_tables(in, n, ZIPCCL_FP32, C, ce.data(), nullptr, out, big, nullptr, ws, big, nullptr) == ZIPCCL_ERR_INVALID_ARG);
     CHECK(g_launches > 0);
 
     /* switcher */

@@ -170,3 +170,61 @@ def test_robust_estimate_edge_cases():
         z.zipccl_estimate_table_robust(to_device_words(f), f.size, z.FP32, torch.zeros(8, dtype=torch.uint8, device=DEV),
                                        None, d_small)
     assert ei.value.code == 3
+
+
+def _chunk_tables_case(x, dtype, ce, label):
+    """Device per-chunk tables == oracle per-chunk tables (sigma bit-equal), and compressing with them gives, slot
+    by slot, the bytes the oracle produces for that chunk alone with that chunk's table."""
+    C = len(ce)
+    n = int(x.size)
+    print(f"[chunk tables] {label}: n={n} chunks={C}", flush=True)
+    decs, sig = osg.robust_chunk_tables(x, dtype, C, ce)
+    d_in = to_device_words(x)
+    d_tabs = torch.full((8 * C,), 0xEE, dtype=torch.uint8, device=DEV)
+    d_sig = torch.zeros(C, dtype=torch.float64, device=DEV)
+    d_ews = torch.full((z.zipccl_estimate_chunk_tables_workspace_size(C),), 0x77, dtype=torch.uint8, device=DEV)
+    z.zipccl_estimate_chunk_tables(d_in, n, dtype, C, ce, d_tabs, d_sig, d_ews)
+    torch.cuda.synchronize()
+    assert np.array_equal(d_tabs.cpu().numpy().reshape(C, 8), decs), label
+    got_sig = d_sig.cpu().numpy()
+    assert np.array_equal(np.isnan(got_sig), np.isnan(sig)) and np.array_equal(got_sig[~np.isnan(sig)], sig[~np.isnan(sig)]), label
+    cap = z.zipccl_max_compressed_size(n, dtype, C, ce)
+    off = z.zipccl_chunk_slot_offsets(n, dtype, C, ce)
+    for reread in (False, True):
+        d_out = torch.full((cap,), 0xA5, dtype=torch.uint8, device=DEV)
+        d_cb = torch.zeros(C, dtype=torch.int64, device=DEV)
+        d_ws = torch.empty(z.zipccl_compress_workspace_size(n, dtype, C, ce), dtype=torch.uint8, device=DEV)
+        wsb = z.zipccl_compress_min_workspace_size(n, dtype, C, ce) if reread else None
+        z.zipccl_compress_chunk_tables(d_in, n, dtype, C, ce, d_tabs, d_out, d_cb, d_ws, workspace_bytes=wsb)
+        torch.cuda.synchronize()
+        got, got_cb = d_out.cpu().numpy(), d_cb.cpu().numpy()
+        start = 0
+        for c in range(C):
+            ref, ref_cb, _ = oracle.compress(x[start:start + int(ce[c])], dtype, decs[c])
+            assert int(got_cb[c]) == int(ref_cb[0]), (label, c)
+            a = int(off[c])
+            assert np.array_equal(got[a:a + int(ref_cb[0])], ref[:int(ref_cb[0])]), (label, c)
+            start += int(ce[c])
+        d_back = torch.zeros_like(d_in)
+        d_st = torch.zeros(1, dtype=torch.int32, device=DEV)
+        z.zipccl_decompress(d_out, d_back, n, dtype, C, ce, d_st)
+        torch.cuda.synchronize()
+        assert int(d_st.item()) == 0 and torch.equal(d_back, d_in), label
+    return x.nbytes / float(got_cb.sum())
+
+
+def test_chunk_tables_match_oracle_and_follow_each_chunks_scale():
+    rng = np.random.default_rng(10)
+    sigmas = [1e-4, 0.02, 1.0, 37.0, 0.02]
+    ce = np.array([30000, 8192 * 3 + 1, 50001, 0, 12345], dtype=np.uint64)      # odd sizes: unaligned chunk starts; one empty
+    x = np.concatenate([W.f32_to_bf16_words(rng.standard_normal(int(n), dtype=np.float32) * np.float32(s)) for n, s in zip(ce, sigmas)])
+    ratio = _chunk_tables_case(x, z.BF16, ce, "scales 1e-4 .. 37, bf16")
+    assert ratio > 1.38
+    f = np.concatenate([(rng.standard_normal(int(n), dtype=np.float32) * np.float32(s)).view(np.uint32) for n, s in zip(ce, sigmas)])
+    _chunk_tables_case(f, z.FP32, ce, "scales 1e-4 .. 37, fp32")
+    w = W.make("c3", 1 / 32)                                                     # 64 ragged chunks
+    _chunk_tables_case(w.data, w.dtype, w.chunk_elems, w.name)
+    many = W.f32_to_bf16_words(rng.standard_normal(300 * 700, dtype=np.float32))  # more chunks than one launch holds
+    _chunk_tables_case(many, z.BF16, np.full(300, 700, dtype=np.uint64), "300 chunks")
+    tiny = np.array([0x3F80, 0x0000, 0x7F80, 0x4000, 0xC000, 0x0001, 0x4040], dtype=np.uint16)
+    _chunk_tables_case(tiny, z.BF16, np.array([1, 2, 0, 4], dtype=np.uint64), "tiny chunks")

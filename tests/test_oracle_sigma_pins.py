@@ -138,3 +138,26 @@ def test_robust_table_on_every_workload_is_the_nominal_one_or_better():
         nominal = oracle.compress(w.data, w.dtype, oracle.build_table(w.sigma), w.n_chunks, w.chunk_elems)[1].sum()
         robust = oracle.compress(w.data, w.dtype, dec, w.n_chunks, w.chunk_elems)[1].sum()
         assert float(robust) <= float(nominal) * 1.01, (name, s, list(dec))
+
+
+def test_robust_chunk_tables_follow_each_chunks_own_scale():
+    """Chunks whose scales differ by orders of magnitude each get the window of their own sigma; with one table
+    for all of them most chunks would be coded as zero-points only."""
+    rng = np.random.default_rng(7)
+    sigmas = [1e-4, 0.02, 1.0, 37.0]
+    ce = [30000, 8192, 50001, 12345]
+    x = np.concatenate([W.f32_to_bf16_words(rng.standard_normal(n, dtype=np.float32) * np.float32(s)) for n, s in zip(ce, sigmas)])
+    decs, est = osg.robust_chunk_tables(x, BF16, 4, ce)
+    for c, s in enumerate(sigmas):
+        assert list(decs[c]) == list(oracle.build_table(s)) and abs(est[c] / s - 1) < 0.05
+    # an empty chunk and a chunk of zeros fall back to the lowest window
+    decs, est = osg.robust_chunk_tables(np.concatenate([x[:100], np.zeros(50, np.uint16)]), BF16, 3, [100, 0, 50])
+    assert list(decs[1]) == [0, 1, 2, 3, 4, 5, 6, 7] and list(decs[2]) == [0, 1, 2, 3, 4, 5, 6, 7] and math.isnan(est[1])
+    # coded chunk by chunk with its own table, every chunk reaches the ratio of a Gaussian; with one table it cannot
+    sizes = []
+    start = 0
+    for c, n in enumerate(ce):
+        sizes.append(int(oracle.compress(x[start:start + n], BF16, osg.robust_chunk_tables(x, BF16, 4, ce)[0][c])[1][0]))
+        start += n
+    one = int(oracle.compress(x, BF16, osg.robust_table(x, BF16)[0], 4, ce)[1].sum())
+    assert x.nbytes / sum(sizes) > 1.38 and x.nbytes / one < 1.1
