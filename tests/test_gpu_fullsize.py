@@ -41,6 +41,27 @@ def test_fullsize_parity(name):
         assert np.array_equal(got[s:e], ref[s:e]), f"chunk {c} differs"
     ratio = w.nbytes / float(ref_cb.sum())
     print(f"[full] {w.name} ratio {ratio:.4f}", flush=True)
+    del ref, got
+    # the robust sigma at this size, in the launch configuration the benchmark times: the median it found must
+    # have the rank the definition gives it (lower median of the nonzero finite magnitudes of the high 16-bit
+    # words; counted here with plain comparisons, no sort), and the window must be the nominal sigma's
+    d_tab = torch.zeros(8, dtype=torch.uint8, device=DEV)
+    d_sig = torch.zeros(1, dtype=torch.float64, device=DEV)
+    d_ews = torch.full((z.zipccl_estimate_robust_workspace_size(),), 0x77, dtype=torch.uint8, device=DEV)
+    z.zipccl_estimate_table_robust(d_in, w.n_elems, w.dtype, d_tab, d_sig, d_ews)
+    torch.cuda.synchronize()
+    med = np.float32(float(d_sig.item()) * 0.6744897501960817)          # sigma = median / Phi^-1(3/4); the median is a bf16 value
+    med_word = int(np.array([med], dtype=np.float32).view(np.uint32)[0])
+    assert med_word & 0xFFFF == 0, hex(med_word)
+    med_bits = med_word >> 16
+    mag = (w.data if w.dtype == z.BF16 else (w.data >> np.uint32(16)).astype(np.uint16)) & np.uint16(0x7FFF)
+    counted = (mag != 0) & (mag < 0x7F80)
+    K = int(np.count_nonzero(counted))
+    below = int(np.count_nonzero(counted & (mag < med_bits)))
+    upto = int(np.count_nonzero(counted & (mag <= med_bits)))
+    assert below <= (K - 1) // 2 < upto, (name, K, below, upto, med_bits)
+    assert list(d_tab.cpu().numpy()) == list(oracle.build_table(w.sigma)), name
+    print(f"[full] {w.name} robust sigma {float(d_sig.item()):.6g}", flush=True)
 
 
 @pytest.mark.parametrize("dtype,n,sigma", [(z.BF16, 2 ** 32 - 1, 0.02), (z.FP32, 2 ** 31 + 4097, 0.5)],
