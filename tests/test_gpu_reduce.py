@@ -213,6 +213,52 @@ def test_estimate_compress_reduce_chain_replays_inside_a_hip_graph():
         assert np.array_equal(d_sum.cpu().numpy().view(np.uint32), want), rep
 
 
+def test_chunk_table_estimate_and_compress_chain_replays_inside_a_hip_graph():
+    """Per-chunk robust tables -> compress with them -> fused reduce, captured and replayed: the histogram state is
+    zeroed by a kernel of the chain itself, so every replay starts clean."""
+    from oracle import sigma as osg
+    P, n = 3, 4 * 8192 + 77
+    d_in = torch.zeros(P * n, dtype=torch.int16, device=DEV)
+    cap = z.zipccl_max_compressed_size(P * n, z.BF16, P)
+    d_comp = torch.empty(cap, dtype=torch.uint8, device=DEV)
+    d_ws = torch.empty(z.zipccl_compress_workspace_size(P * n, z.BF16, P), dtype=torch.uint8, device=DEV)
+    d_ews = torch.empty(z.zipccl_estimate_chunk_tables_workspace_size(P), dtype=torch.uint8, device=DEV)
+    d_tabs = torch.zeros(8 * P, dtype=torch.uint8, device=DEV)
+    d_sum = torch.zeros(n, dtype=torch.int32, device=DEV)
+    d_st = torch.zeros(1, dtype=torch.int32, device=DEV)
+
+    def chain():
+        z.zipccl_estimate_chunk_tables(d_in, P * n, z.BF16, P, None, d_tabs, None, d_ews)
+        z.zipccl_compress_chunk_tables(d_in, P * n, z.BF16, P, None, d_tabs, d_comp, None, d_ws)
+        z.zipccl_decompress_reduce(d_comp, d_sum, n, z.BF16, P, z.FP32, d_st)
+
+    rng = np.random.default_rng(13)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        chain()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        chain()
+    for rep in range(3):
+        scales = [0.01 * 9 ** rep, 3.0, 1e-3 * 2 ** rep]        # every peer's slice at its own scale
+        data = np.concatenate([W.f32_to_bf16_words(rng.standard_normal(n, dtype=np.float32) * np.float32(s)) for s in scales])
+        d_in.copy_(torch.from_numpy(data.view(np.int16)))
+        d_comp.fill_(0xA5)
+        d_sum.fill_(0x3C3C3C3C)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        decs, _ = osg.robust_chunk_tables(data, z.BF16, P)
+        assert np.array_equal(d_tabs.cpu().numpy().reshape(P, 8), decs), rep
+        slots = [oracle.compress(data[p * n:(p + 1) * n], z.BF16, decs[p])[0] for p in range(P)]
+        want = oracle.decompress_reduce(np.concatenate(slots), n, z.BF16, P, z.FP32)
+        assert int(d_st.item()) == 0
+        assert np.array_equal(d_sum.cpu().numpy().view(np.uint32), want), rep
+
+
 def test_reduce_of_the_largest_peer_count_with_rejected_slots_in_every_round():
     """1024 slots (the limit): headers are checked 256 at a time, the accepted ones listed in slot order;
     a rejected slot in each of those rounds (and two side by side) must only drop out of the sum."""

@@ -83,3 +83,39 @@ def test_static_workspace_compress_rejects_what_does_not_fit_and_bad_arguments()
         z.zipccl_compress_static(d_in, 16, z.BF16, 1, None, table, d_out[:128], None)
     assert ei.value.code == 3
     torch.cuda.synchronize()
+
+
+def test_static_workspace_compress_replays_inside_a_hip_graph():
+    """What the entry point is for: captured once (after a first call outside the capture, which looks up the
+    array's address), replayed on fresh input contents with the program's own eager work in between; every replay
+    must equal zipccl_compress on the same input."""
+    rng = np.random.default_rng(22)
+    ce = np.array([8192 * 5 + 3, 0, 20000, 8192 * 2], dtype=np.uint64)
+    n, C = int(ce.sum()), len(ce)
+    table = z.zipccl_build_table(0.3, z.BF16)
+    cap = z.zipccl_max_compressed_size(n, z.BF16, C, ce)
+    d_in = torch.zeros(n, dtype=torch.int16, device=DEV)
+    got = torch.empty(cap, dtype=torch.uint8, device=DEV)
+    got_cb = torch.zeros(C, dtype=torch.int64, device=DEV)
+    want = torch.empty(cap, dtype=torch.uint8, device=DEV)
+    want_cb = torch.zeros(C, dtype=torch.int64, device=DEV)
+    d_ws = torch.empty(z.zipccl_compress_workspace_size(n, z.BF16, C, ce), dtype=torch.uint8, device=DEV)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                              # first call on this GPU: outside the capture
+        z.zipccl_compress_static(d_in, n, z.BF16, C, ce, table, got, got_cb)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        z.zipccl_compress_static(d_in, n, z.BF16, C, ce, table, got, got_cb)
+    for rep in range(3):
+        x = W.f32_to_bf16_words(rng.standard_normal(n, dtype=np.float32) * np.float32(0.3 * 5 ** rep))
+        d_in.copy_(torch.from_numpy(x.view(np.int16)))         # eager work between replays
+        got.fill_(0xA5)
+        want.fill_(0xA5)
+        z.zipccl_compress(d_in, n, z.BF16, C, ce, table, want, want_cb, d_ws)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(got_cb, want_cb) and torch.equal(got, want), rep
