@@ -170,7 +170,7 @@ __global__ __launch_bounds__(kHistThreads) void k_magnitude_hist(const HistArgs 
         for (uint32_t k = 0; k < 4; ++k) count(v[k]);
     }
     for (; i < n16; i += stride) count(ld_stream<u32x4>(mid + i * 16));
-    if (blockIdx.x == 0) {                                    /* fewer than 16 values in all */
+    if (blockIdx.x == 0) {                                    /* head and tail: fewer than 16 bytes each */
         if (threadIdx.x < head) count_one(threadIdx.x);
         const uint64_t done = head + n16 * PER16;
         if (done + threadIdx.x < n) count_one(done + threadIdx.x);
@@ -196,8 +196,8 @@ __device__ __forceinline__ unsigned long long wave_incl_scan_u64(unsigned long l
 }
 
 /*
- * One workgroup per chunk.  Thread t answers for the 32 consecutive bins [32 t, 32 t + 32).  The 32768 counts are read with
- * coalesced loads (thread t holds bin 1024 r + t of every row r, all loads in flight together) and handed to their
+ * One workgroup per chunk.  Thread t answers for the 32 consecutive bins [32 t, 32 t + 32).  The 32768 counts are read
+ * with coalesced loads (thread t holds bin 1024 r + t of every row r, all loads in flight together) and handed to their
  * owners through LDS, 4096 bins at a time; every thread sums its 32 bins, one scan over the 1024 sums finds the
  * thread that holds the rank, and that thread walks its bins.  Bins 0 (zero) and 0x7F80.. (Inf / NaN) do not count.
  */
