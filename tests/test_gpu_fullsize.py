@@ -90,6 +90,26 @@ def test_one_chunk_of_the_largest_sizes(dtype, n, sigma):
     d_ws = torch.empty(z.zipccl_compress_workspace_size(n, dtype, 1), dtype=torch.uint8, device=DEV)
     d_back = torch.empty_like(d_in)
     d_st = torch.zeros(1, dtype=torch.int32, device=DEV)
+    # the robust sigma over 2^32 - 1 (2^31 + 4097) values: bin counts beyond 2^27, 64-bit sums in the finish kernel.
+    # The input is a block repeated, so its magnitude histogram is the block's times the repetitions plus the rest's;
+    # the median found must have the rank the definition gives it.
+    d_tab = torch.zeros(8, dtype=torch.uint8, device=DEV)
+    d_sig = torch.zeros(1, dtype=torch.float64, device=DEV)
+    d_ews = torch.full((z.zipccl_estimate_robust_workspace_size(),), 0x77, dtype=torch.uint8, device=DEV)
+    z.zipccl_estimate_table_robust(d_in, n, dtype, d_tab, d_sig, d_ews)
+    torch.cuda.synchronize()
+    mags = lambda a: ((a if dtype == z.BF16 else (a >> np.uint32(16))) & 0x7FFF).astype(np.int64)
+    reps = n // blk.size
+    hist = reps * np.bincount(mags(blk), minlength=32768) + np.bincount(mags(data[reps * blk.size:]), minlength=32768)
+    hist[0] = 0
+    hist[0x7F80:] = 0
+    K, cum = int(hist.sum()), np.cumsum(hist)
+    med_word = int(np.array([np.float32(float(d_sig.item()) * 0.6744897501960817)], dtype=np.float32).view(np.uint32)[0])
+    assert med_word & 0xFFFF == 0
+    b = med_word >> 16
+    assert int(cum[b - 1]) <= (K - 1) // 2 < int(cum[b]), (K, b)
+    assert list(d_tab.cpu().numpy()) == list(oracle.build_table(sigma))
+    print(f"[huge] robust sigma {float(d_sig.item()):.6g} over {K} magnitudes", flush=True)
     # full workspace: single pass with a stash; minimum workspace: the input is read twice
     for wsb in (None, z.zipccl_compress_min_workspace_size(n, dtype, 1)):
         print(f"[huge] GPU compress, workspace bytes {wsb}", flush=True)
