@@ -113,6 +113,43 @@ def test_reduce_flags_a_corrupt_slot_and_checks_arguments():
     assert ei.value.code == 1
 
 
+def test_reduce_flags_index_and_plane_damage_inside_a_slot():
+    """Damage behind a valid header: an index entry far outside the zero-point list, one that makes a group's slice
+    longer than a group, and plane bytes that disagree with the index about a group's count.  Each is flagged
+    (the sums of the damaged groups are unspecified), in the whole-tile kernel and in the general one, and no
+    access leaves the buffers (the clamps are the kernel's own)."""
+    rng = np.random.default_rng(8)
+    P = 3
+    for n in (6 * 2048 + 100, 700):
+        peers = _peers(rng, P, n, z.BF16, [0.02])
+        buf = _receive_buffer(peers, z.BF16, [0.02])
+        cap1 = z.zipccl_max_compressed_size(n, z.BF16, 1)
+        pad = lambda x: (x + 127) // 128 * 128
+        p0 = 128 + pad(n)                                     # first plane of a slot
+        idx = p0 + 3 * pad((n + 7) // 8)                      # its index
+        ng = (n + 511) // 512
+        pb = pad((n + 7) // 8)                                # bytes of one plane
+        zeros = [0x00, 0x00, 0x00, 0x00]
+        damage = {"index entry beyond the list": [(idx + 4 * (ng - 1), [0xFF, 0xFF, 0xFF, 0x7F])],
+                  "a slice longer than a group": [(idx + 4, [600 & 0xFF, 600 >> 8, 0x00, 0x00])],
+                  # code 0 for values 24..55 of group 0: 32 zero-points the index knows nothing of
+                  "plane bytes against the index": [(p0 + 3, zeros), (p0 + pb + 3, zeros), (p0 + 2 * pb + 3, zeros)]}
+        for label, edits in damage.items():
+            print(f"[reduce] n={n} damage: {label}", flush=True)
+            bad = buf.clone()
+            for at, val in edits:
+                bad[cap1 + at:cap1 + at + 4] = torch.tensor(val, dtype=torch.uint8, device=DEV)  # in slot 1
+            d_out = torch.full((n,), 0x3C3C3C3C, dtype=torch.int32, device=DEV)
+            d_st = torch.zeros(1, dtype=torch.int32, device=DEV)
+            z.zipccl_decompress_reduce(bad, d_out, n, z.BF16, P, z.FP32, d_st)
+            torch.cuda.synchronize()
+            assert int(d_st.item()) == 4, (n, label)
+            z.zipccl_decompress_reduce(buf, d_out, n, z.BF16, P, z.FP32, d_st)          # the intact buffer still sums
+            torch.cuda.synchronize()
+            assert np.array_equal(d_out.cpu().numpy().view(np.uint32),
+                                  oracle.decompress_reduce(buf.cpu().numpy(), n, z.BF16, P, z.FP32))
+
+
 def test_reduce_leaves_rejected_slots_out_of_the_sum():
     """A slot whose header is rejected is flagged and skipped; the others are summed in order
     (first slot rejected: the sum starts at the second).  Sizes cover the bounds-check-free
