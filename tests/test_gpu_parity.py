@@ -68,6 +68,37 @@ def test_ragged_chunks_with_empty_and_unaligned_starts(dtype, compress_path):
 
 
 @pytest.mark.parametrize("dtype", [z.BF16, z.FP32], ids=["bf16", "fp32"])
+def test_ragged_chunks_in_a_launch_of_more_than_64_mib(dtype):
+    """zipccl_decompress picks its tile by the bytes a launch writes: from 64 MiB on it decodes in tiles of
+    8 groups (4096 values), below in tiles of 16.  Same ragged shapes as the small case (empty chunks, chunks
+    around one and two of the small tiles, odd starts), followed by large odd chunks that carry the launch
+    past 64 MiB; element by element against the oracle, and a damaged index entry deep in a large chunk must
+    be flagged."""
+    es = 2 if dtype == z.BF16 else 4
+    big = (66 << 20) // es // 4
+    ce = np.array([0, 1, 4095, 4096, 4097, 3, 0, 8191, 8193, 12289, 513, 7, big + 1, big + 4095, 0, big + 4097, big - 511],
+                  dtype=np.uint64)
+    n = int(ce.sum())
+    assert n * es >= 64 << 20
+    rng = np.random.default_rng(11 + dtype)
+    f = rng.standard_normal(n, dtype=np.float32) * np.float32(0.5)
+    data = W.f32_to_bf16_words(f) if dtype == z.BF16 else f.view(np.uint32).copy()
+    del f
+    _say(f"[ragged-large] dtype={dtype} n={n} chunks={len(ce)}")
+    got, got_cb, off = check_parity(data, dtype, 0.5, len(ce), ce, label="ragged-large")
+    c = 13                                                   # big + 4095 values
+    nc = int(ce[c])
+    pad = lambda x: (x + 127) // 128 * 128
+    lay_idx = 128 + pad(nc) + (pad(2 * nc) if dtype == z.FP32 else 0) + 3 * pad((nc + 7) // 8)
+    g = (nc // 512) - 3
+    bad = torch.from_numpy(got).to(DEV)
+    pos = int(off[c]) + lay_idx + 4 * g
+    bad[pos:pos + 4] = torch.tensor([0xFF, 0xFF, 0xFF, 0x7F], dtype=torch.uint8, device=DEV)
+    _, st = gpu_decompress(bad, n, dtype, len(ce), ce)
+    assert st == 4
+
+
+@pytest.mark.parametrize("dtype", [z.BF16, z.FP32], ids=["bf16", "fp32"])
 def test_chunk_starts_of_every_alignment_with_whole_tiles(dtype, compress_path):
     # chunk starts (in bf16 bytes) at 0, 4, 49168, 81936, 81944 and 114714: multiples of 16, of 8, of 4 and
     # of 2 only, each followed by whole tiles (the vector path takes any dword-aligned start, the
