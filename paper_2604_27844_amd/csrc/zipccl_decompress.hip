@@ -759,12 +759,14 @@ __device__ __forceinline__ void reduce_stages(const ReduceArgs& a, const SlotLay
 }
 
 /*
- * a.gpw = groups per wave: the larger, the fewer workgroups pay for the header checks and the table
- * build; 1 for small shards so that there are enough workgroups to fill the chip.  Dynamic LDS: one
- * 32-bit word per peer.  FAST: every group of the launch is complete and the output dword-aligned.
+ * One launch covers a call: workgroups 0 .. a.n_full - 1 take whole tiles of a.gpw groups per wave (every group
+ * complete, the output dword-aligned: the form without bounds checks), the workgroups after them the rest of the
+ * shard in tiles of a.gpw_rest groups per wave through the general form.  Groups per wave: the larger, the fewer
+ * workgroups pay for the header checks and the table build; 1 for small shards, and for the rest behind whole
+ * tiles, so that there are enough workgroups to fill the chip.  Dynamic LDS: one 32-bit word per peer.
  */
-template <int DT, int ODT, bool FAST>
-__global__ __launch_bounds__(kThreads, !FAST ? 4 : DT == ZIPCCL_BF16 ? 8 : 6) void k_decompress_reduce(const ReduceArgs a)
+template <int DT, int ODT>
+__global__ __launch_bounds__(kThreads, DT == ZIPCCL_BF16 ? 8 : 6) void k_decompress_reduce(const ReduceArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t s_dyn[];
     uint32_t* s_peer = reinterpret_cast<uint32_t*>(s_dyn);     /* the accepted slots, in slot order */
@@ -776,8 +778,11 @@ __global__ __launch_bounds__(kThreads, !FAST ? 4 : DT == ZIPCCL_BF16 ? 8 : 6) vo
     build_tables(s_tab);
 
     const uint64_t n = a.n;
-    const uint32_t kRTile = kGroup * kWavesPerBlock * a.gpw;
-    const uint64_t ts = a.first_elem + (uint64_t)blockIdx.x * kRTile;
+    const bool whole = blockIdx.x < a.n_full;                 /* workgroup-uniform */
+    const uint32_t gpw = whole ? a.gpw : a.gpw_rest;
+    constexpr uint64_t kGroupStride = (uint64_t)kGroup * kWavesPerBlock;
+    const uint64_t ts = whole ? (uint64_t)blockIdx.x * (kGroupStride * a.gpw)
+                              : (uint64_t)a.n_full * (kGroupStride * a.gpw) + (uint64_t)(blockIdx.x - a.n_full) * (kGroupStride * a.gpw_rest);
     const SlotLayout L = slot_layout(n, DT);
     const uint32_t lane = lane_id();
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   /* scalar: group addresses are wave-uniform */
@@ -812,12 +817,12 @@ __global__ __launch_bounds__(kThreads, !FAST ? 4 : DT == ZIPCCL_BF16 ? 8 : 6) vo
 
     /* this wave's groups start at gs0, gs0 + 2048, ...; those that begin inside n count */
     const uint64_t gs0 = ts + (uint64_t)wave * kGroup;
-    constexpr uint64_t kGroupStride = (uint64_t)kGroup * kWavesPerBlock;
-    uint32_t n_groups = a.gpw;
-    if (!FAST) n_groups = gs0 >= n ? 0u : (uint32_t)min((uint64_t)a.gpw, (n - gs0 + kGroupStride - 1) / kGroupStride);
+    uint32_t n_groups = gpw;
+    if (!whole) n_groups = gs0 >= n ? 0u : (uint32_t)min((uint64_t)gpw, (n - gs0 + kGroupStride - 1) / kGroupStride);
     if (n_groups != 0u) {
         if (n_acc != 0u) {
-            reduce_stages<DT, ODT, FAST>(a, L, gs0, n_groups, n_acc, lane, s_esc[wave], s_tab, s_peer, n_acc == a.n_peers, bad);
+            if (whole) reduce_stages<DT, ODT, true>(a, L, gs0, n_groups, n_acc, lane, s_esc[wave], s_tab, s_peer, n_acc == a.n_peers, bad);
+            else reduce_stages<DT, ODT, false>(a, L, gs0, n_groups, n_acc, lane, s_esc[wave], s_tab, s_peer, n_acc == a.n_peers, bad);
         } else {
             /* no slot accepted: the sum of nothing */
             constexpr uint32_t OES = ODT == ZIPCCL_BF16 ? 2u : 4u;
@@ -874,36 +879,26 @@ int launch_decompress_reduce(int dt, int out_dt, const ReduceArgs& a, void* stre
     ReduceArgs b = a;
     b.gpw = a.n >= (uint64_t)kTile * 2048u ? kGroupsPerWave : 1u;
     const uint64_t per = (uint64_t)kGroup * kWavesPerBlock * b.gpw;
-    /* whole tiles with a dword-aligned output go to the kernel without bounds checks, the rest (at most one
-       tile, or everything when the output is only 2-byte aligned) to the general one */
+    /* whole tiles with a dword-aligned output go through the form without bounds checks, the rest (under one
+       tile, or everything when the output is only 2-byte aligned) through the general one, in the same launch */
     const size_t lds_bytes = sizeof(uint32_t) * a.n_peers;
     const bool aligned = (reinterpret_cast<uintptr_t>(a.out) & 3u) == 0;
     const uint64_t full = aligned ? a.n / per : 0;
     const uint64_t rest = a.n - full * per;
-#define ZIPCCL_REDUCE(FAST, GRID)                                                                                      \
-    do {                                                                                                               \
-        if (dt == ZIPCCL_BF16 && out_dt == ZIPCCL_FP32)                                                                \
-            hipLaunchKernelGGL((k_decompress_reduce<ZIPCCL_BF16, ZIPCCL_FP32, FAST>), GRID, block, lds_bytes, s, b);           \
-        else if (dt == ZIPCCL_BF16)                                                                                    \
-            hipLaunchKernelGGL((k_decompress_reduce<ZIPCCL_BF16, ZIPCCL_BF16, FAST>), GRID, block, lds_bytes, s, b);           \
-        else if (out_dt == ZIPCCL_FP32)                                                                                \
-            hipLaunchKernelGGL((k_decompress_reduce<ZIPCCL_FP32, ZIPCCL_FP32, FAST>), GRID, block, lds_bytes, s, b);           \
-        else                                                                                                           \
-            hipLaunchKernelGGL((k_decompress_reduce<ZIPCCL_FP32, ZIPCCL_BF16, FAST>), GRID, block, lds_bytes, s, b);           \
-    } while (0)
-    if (full) {
-        b.first_elem = 0;
-        const dim3 grid((uint32_t)full);
-        ZIPCCL_REDUCE(true, grid);
-    }
-    if (rest || a.n == 0) {     /* n == 0: one workgroup that only checks the headers */
-        b.first_elem = full * per;
-        if (full) b.gpw = 1;    /* under a tile is left: one group per wave, so that it is not one workgroup's crawl */
-        const uint64_t per_rest = (uint64_t)kGroup * kWavesPerBlock * b.gpw;
-        const dim3 grid((uint32_t)(rest == 0 ? 1 : (rest + per_rest - 1) / per_rest));
-        ZIPCCL_REDUCE(false, grid);
-    }
-#undef ZIPCCL_REDUCE
+    b.n_full = (uint32_t)full;
+    b.gpw_rest = full ? 1u : b.gpw;     /* under a tile is left: one group per wave, so that it is not one workgroup's crawl */
+    const uint64_t per_rest = (uint64_t)kGroup * kWavesPerBlock * b.gpw_rest;
+    uint64_t n_rest = (rest + per_rest - 1) / per_rest;
+    if (a.n == 0) n_rest = 1;           /* one workgroup that only checks the headers */
+    const dim3 grid((uint32_t)(full + n_rest));
+    if (dt == ZIPCCL_BF16 && out_dt == ZIPCCL_FP32)
+        hipLaunchKernelGGL((k_decompress_reduce<ZIPCCL_BF16, ZIPCCL_FP32>), grid, block, lds_bytes, s, b);
+    else if (dt == ZIPCCL_BF16)
+        hipLaunchKernelGGL((k_decompress_reduce<ZIPCCL_BF16, ZIPCCL_BF16>), grid, block, lds_bytes, s, b);
+    else if (out_dt == ZIPCCL_FP32)
+        hipLaunchKernelGGL((k_decompress_reduce<ZIPCCL_FP32, ZIPCCL_FP32>), grid, block, lds_bytes, s, b);
+    else
+        hipLaunchKernelGGL((k_decompress_reduce<ZIPCCL_FP32, ZIPCCL_BF16>), grid, block, lds_bytes, s, b);
     return (int)hipGetLastError();
 }
 

@@ -120,8 +120,10 @@ struct ReduceArgs {
     uint32_t* status;        /* may be null */
     uint64_t n;
     uint32_t n_peers;
-    uint32_t gpw;            /* groups per wave, set by the launcher */
-    uint64_t first_elem;     /* first value this launch covers, set by the launcher */
+    /* set by the launcher: */
+    uint32_t gpw;            /* groups per wave in the workgroups that take whole tiles */
+    uint32_t n_full;         /* how many those are: workgroups 0 .. n_full - 1 */
+    uint32_t gpw_rest;       /* groups per wave in the workgroups after them, which take the rest of the shard */
 };
 
 enum CompressMode { kModeCount = 0, kModeEmit = 1, kModeStash = 2 };
