@@ -763,9 +763,11 @@ __device__ __forceinline__ void reduce_stages(const ReduceArgs& a, const SlotLay
  * complete, the output dword-aligned: the form without bounds checks), the workgroups after them the rest of the
  * shard in tiles of a.gpw_rest groups per wave through the general form.  Groups per wave: the larger, the fewer
  * workgroups pay for the header checks and the table build; 1 for small shards, and for the rest behind whole
- * tiles, so that there are enough workgroups to fill the chip.  Dynamic LDS: one 32-bit word per peer.
+ * tiles, so that there are enough workgroups to fill the chip.  REST = false: the launch holds whole tiles only
+ * (the general form is compiled out: it costs the whole-tile workgroups a few per cent of vector instructions
+ * to share a kernel with it).  Dynamic LDS: one 32-bit word per peer.
  */
-template <int DT, int ODT>
+template <int DT, int ODT, bool REST>
 __global__ __launch_bounds__(kThreads, DT == ZIPCCL_BF16 ? 8 : 6) void k_decompress_reduce(const ReduceArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t s_dyn[];
@@ -778,7 +780,7 @@ __global__ __launch_bounds__(kThreads, DT == ZIPCCL_BF16 ? 8 : 6) void k_decompr
     build_tables(s_tab);
 
     const uint64_t n = a.n;
-    const bool whole = blockIdx.x < a.n_full;                 /* workgroup-uniform */
+    const bool whole = !REST || blockIdx.x < a.n_full;        /* workgroup-uniform */
     const uint32_t gpw = whole ? a.gpw : a.gpw_rest;
     constexpr uint64_t kGroupStride = (uint64_t)kGroup * kWavesPerBlock;
     const uint64_t ts = whole ? (uint64_t)blockIdx.x * (kGroupStride * a.gpw)
@@ -822,7 +824,7 @@ __global__ __launch_bounds__(kThreads, DT == ZIPCCL_BF16 ? 8 : 6) void k_decompr
     if (n_groups != 0u) {
         if (n_acc != 0u) {
             if (whole) reduce_stages<DT, ODT, true>(a, L, gs0, n_groups, n_acc, lane, s_esc[wave], s_tab, s_peer, n_acc == a.n_peers, bad);
-            else reduce_stages<DT, ODT, false>(a, L, gs0, n_groups, n_acc, lane, s_esc[wave], s_tab, s_peer, n_acc == a.n_peers, bad);
+            else if (REST) reduce_stages<DT, ODT, false>(a, L, gs0, n_groups, n_acc, lane, s_esc[wave], s_tab, s_peer, n_acc == a.n_peers, bad);
         } else {
             /* no slot accepted: the sum of nothing */
             constexpr uint32_t OES = ODT == ZIPCCL_BF16 ? 2u : 4u;
@@ -891,14 +893,20 @@ int launch_decompress_reduce(int dt, int out_dt, const ReduceArgs& a, void* stre
     uint64_t n_rest = (rest + per_rest - 1) / per_rest;
     if (a.n == 0) n_rest = 1;           /* one workgroup that only checks the headers */
     const dim3 grid((uint32_t)(full + n_rest));
-    if (dt == ZIPCCL_BF16 && out_dt == ZIPCCL_FP32)
-        hipLaunchKernelGGL((k_decompress_reduce<ZIPCCL_BF16, ZIPCCL_FP32>), grid, block, lds_bytes, s, b);
-    else if (dt == ZIPCCL_BF16)
-        hipLaunchKernelGGL((k_decompress_reduce<ZIPCCL_BF16, ZIPCCL_BF16>), grid, block, lds_bytes, s, b);
-    else if (out_dt == ZIPCCL_FP32)
-        hipLaunchKernelGGL((k_decompress_reduce<ZIPCCL_FP32, ZIPCCL_FP32>), grid, block, lds_bytes, s, b);
-    else
-        hipLaunchKernelGGL((k_decompress_reduce<ZIPCCL_FP32, ZIPCCL_BF16>), grid, block, lds_bytes, s, b);
+#define ZIPCCL_REDUCE(REST)                                                                                            \
+    do {                                                                                                               \
+        if (dt == ZIPCCL_BF16 && out_dt == ZIPCCL_FP32)                                                                \
+            hipLaunchKernelGGL((k_decompress_reduce<ZIPCCL_BF16, ZIPCCL_FP32, REST>), grid, block, lds_bytes, s, b);   \
+        else if (dt == ZIPCCL_BF16)                                                                                    \
+            hipLaunchKernelGGL((k_decompress_reduce<ZIPCCL_BF16, ZIPCCL_BF16, REST>), grid, block, lds_bytes, s, b);   \
+        else if (out_dt == ZIPCCL_FP32)                                                                                \
+            hipLaunchKernelGGL((k_decompress_reduce<ZIPCCL_FP32, ZIPCCL_FP32, REST>), grid, block, lds_bytes, s, b);   \
+        else                                                                                                           \
+            hipLaunchKernelGGL((k_decompress_reduce<ZIPCCL_FP32, ZIPCCL_BF16, REST>), grid, block, lds_bytes, s, b);   \
+    } while (0)
+    if (n_rest) ZIPCCL_REDUCE(true);
+    else ZIPCCL_REDUCE(false);
+#undef ZIPCCL_REDUCE
     return (int)hipGetLastError();
 }
 
