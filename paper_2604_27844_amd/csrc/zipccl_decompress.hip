@@ -873,13 +873,27 @@ int launch_decompress(int dt, const DecompressArgs& a, void* stream)
 }
 
 
+/*
+ * Groups per wave of the fused reduce, from timings on MI355X over shards of 2^22 to 2^27 values.  One group per
+ * wave while the shard gives the chip's resident workgroups (256 CUs x 8, or x 6 for fp32) too little to do
+ * for a second group to pay; two from there on; four only for bf16 shards that fill the chip a whole number of
+ * times with four (2048 workgroups at once), where the last round leaves no compute unit idle: 3 % faster than two
+ * at 2^26 values, while between such sizes two groups per wave are 1-6 % faster than four.
+ */
+static uint32_t reduce_groups_per_wave(uint64_t n, int dt)
+{
+    const uint64_t tiles = n / kTile;
+    if (dt == ZIPCCL_FP32) return tiles < 2560u ? 1u : 2u;
+    if (tiles < 640u) return 1u;
+    return tiles % 2048u == 0 ? 4u : 2u;
+}
+
 int launch_decompress_reduce(int dt, int out_dt, const ReduceArgs& a, void* stream)
 {
     hipStream_t s = (hipStream_t)stream;
     const dim3 block(kThreads);
-    /* at least ~8 workgroups per CU before a workgroup takes more than one group per wave */
     ReduceArgs b = a;
-    b.gpw = a.n >= (uint64_t)kTile * 2048u ? kGroupsPerWave : 1u;
+    b.gpw = reduce_groups_per_wave(a.n, dt);
     const uint64_t per = (uint64_t)kGroup * kWavesPerBlock * b.gpw;
     /* whole tiles with a dword-aligned output go through the form without bounds checks, the rest (under one
        tile, or everything when the output is only 2-byte aligned) through the general one, in the same launch */

@@ -70,11 +70,14 @@ def test_single_slot_is_widened_exactly_for_every_bf16_pattern():
     _check([x, np.full(65536, 0x8000, dtype=np.uint16)], z.BF16, [1.0], z.FP32, "all patterns + (-0)")
 
 
-def test_reduce_large_shard_takes_the_four_groups_per_wave_form():
+@pytest.mark.parametrize("dtype,n", [(z.BF16, 2048 * 8192 + 5000), (z.BF16, 700 * 8192 + 4 * 2048 + 1500),
+                                     (z.FP32, 2600 * 8192 + 2048 + 77)], ids=["bf16_four", "bf16_two", "fp32_two"])
+def test_reduce_large_shards_take_several_groups_per_wave(dtype, n):
+    """Past a size that depends on the dtype a workgroup takes two groups per wave, and four for bf16 shards of a
+    multiple of 2048 whole tiles; the rest behind the whole tiles runs in the same launch."""
     rng = np.random.default_rng(44)
-    n = 2048 * 8192 + 5000                                   # past the size where workgroups take 4 groups per wave
     sig = [0.02, 0.03]
-    _check(_peers(rng, 2, n, z.BF16, sig), z.BF16, sig, z.FP32, "large shard")
+    _check(_peers(rng, 2, n, dtype, sig), dtype, sig, z.FP32, "large shard")
 
 
 def test_reduce_order_specials_and_cancellation():
