@@ -64,6 +64,42 @@ def test_fullsize_parity(name):
     print(f"[full] {w.name} robust sigma {float(d_sig.item()):.6g}", flush=True)
 
 
+@pytest.mark.parametrize("name", ["c3", "c4", "c5", "c5_fp32"])
+def test_fullsize_reduce_parity(name):
+    """The fused reduce in the configuration the benchmark times: the workload cut into 8 peer slices of one
+    shard, compressed as 8 slots, decoded and summed; every sum against the oracle's, all bits, for both output
+    types.  c3's shard is not a whole number of tiles (whole tiles and the rest in one launch, two groups per
+    wave), c4 and c5 fill the chip a whole number of times (four), c5_fp32 takes one group per wave."""
+    P = 8
+    w = W.make(name, 1.0)
+    assert w.n_elems % P == 0
+    n = w.n_elems // P
+    print(f"[full-reduce] {w.name}: {P} peers x {n} values ({n / 8192:.2f} tiles)", flush=True)
+    d_in = to_device_words(w.data)
+    table = z.zipccl_build_table(w.sigma, w.dtype)
+    cap = z.zipccl_max_compressed_size(w.n_elems, w.dtype, P)
+    assert cap == P * z.zipccl_max_compressed_size(n, w.dtype, 1)
+    d_comp = torch.full((cap,), 0xA5, dtype=torch.uint8, device=DEV)
+    d_ws = torch.empty(z.zipccl_compress_workspace_size(w.n_elems, w.dtype, P), dtype=torch.uint8, device=DEV)
+    z.zipccl_compress(d_in, w.n_elems, w.dtype, P, None, table, d_comp, None, d_ws)
+    torch.cuda.synchronize()
+    comp = d_comp.cpu().numpy()
+    del d_in, d_ws
+    for out_dt in (z.FP32, z.BF16):
+        print(f"[full-reduce] {w.name}: out dtype {out_dt}", flush=True)
+        d_out = torch.full((n,), 0x3C3C if out_dt == z.BF16 else 0x3C3C3C3C,
+                           dtype=torch.int16 if out_dt == z.BF16 else torch.int32, device=DEV)
+        d_st = torch.zeros(1, dtype=torch.int32, device=DEV)
+        z.zipccl_decompress_reduce(d_comp, d_out, n, w.dtype, P, out_dt, d_st)
+        torch.cuda.synchronize()
+        assert int(d_st.item()) == 0
+        got = d_out.cpu().numpy().view(np.uint16 if out_dt == z.BF16 else np.uint32)
+        want = oracle.decompress_reduce(comp, n, w.dtype, P, out_dt)
+        bad = np.nonzero(got != want)[0]
+        assert bad.size == 0, f"{name}: {bad.size} sums differ, first at {bad[:5]}"
+        del d_out, got, want
+
+
 @pytest.mark.parametrize("dtype,n,sigma", [(z.BF16, 2 ** 32 - 1, 0.02), (z.FP32, 2 ** 31 + 4097, 0.5)],
                          ids=["bf16_max_chunk", "fp32_sections_past_4GiB"])
 def test_one_chunk_of_the_largest_sizes(dtype, n, sigma):
