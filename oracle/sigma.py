@@ -83,3 +83,64 @@ def robust_chunk_tables(words, dtype, n_chunks, chunk_elems=None):
         start += int(n)
     assert start == w.size
     return np.array(decs, dtype=np.uint8).reshape(n_chunks, 8), np.array(sigmas, dtype=np.float64)
+
+
+# --- the same estimate from a sample of the tensor -----------------------------------------------------------
+#
+# The robust estimate reads the whole tensor to fix one integer (the window base).  A sample of one part in S
+# fixes the same integer unless sigma sits within a few parts in ten thousand of a window boundary, at 1/S of
+# the traffic.  The sample is taken in whole groups of 512 consecutive values (the codec's group: contiguous
+# kilobytes, so it reads at full memory efficiency), stratified: the groups of a chunk are cut into blocks of S
+# consecutive groups and one group is taken from every block, at a position inside the block that varies from
+# block to block in a fixed pseudo-random way.  A fixed position would alias with the tensor's own periods (a
+# row of 4096 values is 8 groups: a stride of 16 groups would only ever see columns 0..511); the varying one
+# visits all positions equally often.  Position in block k:
+#     ((k * 2654435761) mod 2^32) >> 16) mod S           (Knuth's multiplicative hash, upper half)
+# A block's group that lies past the end of the chunk (last block only) contributes nothing; a last group that
+# is cut short contributes the values it has.  S = 1 takes everything.
+
+SAMPLE_GROUP = 512
+SAMPLE_MULT = 2654435761
+
+
+def sampled_groups(n, stride):
+    """Indices of the groups of 512 values that the sample of a chunk of n values takes, in increasing order."""
+    stride = int(stride)
+    assert stride >= 1
+    ng = -(-int(n) // SAMPLE_GROUP)
+    out = []
+    for k in range(-(-ng // stride)):
+        g = k * stride + (((k * SAMPLE_MULT) % (1 << 32)) >> 16) % stride
+        if g < ng:
+            out.append(g)
+    return np.array(out, dtype=np.int64)
+
+
+def sample_of(words, stride):
+    """The sampled values themselves, in order."""
+    w = np.ascontiguousarray(words).reshape(-1)
+    g = sampled_groups(w.size, stride)
+    if g.size == 0:
+        return w[:0]
+    idx = (g[:, None] * SAMPLE_GROUP + np.arange(SAMPLE_GROUP, dtype=np.int64)[None, :]).reshape(-1)
+    return w[idx[idx < w.size]]
+
+
+def robust_sigma_sampled(words, dtype, stride):
+    return robust_sigma(sample_of(words, stride), dtype)
+
+
+def robust_chunk_tables_sampled(words, dtype, n_chunks, chunk_elems=None, stride=1):
+    """robust_table of every chunk's own sample (group numbers count from the chunk's first value)."""
+    w = np.ascontiguousarray(words).reshape(-1)
+    if chunk_elems is None:
+        assert w.size % n_chunks == 0
+        chunk_elems = [w.size // n_chunks] * n_chunks
+    decs, sigmas, start = [], [], 0
+    for n in chunk_elems:
+        d, s = robust_table(sample_of(w[start:start + int(n)], stride), dtype)
+        decs.append(d)
+        sigmas.append(s)
+        start += int(n)
+    assert start == w.size
+    return np.array(decs, dtype=np.uint8).reshape(n_chunks, 8), np.array(sigmas, dtype=np.float64)

@@ -161,3 +161,76 @@ def test_robust_chunk_tables_follow_each_chunks_own_scale():
         start += n
     one = int(oracle.compress(x, BF16, osg.robust_table(x, BF16)[0], 4, ce)[1].sum())
     assert x.nbytes / sum(sizes) > 1.38 and x.nbytes / one < 1.1
+
+
+# --- the robust estimate from a stratified sample of whole groups ---------------------------------------------
+
+def test_sample_with_stride_one_is_everything():
+    rng = np.random.default_rng(21)
+    for n in (0, 1, 511, 512, 513, 5000):
+        x = W.f32_to_bf16_words(rng.standard_normal(n, dtype=np.float32))
+        assert np.array_equal(osg.sample_of(x, 1), x)
+        a, b = osg.robust_sigma_sampled(x, BF16, 1), osg.robust_sigma(x, BF16)
+        assert a == b or (math.isnan(a) and math.isnan(b))
+
+
+def test_sampled_groups_hand_values_and_stratification():
+    # positions from Knuth's constant by plain integer arithmetic: ((k * 2654435761) mod 2^32) >> 16, mod S
+    assert list(osg.sampled_groups(8 * 16 * 512, 16)) == [0, 23, 46, 54, 77, 85, 108, 116]
+    assert list(osg.sampled_groups(8 * 4 * 512, 4)) == [0, 7, 10, 14, 17, 21, 24, 28]
+    for n, s in ((1_000_000, 16), (777_777, 8), (512 * 64 + 1, 64), (100, 4), (0, 4)):
+        g = osg.sampled_groups(n, s)
+        ng = -(-n // 512)
+        assert np.all(np.diff(g) > 0) and np.all(g < ng)
+        assert np.array_equal(np.unique(g // s), g // s)                       # one group per block at most
+        full_blocks = ng // s
+        assert np.array_equal((g // s)[:full_blocks], np.arange(full_blocks))  # and every full block has one
+        assert g.size in (full_blocks, -(-ng // s))
+    # a last group that is cut short gives the values it has; one that lies past the end gives nothing
+    x = np.arange(512 * 23 + 100, dtype=np.uint16)                             # groups 0..23, the last one of 100 values
+    s = osg.sample_of(x, 16)                                                   # takes groups 0 and 23
+    assert s.size == 512 + 100 and s[0] == 0 and s[512] == 512 * 23 and s[-1] == x[-1]
+    assert osg.sample_of(x[:512 * 23], 16).size == 512                         # group 23 is past the end now
+
+
+def test_sample_positions_do_not_alias_with_power_of_two_periods():
+    """A row of 4096 values is 8 groups, one of 8192 values 16: the position of the sampled group inside such a
+    period must take every value about equally often (a fixed stride of 16 groups would always give 0)."""
+    for s in (4, 16, 64):
+        g = osg.sampled_groups(512 * s * 8192, s)
+        assert g.size == 8192
+        assert set(g % s) == set(range(s))
+        for period in (8, 16, 32):
+            counts = np.bincount(g % period, minlength=period)
+            assert counts.min() > 0.8 * g.size / period and counts.max() < 1.2 * g.size / period, (s, period, counts)
+
+
+def test_sampled_estimate_finds_the_same_window_as_the_full_one():
+    rng = np.random.default_rng(22)
+    x = W.f32_to_bf16_words(rng.standard_normal(1 << 22, dtype=np.float32) * np.float32(0.02))
+    full = osg.robust_sigma(x, BF16)
+    for s in (4, 16, 64):
+        est = osg.robust_sigma_sampled(x, BF16, s)
+        assert abs(est / full - 1) < 0.01, (s, est, full)
+    # structure the sample must not trip over: outlier columns (c2) and gain rows among weights (c5)
+    for name, scale in (("c2", 1 / 4), ("c5", 1 / 64), ("c4", 1 / 32), ("c5_fp32", 1 / 32)):
+        w = W.make(name, scale)
+        want = list(osg.robust_table(w.data, w.dtype)[0])
+        for s in (8, 16):
+            d, sig = osg.robust_table(osg.sample_of(w.data, s), w.dtype)
+            assert list(d) == want, (name, s, sig)
+
+
+def test_sampled_chunk_tables_number_the_groups_from_each_chunks_start():
+    rng = np.random.default_rng(23)
+    ce = [512 * 40 + 7, 0, 300, 512 * 16 * 3]
+    sig = [1e-3, 1.0, 5.0, 0.3]
+    x = np.concatenate([W.f32_to_bf16_words(rng.standard_normal(n, dtype=np.float32) * np.float32(s)) for n, s in zip(ce, sig)])
+    decs, est = osg.robust_chunk_tables_sampled(x, BF16, 4, ce, stride=16)
+    start = 0
+    for c, n in enumerate(ce):
+        d, s = osg.robust_table(osg.sample_of(x[start:start + n], 16), BF16)
+        assert list(decs[c]) == list(d) and (est[c] == s or (math.isnan(est[c]) and math.isnan(s)))
+        start += n
+    assert list(decs[0]) == list(oracle.build_table(1e-3)) and list(decs[3]) == list(oracle.build_table(0.3))
+    assert list(decs[1]) == [0, 1, 2, 3, 4, 5, 6, 7]
