@@ -247,6 +247,29 @@ def run_estimate(w, r, steps):
     leg.update({"dec1_min": int(dec1.min()), "dec1_max": int(dec1.max()),
                 "ratio_with_estimated_tables": round(w.nbytes / int(d_cb.sum().item()), 5)})
     out["robust_median_per_chunk"] = leg
+    # the same per-chunk tables from one group of 512 values in every 16 (zipccl_estimate_chunk_tables_sampled)
+    SAMPLE = 16
+    d_tabs_s = torch.zeros(8 * w.n_chunks, dtype=torch.uint8, device=dev)
+    call = lambda: z.zipccl_estimate_chunk_tables_sampled(d_in, w.n_elems, w.dtype, w.n_chunks, w.chunk_elems, SAMPLE,
+                                                          d_tabs_s, None, d_ews, stream=stream)
+    leg = {"sample_stride": SAMPLE}
+    if steps:
+        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(steps)]
+        warm_up(call, 1)
+        for k in range(steps):
+            evs[k][0].record(stream)
+            call()
+            evs[k][1].record(stream)
+        torch.cuda.synchronize()
+        ts = [e[0].elapsed_time(e[1]) for e in evs]
+        leg.update({"ms": round(float(np.median(ts)), 4), "ms_min": round(float(min(ts)), 4)})
+    else:
+        call()
+    z.zipccl_compress_chunk_tables(d_in, w.n_elems, w.dtype, w.n_chunks, w.chunk_elems, d_tabs_s, d_out, d_cb, d_ws, stream=stream)
+    torch.cuda.synchronize()
+    leg.update({"tables_equal_to_the_full_estimate": bool(torch.equal(d_tabs_s, d_tabs)),
+                "ratio_with_estimated_tables": round(w.nbytes / int(d_cb.sum().item()), 5)})
+    out["robust_median_per_chunk_sampled"] = leg
     return out
 
 

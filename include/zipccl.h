@@ -209,6 +209,25 @@ zipccl_status_t zipccl_estimate_chunk_tables(const void* d_in, size_t n_elems, z
                                              uint32_t n_chunks, const uint64_t* chunk_elems,
                                              zipccl_table_t* d_tables, double* d_sigmas,
                                              void* d_workspace, size_t workspace_bytes, void* stream);
+/*
+ * The same tables from a sample of every chunk (section 4.1 takes sigma of the whole tensor; the window base it
+ * fixes is one integer, and one part in sample_stride of the values fixes the same integer unless sigma sits
+ * within the sampling error, a few parts in ten thousand for 2^20 sampled values, of a window boundary) at
+ * 1 / sample_stride of the memory traffic.  The sample consists of whole groups of 512 consecutive values, one
+ * from every block of sample_stride consecutive groups of a chunk (groups count from the chunk's first value),
+ * at position ((k * 2654435761 mod 2^32) >> 16) mod sample_stride inside block k; a block's group that lies
+ * past the chunk's end adds nothing, a last group cut short adds the values it has.  The estimate is then the
+ * one of zipccl_estimate_table_robust over the sampled values.
+ *   sample_stride   a power of two in [1, ZIPCCL_MAX_SAMPLE_STRIDE]; 1 = zipccl_estimate_chunk_tables
+ * Everything else, the workspace included, as for zipccl_estimate_chunk_tables (n_chunks = 1 for one table
+ * for the whole tensor, of up to ZIPCCL_MAX_CHUNK_ELEMS values).
+ */
+#define ZIPCCL_MAX_SAMPLE_STRIDE 4096u
+zipccl_status_t zipccl_estimate_chunk_tables_sampled(const void* d_in, size_t n_elems, zipccl_dtype_t dt,
+                                                     uint32_t n_chunks, const uint64_t* chunk_elems,
+                                                     uint32_t sample_stride,
+                                                     zipccl_table_t* d_tables, double* d_sigmas,
+                                                     void* d_workspace, size_t workspace_bytes, void* stream);
 zipccl_status_t zipccl_compress_chunk_tables(const void* d_in, size_t n_elems, zipccl_dtype_t dt,
                                              uint32_t n_chunks, const uint64_t* chunk_elems,
                                              const zipccl_table_t* d_tables,

@@ -9,7 +9,7 @@ _BINDING_NAMES = (
     "zipccl_build_table", "zipccl_max_compressed_size", "zipccl_chunk_slot_offsets", "zipccl_chunk_static_bytes",
     "zipccl_compress_workspace_size", "zipccl_compress_min_workspace_size", "zipccl_compress", "zipccl_decompress", "zipccl_decompress_reduce",
     "zipccl_status_string", "zipccl_switch_prefers_zipped", "zipccl_fit_link_model", "zipccl_estimate_workspace_size", "zipccl_estimate_table",
-    "zipccl_compress_device_table", "zipccl_estimate_robust_workspace_size", "zipccl_estimate_table_robust", "zipccl_compress_static", "zipccl_estimate_chunk_tables_workspace_size", "zipccl_estimate_chunk_tables", "zipccl_compress_chunk_tables", "ZipcclError", "BF16", "FP32", "GROUP", "lib_path",
+    "zipccl_compress_device_table", "zipccl_estimate_robust_workspace_size", "zipccl_estimate_table_robust", "zipccl_compress_static", "zipccl_estimate_chunk_tables_workspace_size", "zipccl_estimate_chunk_tables", "zipccl_estimate_chunk_tables_sampled", "zipccl_compress_chunk_tables", "ZipcclError", "BF16", "FP32", "GROUP", "lib_path",
 )
 
 

@@ -63,6 +63,8 @@ def _load():
     lib.zipccl_estimate_chunk_tables_workspace_size.argtypes = [u32]
     lib.zipccl_estimate_chunk_tables.restype = i32
     lib.zipccl_estimate_chunk_tables.argtypes = [vp, sz, i32, u32, vp, vp, vp, vp, sz, vp]
+    lib.zipccl_estimate_chunk_tables_sampled.restype = i32
+    lib.zipccl_estimate_chunk_tables_sampled.argtypes = [vp, sz, i32, u32, vp, u32, vp, vp, vp, sz, vp]
     lib.zipccl_compress_chunk_tables.restype = i32
     lib.zipccl_compress_chunk_tables.argtypes = [vp, sz, i32, u32, vp, vp, vp, sz, vp, vp, sz, vp]
     lib.zipccl_compress_static.restype = i32
@@ -98,7 +100,8 @@ EXPORTS = ("zipccl_build_table", "zipccl_max_compressed_size", "zipccl_chunk_slo
            "zipccl_switch_prefers_zipped", "zipccl_fit_link_model",
            "zipccl_estimate_workspace_size", "zipccl_estimate_table", "zipccl_compress_device_table",
            "zipccl_estimate_robust_workspace_size", "zipccl_estimate_table_robust", "zipccl_compress_static",
-           "zipccl_estimate_chunk_tables_workspace_size", "zipccl_estimate_chunk_tables", "zipccl_compress_chunk_tables")
+           "zipccl_estimate_chunk_tables_workspace_size", "zipccl_estimate_chunk_tables", "zipccl_estimate_chunk_tables_sampled",
+           "zipccl_compress_chunk_tables")
 
 
 def _host_u64(chunk_elems):
@@ -258,6 +261,18 @@ def zipccl_estimate_chunk_tables(d_in, n_elems, dt, n_chunks, chunk_elems, d_tab
                                            _dptr(d_sigmas), _dptr(d_workspace), wsb, _stream(stream))
     if rc:
         raise ZipcclError(rc, "zipccl_estimate_chunk_tables")
+
+
+def zipccl_estimate_chunk_tables_sampled(d_in, n_elems, dt, n_chunks, chunk_elems, sample_stride, d_tables, d_sigmas,
+                                         d_workspace, stream=None):
+    """As zipccl_estimate_chunk_tables, from one group of 512 values per sample_stride groups of every chunk."""
+    _keep, p = _host_u64(chunk_elems)
+    wsb = d_workspace.numel() * d_workspace.element_size()
+    rc = _lib.zipccl_estimate_chunk_tables_sampled(_dptr(d_in), int(n_elems), dt, int(n_chunks), p, int(sample_stride),
+                                                   _dptr(d_tables), _dptr(d_sigmas), _dptr(d_workspace), wsb,
+                                                   _stream(stream))
+    if rc:
+        raise ZipcclError(rc, "zipccl_estimate_chunk_tables_sampled")
 
 
 def zipccl_compress_chunk_tables(d_in, n_elems, dt, n_chunks, chunk_elems, d_tables, d_out, d_chunk_bytes,

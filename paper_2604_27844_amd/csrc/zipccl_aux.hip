@@ -126,9 +126,15 @@ __global__ __launch_bounds__(kThreads) void k_estimate_finish(const MomentArgs a
 constexpr uint32_t kMagBins = 32768;
 constexpr uint32_t kHistThreads = 1024;
 
-__global__ __launch_bounds__(kHistThreads) void k_clear_hist(unsigned long long* hist)
+constexpr uint32_t kClearThreads = 256, kClearPer = 4;   /* 16-byte stores per thread */
+
+__global__ __launch_bounds__(kClearThreads) void k_clear_hist(unsigned long long* hist)
 {
-    hist[(uint64_t)blockIdx.x * kHistThreads + threadIdx.x] = 0ull;     /* grid = 32 workgroups per chunk */
+    /* grid = 16 workgroups per chunk (the workspace is 8-byte aligned: the 16-byte stores are issued at that alignment) */
+    u32x4_a4* const p = reinterpret_cast<u32x4_a4*>(hist) + (uint64_t)blockIdx.x * (kClearPer * kClearThreads) + threadIdx.x;
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (uint32_t k = 0; k < kClearPer; ++k) p[k * kClearThreads] = zero;
 }
 
 template <int DT>
@@ -174,6 +180,83 @@ __global__ __launch_bounds__(kHistThreads) void k_magnitude_hist(const HistArgs 
         if (threadIdx.x < head) count_one(threadIdx.x);
         const uint64_t done = head + n16 * PER16;
         if (done + threadIdx.x < n) count_one(done + threadIdx.x);
+    }
+    __syncthreads();
+    unsigned long long* __restrict__ hist = a.hist + (uint64_t)c * kMagBins;
+    for (uint32_t b = threadIdx.x; b < kMagBins; b += kHistThreads) {
+        const uint32_t cnt = s_hist[b];
+        if (cnt) atomicAdd(&hist[b], (unsigned long long)cnt);
+    }
+}
+
+/*
+ * The same histogram over a sample of the chunk: its groups of 512 values are cut into blocks of S consecutive
+ * groups (S = a.sample_stride, a power of two) and one group is taken from every block, at position
+ * ((k * 2654435761 mod 2^32) >> 16) mod S inside block k (Knuth's multiplicative hash: the position varies from
+ * block to block, so the sample does not alias with the periods of the tensor itself, rows of 8 or 16 groups
+ * say).  A wave takes a group at a time, 8 values per lane, four groups in flight; a group that is cut short by
+ * the chunk's end, and every group of a chunk that does not start on a 16-byte boundary, is read value by value.
+ */
+template <int DT>
+__global__ __launch_bounds__(kHistThreads) void k_magnitude_hist_sampled(const HistArgs a)
+{
+    constexpr uint32_t ES = DT == ZIPCCL_BF16 ? 2u : 4u;
+    constexpr uint32_t NV = DT == ZIPCCL_BF16 ? 1u : 2u;    /* 16-byte pieces per lane and group */
+    constexpr uint32_t NF = 4;                              /* groups in flight per wave */
+    __shared__ uint32_t s_hist[kMagBins];                  /* 128 KiB */
+    for (uint32_t i = threadIdx.x; i < kMagBins; i += kHistThreads) s_hist[i] = 0u;
+    __syncthreads();
+    /* grid = (workgroups per chunk, chunks) */
+    const uint32_t c = blockIdx.y;
+    const uint8_t* __restrict__ in = a.in + a.tab.elem_off[c] * ES;
+    const uint64_t n = a.tab.elem_off[c + 1] - a.tab.elem_off[c];
+    const uint32_t S = a.sample_stride;
+    const uint64_t ng = (n + kGroup - 1) / kGroup;           /* at most 2^23 */
+    const uint32_t n_blk = (uint32_t)((ng + S - 1) / S);
+    const bool vec = (reinterpret_cast<uintptr_t>(in) & 15u) == 0;
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t n_waves = gridDim.x * (kHistThreads / 64u);
+    for (uint32_t k0 = blockIdx.x * (kHistThreads / 64u) + wave; k0 < n_blk; k0 += NF * n_waves) {
+        u32x4 v[NF][NV];
+        uint64_t first[NF];
+        bool some[NF], whole[NF];
+#pragma unroll
+        for (uint32_t u = 0; u < NF; ++u) {
+            const uint32_t k = k0 + u * n_waves;
+            const uint64_t g = (uint64_t)k * S + (((k * 2654435761u) >> 16) & (S - 1u));
+            first[u] = g * kGroup;
+            some[u] = k < n_blk && g < ng;
+            whole[u] = some[u] && vec && first[u] + kGroup <= n;
+            if (whole[u]) {
+#pragma unroll
+                for (uint32_t q = 0; q < NV; ++q)
+                    v[u][q] = ld_stream<u32x4>(in + (first[u] + lane * kLaneElems) * ES + 16u * q);
+            }
+        }
+#pragma unroll
+        for (uint32_t u = 0; u < NF; ++u) {
+            if (whole[u]) {
+#pragma unroll
+                for (uint32_t q = 0; q < NV; ++q) {
+                    const uint32_t w[4] = {v[u][q].x, v[u][q].y, v[u][q].z, v[u][q].w};
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        if (DT == ZIPCCL_BF16) atomicAdd(&s_hist[w[j] & 0x7FFFu], 1u);
+                        atomicAdd(&s_hist[(w[j] >> 16) & 0x7FFFu], 1u);
+                    }
+                }
+            } else if (some[u]) {
+                for (uint32_t j = 0; j < kLaneElems; ++j) {
+                    const uint64_t e = first[u] + lane * kLaneElems + j;
+                    if (e < n) {
+                        const uint32_t hi = DT == ZIPCCL_BF16 ? *reinterpret_cast<const uint16_t*>(in + e * 2)
+                                                              : *reinterpret_cast<const uint32_t*>(in + e * 4) >> 16;
+                        atomicAdd(&s_hist[hi & 0x7FFFu], 1u);
+                    }
+                }
+            }
+        }
     }
     __syncthreads();
     unsigned long long* __restrict__ hist = a.hist + (uint64_t)c * kMagBins;
@@ -284,7 +367,7 @@ int launch_estimate(int dt, const MomentArgs& a, void* stream)
 
 int launch_clear_hist(unsigned long long* hist, uint32_t n_chunks, void* stream)
 {
-    hipLaunchKernelGGL(k_clear_hist, dim3(n_chunks * (kMagBins / kHistThreads)), dim3(kHistThreads), 0, (hipStream_t)stream, hist);
+    hipLaunchKernelGGL(k_clear_hist, dim3(n_chunks * (kMagBins * 8u / (16u * kClearPer * kClearThreads))), dim3(kClearThreads), 0, (hipStream_t)stream, hist);
     return (int)hipGetLastError();
 }
 
@@ -292,7 +375,10 @@ int launch_estimate_robust(int dt, const HistArgs& a, void* stream)
 {
     hipStream_t s = (hipStream_t)stream;
     const dim3 grid(a.n_blocks, a.tab.n_chunks);
-    if (dt == ZIPCCL_BF16) hipLaunchKernelGGL((k_magnitude_hist<ZIPCCL_BF16>), grid, dim3(kHistThreads), 0, s, a);
+    if (a.sample_stride > 1u) {
+        if (dt == ZIPCCL_BF16) hipLaunchKernelGGL((k_magnitude_hist_sampled<ZIPCCL_BF16>), grid, dim3(kHistThreads), 0, s, a);
+        else hipLaunchKernelGGL((k_magnitude_hist_sampled<ZIPCCL_FP32>), grid, dim3(kHistThreads), 0, s, a);
+    } else if (dt == ZIPCCL_BF16) hipLaunchKernelGGL((k_magnitude_hist<ZIPCCL_BF16>), grid, dim3(kHistThreads), 0, s, a);
     else hipLaunchKernelGGL((k_magnitude_hist<ZIPCCL_FP32>), grid, dim3(kHistThreads), 0, s, a);
     if (hipGetLastError() != hipSuccess) return 1;
     hipLaunchKernelGGL(k_robust_finish, dim3(a.tab.n_chunks), dim3(kHistThreads), 0, s, a);

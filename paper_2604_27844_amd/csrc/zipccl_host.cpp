@@ -330,12 +330,14 @@ size_t zipccl_estimate_robust_workspace_size(void) { return kHistBytes; }
 
 size_t zipccl_estimate_chunk_tables_workspace_size(uint32_t n_chunks) { return (size_t)kHistBytes * n_chunks; }
 
-zipccl_status_t zipccl_estimate_chunk_tables(const void* d_in, size_t n_elems, zipccl_dtype_t dt,
-                                             uint32_t n_chunks, const uint64_t* chunk_elems,
-                                             zipccl_table_t* d_tables, double* d_sigmas,
-                                             void* d_workspace, size_t workspace_bytes, void* stream)
+static zipccl_status_t estimate_chunk_tables_impl(const void* d_in, size_t n_elems, zipccl_dtype_t dt,
+                                                  uint32_t n_chunks, const uint64_t* chunk_elems, uint32_t sample_stride,
+                                                  zipccl_table_t* d_tables, double* d_sigmas,
+                                                  void* d_workspace, size_t workspace_bytes, void* stream)
 {
     if (!dtype_ok(dt)) return ZIPCCL_ERR_UNSUPPORTED_DTYPE;
+    if (sample_stride == 0 || sample_stride > ZIPCCL_MAX_SAMPLE_STRIDE || (sample_stride & (sample_stride - 1u)))
+        return ZIPCCL_ERR_INVALID_ARG;
     std::vector<uint64_t> ce;
     if (!resolve_split(n_elems, n_chunks, chunk_elems, ce)) return ZIPCCL_ERR_INVALID_ARG;
     if (!d_tables || !d_workspace || (!d_in && n_elems)) return ZIPCCL_ERR_INVALID_ARG;
@@ -354,10 +356,13 @@ zipccl_status_t zipccl_estimate_chunk_tables(const void* d_in, size_t n_elems, z
         fill_tab(a.tab, ce, no_slots, c0, nb);
         uint64_t largest = 0;
         for (uint32_t c = 0; c < nb; ++c) largest = std::max(largest, ce[c0 + c]);
-        /* a workgroup counts in 32 bits, and wants about 64 values per thread at least; about one workgroup per
-           compute unit in all */
-        const uint64_t want = (largest + 65535) / 65536, cap = std::max<uint64_t>(1, kHistBlocks / nb);
+        /* a workgroup counts in 32 bits, and wants about 64 values per thread at least (of a sample: four groups
+           per wave); about one workgroup per compute unit in all */
+        const uint64_t sampled = (largest + sample_stride - 1) / sample_stride;
+        const uint64_t want = sample_stride > 1 ? (sampled + 32767) / 32768 : (largest + 65535) / 65536;
+        const uint64_t cap = std::max<uint64_t>(1, kHistBlocks / nb);
         a.n_blocks = (uint32_t)std::min(std::max<uint64_t>(want, 1), cap);
+        a.sample_stride = sample_stride;
         if (largest / a.n_blocks >= 0xFFFFFFFFull) return ZIPCCL_ERR_INVALID_ARG;
         a.in = static_cast<const uint8_t*>(d_in) + elem_base * elem_size(dt);
         a.hist = hist + (uint64_t)c0 * 32768;
@@ -367,6 +372,25 @@ zipccl_status_t zipccl_estimate_chunk_tables(const void* d_in, size_t n_elems, z
         elem_base += a.tab.elem_off[nb];
     }
     return ZIPCCL_OK;
+}
+
+zipccl_status_t zipccl_estimate_chunk_tables(const void* d_in, size_t n_elems, zipccl_dtype_t dt,
+                                             uint32_t n_chunks, const uint64_t* chunk_elems,
+                                             zipccl_table_t* d_tables, double* d_sigmas,
+                                             void* d_workspace, size_t workspace_bytes, void* stream)
+{
+    return estimate_chunk_tables_impl(d_in, n_elems, dt, n_chunks, chunk_elems, 1, d_tables, d_sigmas, d_workspace,
+                                      workspace_bytes, stream);
+}
+
+zipccl_status_t zipccl_estimate_chunk_tables_sampled(const void* d_in, size_t n_elems, zipccl_dtype_t dt,
+                                                     uint32_t n_chunks, const uint64_t* chunk_elems,
+                                                     uint32_t sample_stride,
+                                                     zipccl_table_t* d_tables, double* d_sigmas,
+                                                     void* d_workspace, size_t workspace_bytes, void* stream)
+{
+    return estimate_chunk_tables_impl(d_in, n_elems, dt, n_chunks, chunk_elems, sample_stride, d_tables, d_sigmas,
+                                      d_workspace, workspace_bytes, stream);
 }
 
 zipccl_status_t zipccl_estimate_table_robust(const void* d_in, size_t n_elems, zipccl_dtype_t dt,
@@ -389,6 +413,7 @@ zipccl_status_t zipccl_estimate_table_robust(const void* d_in, size_t n_elems, z
     for (uint32_t i = 1; i <= kMaxBatch; ++i) a.tab.elem_off[i] = whole;
     const uint64_t want = (whole + 65535) / 65536;                    /* about 64 values per thread at least */
     a.n_blocks = (uint32_t)(want < 1 ? 1 : (want > kHistBlocks ? kHistBlocks : want));
+    a.sample_stride = 1;
     a.in = static_cast<const uint8_t*>(d_in);
     a.hist = hist;
     a.table = reinterpret_cast<uint8_t*>(d_table);

@@ -96,6 +96,7 @@ struct HistArgs {
     const uint8_t* in;       /* first element of the launch's first chunk */
     unsigned long long* hist;   /* 32768 counts per chunk of the launch, zeroed by the first kernel of the call */
     uint32_t n_blocks;       /* workgroups per chunk */
+    uint32_t sample_stride;  /* 1: every value counts; a power of two S: one group of 512 values per S groups */
     uint8_t* table;          /* device zipccl_table_t (8 bytes) per chunk of the launch */
     double* sigma;           /* one per chunk of the launch; may be null */
     ChunkTab tab;            /* the launch's chunks (elem_off; the other fields are not used) */

@@ -228,3 +228,64 @@ def test_chunk_tables_match_oracle_and_follow_each_chunks_scale():
     _chunk_tables_case(many, z.BF16, np.full(300, 700, dtype=np.uint64), "300 chunks")
     tiny = np.array([0x3F80, 0x0000, 0x7F80, 0x4000, 0xC000, 0x0001, 0x4040], dtype=np.uint16)
     _chunk_tables_case(tiny, z.BF16, np.array([1, 2, 0, 4], dtype=np.uint64), "tiny chunks")
+
+
+def _sampled_case(x, dtype, ce, stride, label):
+    """Tables and sigmas from the sample of every chunk must be the oracle's, bit for bit (the estimate is a count)."""
+    C = len(ce)
+    n = int(x.size)
+    print(f"[sampled tables] {label}: n={n} chunks={C} stride={stride}", flush=True)
+    decs, sig = osg.robust_chunk_tables_sampled(x, dtype, C, [int(v) for v in ce], stride=stride)
+    d_in = to_device_words(x)
+    d_tabs = torch.full((8 * C,), 0xEE, dtype=torch.uint8, device=DEV)
+    d_sig = torch.zeros(C, dtype=torch.float64, device=DEV)
+    d_ews = torch.full((z.zipccl_estimate_chunk_tables_workspace_size(C),), 0x77, dtype=torch.uint8, device=DEV)
+    z.zipccl_estimate_chunk_tables_sampled(d_in, n, dtype, C, ce, stride, d_tabs, d_sig, d_ews)
+    torch.cuda.synchronize()
+    got_sig = d_sig.cpu().numpy()
+    assert np.array_equal(np.isnan(got_sig), np.isnan(sig)), (label, got_sig, sig)
+    assert np.array_equal(got_sig[~np.isnan(sig)], sig[~np.isnan(sig)]), (label, got_sig, sig)
+    assert np.array_equal(d_tabs.cpu().numpy().reshape(C, 8), decs), label
+
+
+def test_sampled_chunk_tables_match_oracle():
+    rng = np.random.default_rng(12)
+    # chunk lengths around the group and block sizes, odd lengths (chunk starts that are only element-aligned: read
+    # value by value), an empty chunk, a chunk shorter than one group, a last group cut short, a last block whose
+    # group lies past the end
+    ce = np.array([512 * 64 + 7, 0, 300, 512 * 16 * 5, 512 * 23 + 100, 512 * 23, 99_999, 8], dtype=np.uint64)
+    sig = [1e-3, 1.0, 5.0, 0.3, 0.02, 0.02, 2.0, 1.0]
+    for dtype in (z.BF16, z.FP32):
+        f = [rng.standard_normal(int(n), dtype=np.float32) * np.float32(s) for n, s in zip(ce, sig)]
+        x = np.concatenate([W.f32_to_bf16_words(v) if dtype == z.BF16 else v.view(np.uint32) for v in f])
+        for stride in (1, 2, 16, 64, 4096):
+            _sampled_case(x, dtype, ce, stride, f"ragged dtype={dtype}")
+    # one chunk, aligned: the vector path, several workgroups, four groups in flight per wave and a ragged end
+    for dtype, n in ((z.BF16, 512 * 16 * 700 + 512 * 5 + 33), (z.FP32, 512 * 16 * 300 + 17)):
+        f = rng.standard_normal(n, dtype=np.float32) * np.float32(0.02)
+        f[::997] = 0.0
+        f[5::4001] = np.inf
+        x = W.f32_to_bf16_words(f) if dtype == z.BF16 else f.view(np.uint32).copy()
+        for stride in (4, 16):
+            _sampled_case(x, dtype, np.array([n], dtype=np.uint64), stride, f"one chunk dtype={dtype}")
+    # more chunks than one launch holds
+    many = W.f32_to_bf16_words(rng.standard_normal(300 * 2048, dtype=np.float32))
+    _sampled_case(many, z.BF16, np.full(300, 2048, dtype=np.uint64), 2, "300 chunks")
+
+
+@pytest.mark.parametrize("name,scale", [("c2", 1 / 8), ("c3", 1 / 32), ("c4", 1 / 64), ("c5", 1 / 64), ("c5_fp32", 1 / 32)])
+def test_sampled_tables_on_workloads_are_the_full_estimates(name, scale):
+    """On the benchmark's workloads (outlier columns, gain rows, heavy tails, ragged chunks) a sample of one group
+    in 16 picks the window the whole tensor picks, per chunk and for the tensor as one chunk."""
+    w = W.make(name, scale)
+    ce = w.chunk_elems if w.chunk_elems is not None else np.full(w.n_chunks, w.n_elems // w.n_chunks, dtype=np.uint64)
+    _sampled_case(w.data, w.dtype, ce, 16, w.name)
+    _sampled_case(w.data, w.dtype, np.array([w.n_elems], dtype=np.uint64), 16, w.name + " as one chunk")
+    d_in = to_device_words(w.data)
+    d_tab = torch.zeros(8, dtype=torch.uint8, device=DEV)
+    d_full = torch.zeros(8, dtype=torch.uint8, device=DEV)
+    d_ews = torch.empty(z.zipccl_estimate_robust_workspace_size(), dtype=torch.uint8, device=DEV)
+    z.zipccl_estimate_chunk_tables_sampled(d_in, w.n_elems, w.dtype, 1, None, 16, d_tab, None, d_ews)
+    z.zipccl_estimate_table_robust(d_in, w.n_elems, w.dtype, d_full, None, d_ews)
+    torch.cuda.synchronize()
+    assert torch.equal(d_tab, d_full), w.name

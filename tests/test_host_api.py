@@ -117,4 +117,13 @@ def test_argument_errors_return_before_any_launch():
     assert decomp(comp_=A + 32) == 1
     assert decomp(out=A + 1) == 1
     assert decomp(ccap=128) == 3      # static part of the slot is not readable
+    def sampled(stride, d_in=A, n=1 << 20, dt=z.BF16, k=4, tables=A, ws_=A, wsb=z.zipccl_estimate_chunk_tables_workspace_size(4)):
+        return lib.zipccl_estimate_chunk_tables_sampled(d_in, n, dt, k, None, stride, tables, None, ws_, wsb, None)
+
+    for stride in (0, 3, 24, 8192, 1 << 31):              # a power of two from 1 to 4096 is asked for
+        assert sampled(stride) == 1, stride
+    assert sampled(16, dt=5) == 2
+    assert sampled(16, tables=None) == 1
+    assert sampled(16, k=3) == 1                          # 2^20 values do not split into 3 equal chunks
+    assert sampled(16, wsb=100) == 3
     assert z.zipccl_status_string(4) == "corrupt compressed data"
