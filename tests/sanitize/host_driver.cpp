@@ -36,6 +36,7 @@ int launch_clear_hist(unsigned long long* hist, uint32_t n_chunks, void*) { CHEC
 int launch_estimate_robust(int, const HistArgs& a, void*)
 {
     CHECK(a.n_blocks >= 1 && a.n_blocks <= kHistBlocks && a.tab.n_chunks >= 1 && a.tab.n_chunks <= kMaxBatch);
+    CHECK(a.sample_stride >= 1 && a.sample_stride <= ZIPCCL_MAX_SAMPLE_STRIDE && (a.sample_stride & (a.sample_stride - 1)) == 0);
     for (uint32_t c = 0; c < kMaxBatch; ++c) CHECK(a.tab.elem_off[c] <= a.tab.elem_off[c + 1]);
     ++g_launches;
     return 0;
@@ -127,6 +128,10 @@ int main()
     CHECK(zipccl_estimate_chunk_tables(in, n, ZIPCCL_FP32, C, ce.data(), (zipccl_table_t*)out, nullptr, ws, big, nullptr) == ZIPCCL_OK);
     CHECK(zipccl_estimate_chunk_tables(in, n, ZIPCCL_FP32, C, ce.data(), (zipccl_table_t*)out, nullptr, ws, 1000, nullptr) == ZIPCCL_ERR_BUFFER_TOO_SMALL);
     CHECK(zipccl_estimate_chunk_tables(in, n + 1, ZIPCCL_FP32, C, ce.data(), (zipccl_table_t*)out, nullptr, ws, big, nullptr) == ZIPCCL_ERR_INVALID_ARG);
+    for (uint32_t stride : {1u, 2u, 16u, 4096u})
+        CHECK(zipccl_estimate_chunk_tables_sampled(in, n, ZIPCCL_FP32, C, ce.data(), stride, (zipccl_table_t*)out, nullptr, ws, big, nullptr) == ZIPCCL_OK);
+    for (uint32_t stride : {0u, 3u, 48u, 8192u, 0x80000000u})
+        CHECK(zipccl_estimate_chunk_tables_sampled(in, n, ZIPCCL_FP32, C, ce.data(), stride, (zipccl_table_t*)out, nullptr, ws, big, nullptr) == ZIPCCL_ERR_INVALID_ARG);
     CHECK(zipccl_compress_chunk_tables(in, n, ZIPCCL_FP32, C, ce.data(), (const zipccl_table_t*)out, out, big, nullptr, ws, big, nullptr) == ZIPCCL_OK);
     CHECK(zipccl_compress_chunk_tables(in, n, ZIPCCL_FP32, C, ce.data(), nullptr, out, big, nullptr, ws, big, nullptr) == ZIPCCL_ERR_INVALID_ARG);
     CHECK(g_launches > 0);
