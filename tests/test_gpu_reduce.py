@@ -253,9 +253,10 @@ def test_estimate_compress_reduce_chain_replays_inside_a_hip_graph():
         assert np.array_equal(d_sum.cpu().numpy().view(np.uint32), want), rep
 
 
-def test_chunk_table_estimate_and_compress_chain_replays_inside_a_hip_graph():
-    """Per-chunk robust tables -> compress with them -> fused reduce, captured and replayed: the histogram state is
-    zeroed by a kernel of the chain itself, so every replay starts clean."""
+@pytest.mark.parametrize("stride", [1, 4], ids=["every_value", "sampled"])
+def test_chunk_table_estimate_and_compress_chain_replays_inside_a_hip_graph(stride):
+    """Per-chunk robust tables (from every value, or from a sample) -> compress with them -> fused reduce, captured
+    and replayed: the histogram state is zeroed by a kernel of the chain itself, so every replay starts clean."""
     from oracle import sigma as osg
     P, n = 3, 4 * 8192 + 77
     d_in = torch.zeros(P * n, dtype=torch.int16, device=DEV)
@@ -268,7 +269,10 @@ def test_chunk_table_estimate_and_compress_chain_replays_inside_a_hip_graph():
     d_st = torch.zeros(1, dtype=torch.int32, device=DEV)
 
     def chain():
-        z.zipccl_estimate_chunk_tables(d_in, P * n, z.BF16, P, None, d_tabs, None, d_ews)
+        if stride == 1:
+            z.zipccl_estimate_chunk_tables(d_in, P * n, z.BF16, P, None, d_tabs, None, d_ews)
+        else:
+            z.zipccl_estimate_chunk_tables_sampled(d_in, P * n, z.BF16, P, None, stride, d_tabs, None, d_ews)
         z.zipccl_compress_chunk_tables(d_in, P * n, z.BF16, P, None, d_tabs, d_comp, None, d_ws)
         z.zipccl_decompress_reduce(d_comp, d_sum, n, z.BF16, P, z.FP32, d_st)
 
@@ -291,7 +295,7 @@ def test_chunk_table_estimate_and_compress_chain_replays_inside_a_hip_graph():
         torch.cuda.synchronize()
         g.replay()
         torch.cuda.synchronize()
-        decs, _ = osg.robust_chunk_tables(data, z.BF16, P)
+        decs, _ = osg.robust_chunk_tables_sampled(data, z.BF16, P, stride=stride)
         assert np.array_equal(d_tabs.cpu().numpy().reshape(P, 8), decs), rep
         slots = [oracle.compress(data[p * n:(p + 1) * n], z.BF16, decs[p])[0] for p in range(P)]
         want = oracle.decompress_reduce(np.concatenate(slots), n, z.BF16, P, z.FP32)
