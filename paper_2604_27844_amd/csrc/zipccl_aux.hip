@@ -194,30 +194,20 @@ __global__ __launch_bounds__(kHistThreads) void k_magnitude_hist(const HistArgs 
  * groups (S = a.sample_stride, a power of two) and one group is taken from every block, at position
  * ((k * 2654435761 mod 2^32) >> 16) mod S inside block k (Knuth's multiplicative hash: the position varies from
  * block to block, so the sample does not alias with the periods of the tensor itself, rows of 8 or 16 groups
- * say).  A wave takes a group at a time, 8 values per lane, four groups in flight; a group that is cut short by
+ * say).  A wave takes a group at a time, 8 values per lane, several groups in flight; a group that is cut short by
  * the chunk's end, and every group of a chunk that does not start on a 16-byte boundary, is read value by value.
  */
-template <int DT>
-__global__ __launch_bounds__(kHistThreads) void k_magnitude_hist_sampled(const HistArgs a)
+template <int DT, uint32_t NF>   /* NF groups in flight per wave */
+__device__ __forceinline__ void sample_into_lds(uint32_t* s_hist, const uint8_t* __restrict__ in, uint64_t n, uint32_t S,
+                                                uint32_t first_wave, uint32_t n_waves)
 {
     constexpr uint32_t ES = DT == ZIPCCL_BF16 ? 2u : 4u;
     constexpr uint32_t NV = DT == ZIPCCL_BF16 ? 1u : 2u;    /* 16-byte pieces per lane and group */
-    constexpr uint32_t NF = 4;                              /* groups in flight per wave */
-    __shared__ uint32_t s_hist[kMagBins];                  /* 128 KiB */
-    for (uint32_t i = threadIdx.x; i < kMagBins; i += kHistThreads) s_hist[i] = 0u;
-    __syncthreads();
-    /* grid = (workgroups per chunk, chunks) */
-    const uint32_t c = blockIdx.y;
-    const uint8_t* __restrict__ in = a.in + a.tab.elem_off[c] * ES;
-    const uint64_t n = a.tab.elem_off[c + 1] - a.tab.elem_off[c];
-    const uint32_t S = a.sample_stride;
     const uint64_t ng = (n + kGroup - 1) / kGroup;           /* at most 2^23 */
     const uint32_t n_blk = (uint32_t)((ng + S - 1) / S);
     const bool vec = (reinterpret_cast<uintptr_t>(in) & 15u) == 0;
     const uint32_t lane = threadIdx.x & 63u;
-    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const uint32_t n_waves = gridDim.x * (kHistThreads / 64u);
-    for (uint32_t k0 = blockIdx.x * (kHistThreads / 64u) + wave; k0 < n_blk; k0 += NF * n_waves) {
+    for (uint32_t k0 = first_wave; k0 < n_blk; k0 += NF * n_waves) {
         u32x4 v[NF][NV];
         uint64_t first[NF];
         bool some[NF], whole[NF];
@@ -258,12 +248,81 @@ __global__ __launch_bounds__(kHistThreads) void k_magnitude_hist_sampled(const H
             }
         }
     }
+}
+
+template <int DT>
+__global__ __launch_bounds__(kHistThreads) void k_magnitude_hist_sampled(const HistArgs a)
+{
+    constexpr uint32_t ES = DT == ZIPCCL_BF16 ? 2u : 4u;
+    __shared__ uint32_t s_hist[kMagBins];                  /* 128 KiB */
+    for (uint32_t i = threadIdx.x; i < kMagBins; i += kHistThreads) s_hist[i] = 0u;
+    __syncthreads();
+    /* grid = (workgroups per chunk, chunks) */
+    const uint32_t c = blockIdx.y;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    sample_into_lds<DT, 4>(s_hist, a.in + a.tab.elem_off[c] * ES, a.tab.elem_off[c + 1] - a.tab.elem_off[c], a.sample_stride,
+                           blockIdx.x * (kHistThreads / 64u) + wave, gridDim.x * (kHistThreads / 64u));
     __syncthreads();
     unsigned long long* __restrict__ hist = a.hist + (uint64_t)c * kMagBins;
     for (uint32_t b = threadIdx.x; b < kMagBins; b += kHistThreads) {
         const uint32_t cnt = s_hist[b];
         if (cnt) atomicAdd(&hist[b], (unsigned long long)cnt);
     }
+}
+
+/*
+ * A chunk whose sample is small enough for one workgroup (at most kFusedGroups groups): histogram, rank and table
+ * in one kernel, nothing outside LDS, no histogram in the workspace to clear and no second or third launch.
+ * grid = chunks.  Thread t answers for bins [32 t, 32 t + 32) as in k_robust_finish; a chunk holds fewer than 2^32
+ * values, so 32-bit counts do.
+ */
+template <int DT>
+__global__ __launch_bounds__(kHistThreads) void k_robust_chunk_fused(const HistArgs a)
+{
+    constexpr uint32_t ES = DT == ZIPCCL_BF16 ? 2u : 4u;
+    constexpr uint32_t kPer = kMagBins / kHistThreads;       /* 32 */
+    constexpr uint32_t kWaves = kHistThreads / 64;
+    constexpr uint32_t kFirstNonFinite = 0x7F80u;
+    __shared__ uint32_t s_hist[kMagBins];                  /* 128 KiB */
+    __shared__ uint32_t s_wave[kWaves];
+    for (uint32_t i = threadIdx.x; i < kMagBins; i += kHistThreads) s_hist[i] = 0u;
+    __syncthreads();
+    const uint32_t c = blockIdx.x;
+    const uint32_t t = threadIdx.x, lane = t & 63u;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(t >> 6);
+    /* one workgroup per chunk has the chunk's whole latency to hide: eight groups in flight per wave */
+    sample_into_lds<DT, 8>(s_hist, a.in + a.tab.elem_off[c] * ES, a.tab.elem_off[c + 1] - a.tab.elem_off[c], a.sample_stride,
+                           wave, kWaves);
+    __syncthreads();
+    uint8_t* const table = a.table + 8u * c;
+    double* const sigma = a.sigma ? a.sigma + c : nullptr;
+    auto counted = [&](uint32_t b) { return (b != 0u && b < kFirstNonFinite) ? s_hist[b] : 0u; };
+    uint32_t mine = 0;
+#pragma unroll
+    for (uint32_t k = 0; k < kPer; ++k) mine += counted(t * kPer + ((k + t) & (kPer - 1u)));   /* rotated: no bank conflicts */
+    const uint32_t inc = wave_incl_scan(mine);
+    if (lane == 63u) s_wave[wave] = inc;
+    __syncthreads();
+    uint32_t before = 0, total = 0;
+    for (uint32_t w = 0; w < kWaves; ++w) {
+        const uint32_t cw = s_wave[w];
+        before += w < wave ? cw : 0u;
+        total += cw;
+    }
+    if (total == 0u) {
+        if (t == 0) table_from_sigma(__longlong_as_double(0x7FF8000000000000ll), table, sigma);
+        return;
+    }
+    const uint32_t rank = (total - 1u) / 2u, excl = before + inc - mine;
+    if (rank < excl || rank - excl >= mine) return;          /* exactly one thread holds the rank */
+    uint32_t run = excl, bin = 0;
+    bool found = false;
+    for (uint32_t k = 0; k < kPer; ++k) {
+        run += counted(t * kPer + k);
+        if (!found && rank < run) { found = true; bin = t * kPer + k; }
+    }
+    const double med = (double)__uint_as_float(bin << 16);
+    table_from_sigma(med / 0.6744897501960817, table, sigma);     /* Phi^-1(3/4) */
 }
 
 /* Inclusive prefix sum of 64-bit values over the 64 lanes of a wave, exact, without going through LDS: the four
@@ -368,6 +427,14 @@ int launch_estimate(int dt, const MomentArgs& a, void* stream)
 int launch_clear_hist(unsigned long long* hist, uint32_t n_chunks, void* stream)
 {
     hipLaunchKernelGGL(k_clear_hist, dim3(n_chunks * (kMagBins * 8u / (16u * kClearPer * kClearThreads))), dim3(kClearThreads), 0, (hipStream_t)stream, hist);
+    return (int)hipGetLastError();
+}
+
+int launch_estimate_robust_fused(int dt, const HistArgs& a, void* stream)
+{
+    const dim3 grid(a.tab.n_chunks);
+    if (dt == ZIPCCL_BF16) hipLaunchKernelGGL((k_robust_chunk_fused<ZIPCCL_BF16>), grid, dim3(kHistThreads), 0, (hipStream_t)stream, a);
+    else hipLaunchKernelGGL((k_robust_chunk_fused<ZIPCCL_FP32>), grid, dim3(kHistThreads), 0, (hipStream_t)stream, a);
     return (int)hipGetLastError();
 }
 

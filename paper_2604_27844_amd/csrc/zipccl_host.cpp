@@ -347,7 +347,12 @@ static zipccl_status_t estimate_chunk_tables_impl(const void* d_in, size_t n_ele
     if (workspace_bytes < zipccl_estimate_chunk_tables_workspace_size(n_chunks)) return ZIPCCL_ERR_BUFFER_TOO_SMALL;
     if ((uint64_t)n_chunks * (32768 / 1024) > 0x7FFFFFFFull) return ZIPCCL_ERR_INVALID_ARG;
     unsigned long long* const hist = static_cast<unsigned long long*>(d_workspace);
-    if (launch_clear_hist(hist, n_chunks, stream) != 0) return ZIPCCL_ERR_DEVICE;
+    /* when every chunk's sample is small enough for one workgroup, one kernel does it all inside LDS: no histogram
+       in the workspace, nothing to clear */
+    uint64_t largest_of_all = 0;
+    for (uint32_t c = 0; c < n_chunks; ++c) largest_of_all = std::max(largest_of_all, ce[c]);
+    const bool fused = ((largest_of_all + kGroup - 1) / kGroup + sample_stride - 1) / sample_stride <= kFusedGroups;
+    if (!fused && launch_clear_hist(hist, n_chunks, stream) != 0) return ZIPCCL_ERR_DEVICE;
     const std::vector<uint64_t> no_slots(n_chunks + 1, 0);            /* slot offsets play no part here */
     HistArgs a;
     uint64_t elem_base = 0;
@@ -356,6 +361,17 @@ static zipccl_status_t estimate_chunk_tables_impl(const void* d_in, size_t n_ele
         fill_tab(a.tab, ce, no_slots, c0, nb);
         uint64_t largest = 0;
         for (uint32_t c = 0; c < nb; ++c) largest = std::max(largest, ce[c0 + c]);
+        if (fused) {
+            a.n_blocks = 1;
+            a.sample_stride = sample_stride;
+            a.in = static_cast<const uint8_t*>(d_in) + elem_base * elem_size(dt);
+            a.hist = hist;
+            a.table = reinterpret_cast<uint8_t*>(d_tables + c0);
+            a.sigma = d_sigmas ? d_sigmas + c0 : nullptr;
+            if (launch_estimate_robust_fused(dt, a, stream) != 0) return ZIPCCL_ERR_DEVICE;
+            elem_base += a.tab.elem_off[nb];
+            continue;
+        }
         /* a workgroup counts in 32 bits, and wants about 64 values per thread at least (of a sample: four groups
            per wave); about one workgroup per compute unit in all */
         const uint64_t sampled = (largest + sample_stride - 1) / sample_stride;

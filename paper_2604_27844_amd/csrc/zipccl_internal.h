@@ -28,6 +28,7 @@ constexpr uint32_t kVersion = 1;
 constexpr uint32_t kMagic = 0x4C43505Au;            /* "ZPCL" little-endian */
 constexpr uint32_t kWorkspaceHeader = 256;          /* reserved bytes before the per-tile arrays */
 constexpr uint32_t kMaxPeers = 1024;                /* slots one zipccl_decompress_reduce call can sum */
+constexpr uint32_t kFusedGroups = 512;              /* sampled groups of a chunk that one workgroup takes on its own */
 constexpr uint32_t kStashSlack = 64;                /* readable bytes past the last stash byte */
 
 /* header words (u32 index): 0 magic, 1 version, 2 dtype, 3 G, 4-5 n, 6-7 n_esc, 8-9 chunk_bytes, 10-11 dec[8] */
@@ -134,6 +135,7 @@ enum CompressMode { kModeCount = 0, kModeEmit = 1, kModeStash = 2 };
 int launch_estimate(int dt, const MomentArgs& a, void* stream);
 int launch_clear_hist(unsigned long long* hist, uint32_t n_chunks, void* stream);
 int launch_estimate_robust(int dt, const HistArgs& a, void* stream);
+int launch_estimate_robust_fused(int dt, const HistArgs& a, void* stream);   /* chunks of at most kFusedGroups sampled groups */
 int launch_compress(int dt, int mode, const CompressArgs& a, void* stream);
 /* device address and size of the library's own workspace on the current GPU (zipccl_compress_static) */
 int static_scratch(void** ptr, size_t* bytes);

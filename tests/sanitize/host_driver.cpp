@@ -41,6 +41,12 @@ int launch_estimate_robust(int, const HistArgs& a, void*)
     ++g_launches;
     return 0;
 }
+int launch_estimate_robust_fused(int dt, const HistArgs& a, void* s)
+{
+    for (uint32_t c = 0; c < a.tab.n_chunks; ++c)           /* one workgroup per chunk: its sample must be small */
+        CHECK(((a.tab.elem_off[c + 1] - a.tab.elem_off[c] + kGroup - 1) / kGroup + a.sample_stride - 1) / a.sample_stride <= kFusedGroups);
+    return launch_estimate_robust(dt, a, s);
+}
 int launch_compress(int, int, const CompressArgs& a, void*) { check_tab(a.tab); ++g_launches; return 0; }
 int launch_tile_scan(const CompressArgs& a, void*) { check_tab(a.tab); ++g_launches; return 0; }
 int launch_place(int, bool, const CompressArgs& a, void*) { check_tab(a.tab); ++g_launches; return 0; }

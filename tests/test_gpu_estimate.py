@@ -228,6 +228,12 @@ def test_chunk_tables_match_oracle_and_follow_each_chunks_scale():
     _chunk_tables_case(many, z.BF16, np.full(300, 700, dtype=np.uint64), "300 chunks")
     tiny = np.array([0x3F80, 0x0000, 0x7F80, 0x4000, 0xC000, 0x0001, 0x4040], dtype=np.uint16)
     _chunk_tables_case(tiny, z.BF16, np.array([1, 2, 0, 4], dtype=np.uint64), "tiny chunks")
+    # chunks of more than 512 groups: histograms in the workspace, several workgroups per chunk, a finish kernel
+    # (smaller chunks are taken by one workgroup each, in one kernel)
+    ce_big = np.array([700_001, 0, 1024 * 512 + 1, 1024 * 512, 40_000], dtype=np.uint64)
+    sig_big = [0.02, 1.0, 3.0, 1e-3, 0.5]
+    big = np.concatenate([W.f32_to_bf16_words(rng.standard_normal(int(n), dtype=np.float32) * np.float32(s)) for n, s in zip(ce_big, sig_big)])
+    _chunk_tables_case(big, z.BF16, ce_big, "chunks past one workgroup's share")
 
 
 def _sampled_case(x, dtype, ce, stride, label):
