@@ -277,6 +277,11 @@ def test_sampled_chunk_tables_match_oracle():
     # more chunks than one launch holds
     many = W.f32_to_bf16_words(rng.standard_normal(300 * 2048, dtype=np.float32))
     _sampled_case(many, z.BF16, np.full(300, 2048, dtype=np.uint64), 2, "300 chunks")
+    # either side of the size up to which one workgroup takes a chunk's sample on its own (512 sampled groups)
+    edge = W.f32_to_bf16_words(rng.standard_normal(4 * 512 * 512 + 600, dtype=np.float32) * np.float32(0.3))
+    for n in (512 * 512, 512 * 512 + 1):
+        _sampled_case(edge[:n], z.BF16, np.array([n], dtype=np.uint64), 1, f"one chunk of {n} values")
+        _sampled_case(edge[:4 * n], z.BF16, np.array([4 * n], dtype=np.uint64), 4, f"one chunk of {4 * n} values")
 
 
 @pytest.mark.parametrize("name,scale", [("c2", 1 / 8), ("c3", 1 / 32), ("c4", 1 / 64), ("c5", 1 / 64), ("c5_fp32", 1 / 32)])
