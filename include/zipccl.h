@@ -50,6 +50,7 @@ extern "C" {
 #define ZIPCCL_ALIGN 128u        /* alignment of every slot and section */
 #define ZIPCCL_MAX_CHUNK_ELEMS 0xFFFFFFFFull /* IDX entries are u32 */
 #define ZIPCCL_STATIC_SCRATCH_BYTES (32u << 20) /* the library's own workspace, per GPU: zipccl_compress_static */
+#define ZIPCCL_MAX_SAMPLE_STRIDE 4096u /* largest sample_stride of zipccl_estimate_chunk_tables_sampled */
 
 typedef enum { ZIPCCL_BF16 = 0, ZIPCCL_FP32 = 1 } zipccl_dtype_t;
 
@@ -222,7 +223,6 @@ zipccl_status_t zipccl_estimate_chunk_tables(const void* d_in, size_t n_elems, z
  * Everything else, the workspace included, as for zipccl_estimate_chunk_tables (n_chunks = 1 for one table
  * for the whole tensor, of up to ZIPCCL_MAX_CHUNK_ELEMS values).
  */
-#define ZIPCCL_MAX_SAMPLE_STRIDE 4096u
 zipccl_status_t zipccl_estimate_chunk_tables_sampled(const void* d_in, size_t n_elems, zipccl_dtype_t dt,
                                                      uint32_t n_chunks, const uint64_t* chunk_elems,
                                                      uint32_t sample_stride,
