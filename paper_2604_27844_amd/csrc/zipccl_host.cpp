@@ -422,7 +422,6 @@ zipccl_status_t zipccl_estimate_table_robust(const void* d_in, size_t n_elems, z
         return ZIPCCL_ERR_INVALID_ARG;
     if (workspace_bytes < zipccl_estimate_robust_workspace_size()) return ZIPCCL_ERR_BUFFER_TOO_SMALL;
     unsigned long long* const hist = static_cast<unsigned long long*>(d_workspace);
-    if (launch_clear_hist(hist, 1, stream) != 0) return ZIPCCL_ERR_DEVICE;
     HistArgs a;
     std::memset(&a.tab, 0, sizeof a.tab);
     a.tab.n_chunks = 1;
@@ -434,6 +433,10 @@ zipccl_status_t zipccl_estimate_table_robust(const void* d_in, size_t n_elems, z
     a.hist = hist;
     a.table = reinterpret_cast<uint8_t*>(d_table);
     a.sigma = d_sigma;
+    /* a tensor one workgroup can take on its own: one kernel, nothing to clear */
+    if ((whole + kGroup - 1) / kGroup <= kFusedGroups)
+        return launch_estimate_robust_fused(dt, a, stream) == 0 ? ZIPCCL_OK : ZIPCCL_ERR_DEVICE;
+    if (launch_clear_hist(hist, 1, stream) != 0) return ZIPCCL_ERR_DEVICE;
     return launch_estimate_robust(dt, a, stream) == 0 ? ZIPCCL_OK : ZIPCCL_ERR_DEVICE;
 }
 
