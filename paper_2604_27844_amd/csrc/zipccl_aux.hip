@@ -205,12 +205,26 @@ __device__ __forceinline__ void sample_into_lds(uint32_t* s_hist, const uint8_t*
     constexpr uint32_t NV = DT == ZIPCCL_BF16 ? 1u : 2u;    /* 16-byte pieces per lane and group */
     const uint64_t ng = (n + kGroup - 1) / kGroup;           /* at most 2^23 */
     const uint32_t n_blk = (uint32_t)((ng + S - 1) / S);
-    const bool vec = (reinterpret_cast<uintptr_t>(in) & 15u) == 0;
+    /* vector loads need a chunk that starts on a 16-byte boundary; then group 0, if whole, is an address that is
+       always safe to load from */
+    const bool vec = (reinterpret_cast<uintptr_t>(in) & 15u) == 0 && n >= kGroup;
     const uint32_t lane = threadIdx.x & 63u;
+    auto one_by_one = [&](uint64_t first) {
+        for (uint32_t j = 0; j < kLaneElems; ++j) {
+            const uint64_t e = first + lane * kLaneElems + j;
+            if (e < n) {
+                const uint32_t hi = DT == ZIPCCL_BF16 ? *reinterpret_cast<const uint16_t*>(in + e * 2)
+                                                      : *reinterpret_cast<const uint32_t*>(in + e * 4) >> 16;
+                atomicAdd(&s_hist[hi & 0x7FFFu], 1u);
+            }
+        }
+    };
     for (uint32_t k0 = first_wave; k0 < n_blk; k0 += NF * n_waves) {
         u32x4 v[NF][NV];
         uint64_t first[NF];
         bool some[NF], whole[NF];
+        /* the loads of all NF groups go out back to back: no branch between them (a group that is not there, or
+           not whole, loads group 0 instead and is not counted from it) */
 #pragma unroll
         for (uint32_t u = 0; u < NF; ++u) {
             const uint32_t k = k0 + u * n_waves;
@@ -218,10 +232,14 @@ __device__ __forceinline__ void sample_into_lds(uint32_t* s_hist, const uint8_t*
             first[u] = g * kGroup;
             some[u] = k < n_blk && g < ng;
             whole[u] = some[u] && vec && first[u] + kGroup <= n;
-            if (whole[u]) {
+        }
+        if (vec) {
+#pragma unroll
+            for (uint32_t u = 0; u < NF; ++u) {
+                const uint64_t from = whole[u] ? first[u] : 0ull;
 #pragma unroll
                 for (uint32_t q = 0; q < NV; ++q)
-                    v[u][q] = ld_stream<u32x4>(in + (first[u] + lane * kLaneElems) * ES + 16u * q);
+                    v[u][q] = ld_stream<u32x4>(in + (from + lane * kLaneElems) * ES + 16u * q);
             }
         }
 #pragma unroll
@@ -236,17 +254,12 @@ __device__ __forceinline__ void sample_into_lds(uint32_t* s_hist, const uint8_t*
                         atomicAdd(&s_hist[(w[j] >> 16) & 0x7FFFu], 1u);
                     }
                 }
-            } else if (some[u]) {
-                for (uint32_t j = 0; j < kLaneElems; ++j) {
-                    const uint64_t e = first[u] + lane * kLaneElems + j;
-                    if (e < n) {
-                        const uint32_t hi = DT == ZIPCCL_BF16 ? *reinterpret_cast<const uint16_t*>(in + e * 2)
-                                                              : *reinterpret_cast<const uint32_t*>(in + e * 4) >> 16;
-                        atomicAdd(&s_hist[hi & 0x7FFFu], 1u);
-                    }
-                }
             }
         }
+        /* a group cut short by the chunk's end, or any group of a chunk that is only element-aligned */
+#pragma unroll
+        for (uint32_t u = 0; u < NF; ++u)
+            if (some[u] && !whole[u]) one_by_one(first[u]);
     }
 }
 
