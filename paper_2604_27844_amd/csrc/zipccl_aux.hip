@@ -126,11 +126,13 @@ __global__ __launch_bounds__(kThreads) void k_estimate_finish(const MomentArgs a
 constexpr uint32_t kMagBins = 32768;
 constexpr uint32_t kHistThreads = 1024;
 
-constexpr uint32_t kClearThreads = 256, kClearPer = 4;   /* 16-byte stores per thread */
+/* One workgroup per chunk's histogram, 64 stores per thread: with the same bytes spread over 16 or 32 times as many
+ * workgroups the kernel took 5 us longer for 64 histograms (the launch, not the memory, was its limit). */
+constexpr uint32_t kClearThreads = 256, kClearPer = 64;  /* 16-byte stores per thread */
 
 __global__ __launch_bounds__(kClearThreads) void k_clear_hist(unsigned long long* hist)
 {
-    /* grid = 16 workgroups per chunk (the workspace is 8-byte aligned: the 16-byte stores are issued at that alignment) */
+    /* grid = chunks (the workspace is 8-byte aligned: the 16-byte stores are issued at that alignment) */
     u32x4_a4* const p = reinterpret_cast<u32x4_a4*>(hist) + (uint64_t)blockIdx.x * (kClearPer * kClearThreads) + threadIdx.x;
     const u32x4 zero = {0u, 0u, 0u, 0u};
 #pragma unroll
