@@ -300,3 +300,37 @@ def test_sampled_tables_on_workloads_are_the_full_estimates(name, scale):
     z.zipccl_estimate_table_robust(d_in, w.n_elems, w.dtype, d_full, None, d_ews)
     torch.cuda.synchronize()
     assert torch.equal(d_tab, d_full), w.name
+
+
+def test_sampled_estimate_seeded_fuzz():
+    """Random splits (empty, tiny, around the group, block and one-workgroup sizes), strides, scales, zeros and
+    infinities, both dtypes, inputs that are only element-aligned: tables and sigmas bit-equal to the oracle's."""
+    rng = np.random.default_rng(77)
+    sizes = [0, 1, 7, 511, 512, 513, 1000, 4096, 8191, 8193, 40000, 100003, 262144, 262145, 300001, 1_000_003]
+    for case in range(80):
+        dtype = int(rng.integers(0, 2))
+        C = int(rng.integers(1, 7))
+        ce = rng.choice(sizes, size=C).astype(np.uint64)
+        n = int(ce.sum())
+        stride = int(2 ** rng.integers(0, 13))
+        f = np.concatenate([rng.standard_normal(int(k), dtype=np.float32) * np.float32(np.exp(rng.uniform(-12, 6))) for k in ce])
+        if n and rng.integers(0, 3) == 0:
+            f[rng.integers(0, n, max(1, n // 20))] = 0.0
+        if n and rng.integers(0, 4) == 0:
+            f[rng.integers(0, n, max(1, n // 100))] = np.inf
+        x = W.f32_to_bf16_words(f) if dtype == z.BF16 else f.view(np.uint32).copy()
+        off = int(rng.integers(0, 2))
+        print(f"[sampled fuzz {case}] dtype={dtype} chunks={[int(v) for v in ce]} stride={stride} offset={off}", flush=True)
+        decs, sig = osg.robust_chunk_tables_sampled(x, dtype, C, [int(v) for v in ce], stride=stride)
+        d_all = torch.zeros(n + 1, dtype=torch.int16 if dtype == z.BF16 else torch.int32, device=DEV)
+        if n:
+            d_all[off:off + n] = to_device_words(x)
+        d_in = d_all[off:off + max(n, 1)]
+        d_tabs = torch.full((8 * C,), 0xEE, dtype=torch.uint8, device=DEV)
+        d_sig = torch.zeros(C, dtype=torch.float64, device=DEV)
+        d_ews = torch.full((z.zipccl_estimate_chunk_tables_workspace_size(C),), 0x77, dtype=torch.uint8, device=DEV)
+        z.zipccl_estimate_chunk_tables_sampled(d_in, n, dtype, C, ce, stride, d_tabs, d_sig, d_ews)
+        torch.cuda.synchronize()
+        got = d_sig.cpu().numpy()
+        assert np.array_equal(np.isnan(got), np.isnan(sig)) and np.array_equal(got[~np.isnan(sig)], sig[~np.isnan(sig)]), case
+        assert np.array_equal(d_tabs.cpu().numpy().reshape(C, 8), decs), case
